@@ -1,0 +1,1 @@
+"""Plain CPU oracle (test infrastructure; never imported by the product path)."""

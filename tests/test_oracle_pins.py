@@ -1,0 +1,411 @@
+"""Pins for the CPU oracle: each check ties one oracle function to something other than itself
+(exact rational arithmetic, brute force, closed forms and special cases stated in the paper)."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import retrieval_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers
+def rand_bf16_bits(rng, shape, scale=1.0):
+    """Random bf16 bit patterns (uint16): fp32 normals truncated to their upper 16 bits."""
+    x = (rng.standard_normal(shape) * scale).astype(np.float32)
+    return (x.view(np.uint32) >> 16).astype(np.uint16)
+
+
+def bf16_fraction(bits: int) -> Fraction:
+    """Decode one bf16 bit pattern by hand (sign, 8-bit exponent, 7-bit mantissa) to an exact rational."""
+    sign = -1 if bits >> 15 else 1
+    e = (bits >> 7) & 0xFF
+    m = bits & 0x7F
+    assert e != 0xFF
+    if e == 0:
+        return sign * Fraction(m, 1 << 7) * Fraction(1, 1 << 126)
+    return sign * (1 + Fraction(m, 1 << 7)) * (Fraction(2) ** (e - 127))
+
+
+def unit_rows(x):
+    return x / np.linalg.norm(x, axis=-1, keepdims=True)
+
+
+def small_model(rng, N=40, k_u=2, k_x=3, d=8, H=5, d_gu=4, d_gx=3, scale=1.0, act="relu", bias=True):
+    P = k_u * k_x
+    G = rand_bf16_bits(rng, (N, k_x, d), 0.5)
+    gx = rand_bf16_bits(rng, (N, d_gx), 0.5)
+    W1 = rand_bf16_bits(rng, (H, P + d_gu + d_gx), 0.7)
+    W2 = rand_bf16_bits(rng, (P, H), 0.7)
+    b1 = (rng.standard_normal(H) * 0.3).astype(np.float32) if bias else None
+    b2 = (rng.standard_normal(P) * 0.3).astype(np.float32) if bias else None
+    model = orc.MolModel(G, gx, W1, b1, W2, b2, logit_scale=scale, act=act)
+    F = rand_bf16_bits(rng, (3, k_u, d), 0.5)
+    gu = rand_bf16_bits(rng, (3, d_gu), 0.5)
+    return model, F, gu
+
+
+# ----------------------------------------------------------------------------- decoding + dot product
+def test_bf16_decode_matches_hand_decoding():
+    rng = np.random.default_rng(0)
+    bits = rand_bf16_bits(rng, (200,), 3.0)
+    bits[:4] = [0x0000, 0x8000, 0x3F80, 0x0001]          # +0, -0, 1.0, smallest subnormal
+    got = orc.bf16_bits_to_f64(bits)
+    for b, g in zip(bits.tolist(), got.tolist()):
+        assert Fraction(g) == bf16_fraction(b)
+
+
+def test_stage1_scores_exact_rational():
+    """Products of bf16 values and their 16-term sums are exactly representable in fp64 here,
+    so the oracle's dot product must equal exact rational arithmetic."""
+    rng = np.random.default_rng(1)
+    Q = rand_bf16_bits(rng, (3, 16))
+    X = rand_bf16_bits(rng, (7, 16))
+    s = orc.stage1_scores(Q, X)
+    assert s.shape == (3, 7)
+    for b in range(3):
+        for n in range(7):
+            exact = sum(bf16_fraction(int(Q[b, j])) * bf16_fraction(int(X[n, j])) for j in range(16))
+            assert abs(Fraction(s[b, n]) - exact) <= abs(exact) * Fraction(1, 10**14)
+
+
+def test_stage1_scores_orientation_fp32():
+    Q = np.array([[1, 0, 0], [0, 2, 0]], dtype=np.float32)
+    X = np.array([[3, 5, 7], [11, 13, 17], [19, 23, 29], [1, 1, 1]], dtype=np.float32)
+    s = orc.stage1_scores(Q, X)
+    assert s.tolist() == [[3, 11, 19, 1], [10, 26, 46, 2]]
+
+
+# ----------------------------------------------------------------------------- ordering / top-k
+def brute_topk(scores, ids, k):
+    """Repeated arg-max with removal; ties broken by the smaller id."""
+    pool = list(zip(scores, ids))
+    out = []
+    for _ in range(min(k, len(pool))):
+        best = 0
+        for i in range(1, len(pool)):
+            if pool[i][0] > pool[best][0] or (pool[i][0] == pool[best][0] and pool[i][1] < pool[best][1]):
+                best = i
+        out.append(pool.pop(best))
+    return [i for _, i in out], [s for s, _ in out]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_topk_matches_brute_force_with_ties(seed):
+    rng = np.random.default_rng(seed)
+    scores = rng.integers(0, 12, size=300).astype(np.float64) / 4.0       # many exact ties
+    ids = rng.permutation(1000)[:300]
+    for k in (1, 7, 100, 300, 400):
+        gi, gs = orc.topk_desc(scores, k, ids)
+        bi, bs = brute_topk(scores.tolist(), ids.tolist(), k)
+        assert gi.tolist() == bi and gs.tolist() == bs
+
+
+def test_nth_largest_is_one_based_from_the_top():
+    v = np.array([5.0, 1.0, 9.0, 7.0, 7.0])
+    assert orc.nth_largest(v, 1) == 9.0
+    assert orc.nth_largest(v, 2) == 7.0
+    assert orc.nth_largest(v, 3) == 7.0
+    assert orc.nth_largest(v, 5) == 1.0
+    with pytest.raises(ValueError):
+        orc.nth_largest(v, 0)
+
+
+# ----------------------------------------------------------------------------- sampler
+def test_splitmix64_published_vector():
+    want = [int(line) for line in open(os.path.join(GOLDEN, "splitmix64_seed1234567.txt")) if line[0].isdigit()]
+    state, got = 1234567, []
+    for _ in want:
+        state = (state + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+        got.append(orc.splitmix64(state))
+    assert got == want
+
+
+def test_sample_indices_vectorised_equals_scalar_and_is_uniform():
+    N, lam, seed = 1000, 20000, 77
+    got = orc.sample_indices(seed, lam, N)
+    state = seed
+    for i in range(50):
+        state = (state + 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+        assert got[i] == ((orc.splitmix64(state) >> 32) * N) >> 32
+    assert got.min() >= 0 and got.max() < N
+    counts = np.bincount(got, minlength=N)
+    # mean 20 per bin, std ~4.5: a broken mapping (e.g. only low indices) fails this by far
+    assert counts.min() > 0 and counts.max() < 60
+    assert abs(got.mean() - (N - 1) / 2) < 10
+
+
+def test_threshold_rank():
+    assert orc.threshold_rank(100_000, 1_000_000, 100_000_000) == 1000
+    assert orc.threshold_rank(10, 10, 1000) == 1            # never below 1
+    assert orc.threshold_rank(1024, 25_000, 100_000) == 256
+
+
+# ----------------------------------------------------------------------------- Algorithm 2
+def test_hindexer_full_sample_is_exact_threshold():
+    """Sample = whole corpus and rank = K': t is the K'-th largest score, so the strict filter keeps
+    exactly the items strictly above it (K'-1 of them when scores are distinct)."""
+    rng = np.random.default_rng(3)
+    Q = rng.integers(-8, 9, size=(2, 8)).astype(np.float32)          # integer data: every dot product exact
+    X = rng.integers(-8, 9, size=(500, 8)).astype(np.float32)
+    Kp = 37
+    res = orc.hindexer(Q, X, Kp, np.arange(500))
+    for b, (ids, sc, t) in enumerate(res):
+        s = [sum(int(Q[b, j]) * int(X[n, j]) for j in range(8)) for n in range(500)]
+        order = sorted(range(500), key=lambda n: (-s[n], n))
+        assert t == s[order[Kp - 1]]
+        above = [n for n in order if s[n] > t]                        # strict: ties with t are dropped
+        assert len(above) <= Kp - 1
+        assert ids.tolist() == above
+        assert np.all(sc > t)
+
+
+def test_hindexer_general_sample_invariants_and_truncation():
+    rng = np.random.default_rng(4)
+    Q = rng.integers(-8, 9, size=(3, 8)).astype(np.float32)
+    X = rng.integers(-8, 9, size=(2000, 8)).astype(np.float32)
+    S = orc.sample_indices(5, 400, 2000)
+    Kp = 100                                              # rank = 100*400/2000 = 20
+    full = orc.hindexer(Q, X, Kp, S, truncate=False)
+    cut = orc.hindexer(Q, X, Kp, S, truncate=True)
+    s = np.array([[sum(int(Q[b, j]) * int(X[n, j]) for j in range(8)) for n in range(2000)] for b in range(3)],
+                 dtype=np.float64)
+    for b in range(3):
+        ids, sc, t = full[b]
+        assert t == np.sort(s[b, S])[::-1][19]
+        assert set(ids.tolist()) == {n for n in range(2000) if s[b, n] > t}
+        cids, csc, _ = cut[b]
+        assert len(cids) == min(Kp, len(ids)) and cids.tolist() == ids[: len(cids)].tolist()
+        assert np.all(np.diff(csc) <= 0)
+        # the estimate is in the right region: expected count K', binomial spread ~ K'/sqrt(rank)
+        assert 30 <= len(ids) <= 250
+
+
+def test_hindexer_deeper_rank_keeps_superset():
+    rng = np.random.default_rng(5)
+    Q = rng.standard_normal((1, 8)).astype(np.float32)
+    X = rng.standard_normal((1000, 8)).astype(np.float32)
+    S = orc.sample_indices(9, 300, 1000)
+    a = orc.hindexer(Q, X, 50, S, rank=10, truncate=False)[0][0]
+    b = orc.hindexer(Q, X, 50, S, rank=25, truncate=False)[0][0]
+    assert set(a.tolist()) <= set(b.tolist())
+
+
+# ----------------------------------------------------------------------------- MoL
+def test_component_index_is_user_major():
+    """Algorithm 1's view/permute: component p = ku * k_x + kx."""
+    rng = np.random.default_rng(6)
+    F = rng.standard_normal((3, 5))
+    G = rng.standard_normal((4, 2, 5))
+    cl = orc.component_logits(F, G, 0.5)
+    assert cl.shape == (4, 6)
+    for c in range(4):
+        for ku in range(3):
+            for kx in range(2):
+                want = 0.5 * sum(F[ku, j] * G[c, kx, j] for j in range(5))
+                assert abs(cl[c, ku * 2 + kx] - want) < 1e-14
+
+
+def test_mol_single_component_is_scaled_dot_product():
+    """P = 1: the softmax over one component is 1, so phi = <f, g> / tau (Eq. 4 with one term, Eq. 9)."""
+    rng = np.random.default_rng(7)
+    model, F, gu = small_model(rng, k_u=1, k_x=1, scale=1 / 20)
+    phi = orc.mol_scores(model, F, gu)
+    Ff, Gf = orc.as_f64(F), model.G
+    want = np.einsum("bd,nd->bn", Ff[:, 0], Gf[:, 0]) / 20
+    np.testing.assert_allclose(phi, want, rtol=1e-13, atol=1e-15)
+
+
+@pytest.mark.parametrize("act", ["relu", "silu"])
+def test_gate_is_a_distribution_and_phi_is_a_convex_combination(act):
+    rng = np.random.default_rng(8)
+    model, F, gu = small_model(rng, act=act)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    for b in range(3):
+        cl = orc.component_logits(Ff[b], model.G, model.logit_scale)
+        pi = orc.gating_weights(cl, guf[b], model.gx, model.W1, model.b1, model.W2, model.b2, act)
+        assert np.all(pi > 0)
+        np.testing.assert_allclose(pi.sum(axis=1), 1.0, rtol=1e-14)
+        phi = orc.mol_scores_for(model, Ff[b], guf[b], np.arange(model.G.shape[0]))
+        assert np.all(phi >= cl.min(axis=1) - 1e-14) and np.all(phi <= cl.max(axis=1) + 1e-14)
+
+
+def test_uniform_gate_closed_form():
+    """W2 = 0, b2 = 0 => pi = 1/P => phi = <sum_ku f_ku, sum_kx g_kx> * scale / P (from Eq. 6)."""
+    rng = np.random.default_rng(9)
+    model, F, gu = small_model(rng, scale=3.0)
+    model.W2[:] = 0.0
+    model.b2[:] = 0.0
+    phi = orc.mol_scores(model, F, gu)
+    Ff = orc.as_f64(F)
+    want = 3.0 * np.einsum("bd,nd->bn", Ff.sum(axis=1), model.G.sum(axis=1)) / model.W2.shape[0]
+    np.testing.assert_allclose(phi, want, rtol=1e-12, atol=1e-14)
+
+
+def test_user_only_gate_reduces_to_weighted_embeddings():
+    """If the gate ignores the item and the logits, Eq. 5 holds: the mixture is a sum of dot products
+    of pi-weighted user embeddings.  Evaluated here the other way round (weight first, dot after)."""
+    rng = np.random.default_rng(10)
+    k_u, k_x, d_gu, d_gx = 2, 3, 4, 3
+    model, F, gu = small_model(rng, k_u=k_u, k_x=k_x, d_gu=d_gu, d_gx=d_gx, scale=0.7)
+    P = k_u * k_x
+    model.W1[:, :P] = 0.0                        # no cross input
+    model.W1[:, P + d_gu:] = 0.0                 # no item input
+    phi = orc.mol_scores(model, F, gu)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    for b in range(3):
+        h = np.maximum(model.W1[:, P:P + d_gu] @ guf[b] + model.b1, 0.0)
+        z = model.W2 @ h + model.b2
+        pi = np.exp(z - z.max())
+        pi = (pi / pi.sum()).reshape(k_u, k_x)
+        for n in range(model.G.shape[0]):
+            want = 0.0
+            for kx in range(k_x):
+                weighted_user = sum(pi[ku, kx] * Ff[b, ku] for ku in range(k_u))
+                want += 0.7 * float(weighted_user @ model.G[n, kx])
+            assert abs(phi[b, n] - want) < 1e-12
+
+
+def test_one_hot_gate_selects_the_indexed_pair():
+    """b2 strongly favouring component p* must return <f_{p* div k_x}, g_{p* mod k_x}> * scale."""
+    rng = np.random.default_rng(11)
+    k_u, k_x = 3, 2
+    model, F, gu = small_model(rng, k_u=k_u, k_x=k_x, scale=2.0)
+    Ff = orc.as_f64(F)
+    for p_star in range(k_u * k_x):
+        model.W2[:] = 0.0
+        model.b2[:] = 0.0
+        model.b2[p_star] = 800.0                 # exp(-800) underflows to exactly 0
+        phi = orc.mol_scores(model, F, gu)
+        want = 2.0 * np.einsum("bd,nd->bn", Ff[:, p_star // k_x], model.G[:, p_star % k_x])
+        np.testing.assert_allclose(phi, want, rtol=1e-13, atol=1e-15)
+
+
+def test_softmax_shift_invariance():
+    rng = np.random.default_rng(12)
+    model, F, gu = small_model(rng)
+    a = orc.mol_scores(model, F, gu)
+    model.b2 += 5.25
+    b = orc.mol_scores(model, F, gu)
+    np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-14)
+
+
+def test_split_first_layer_equals_concatenated():
+    """The first gating layer is linear in the concatenation, so it splits exactly into a cross part,
+    a user part and an item part (Eq. 8); the item part is what an item-side cache would hold."""
+    rng = np.random.default_rng(13)
+    model, F, gu = small_model(rng)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    P = model.W2.shape[0]
+    d_gu = guf.shape[1]
+    item_part = model.gx @ model.W1[:, P + d_gu:].T + model.b1            # cachable
+    for b in range(3):
+        cl = orc.component_logits(Ff[b], model.G, model.logit_scale)
+        user_part = model.W1[:, P:P + d_gu] @ guf[b]
+        h = np.maximum(cl @ model.W1[:, :P].T + user_part + item_part, 0.0)
+        z = h @ model.W2.T + model.b2
+        e = np.exp(z - z.max(axis=1, keepdims=True))
+        want = ((e / e.sum(axis=1, keepdims=True)) * cl).sum(axis=1)
+        got = orc.mol_scores_for(model, Ff[b], guf[b], np.arange(model.G.shape[0]))
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("act", ["relu", "silu"])
+def test_mol_loop_by_loop_rederivation(act):
+    """Pure-Python scalar loops over Eq. 3 / Eq. 6 / the 2-layer gate, no numpy broadcasting."""
+    import math
+    rng = np.random.default_rng(14)
+    model, F, gu = small_model(rng, N=6, act=act, scale=1.3)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    k_u, d = Ff.shape[1], Ff.shape[2]
+    k_x = model.G.shape[1]
+    P, H = k_u * k_x, model.W1.shape[0]
+    got = orc.mol_scores(model, F, gu)
+    for b in range(3):
+        for n in range(6):
+            cl = [1.3 * sum(Ff[b, p // k_x, j] * model.G[n, p % k_x, j] for j in range(d)) for p in range(P)]
+            x = cl + guf[b].tolist() + model.gx[n].tolist()
+            hid = []
+            for h in range(H):
+                pre = model.b1[h] + sum(model.W1[h, i] * x[i] for i in range(len(x)))
+                hid.append(max(pre, 0.0) if act == "relu" else pre / (1.0 + math.exp(-pre)))
+            z = [model.b2[p] + sum(model.W2[p, h] * hid[h] for h in range(H)) for p in range(P)]
+            m = max(z)
+            e = [math.exp(v - m) for v in z]
+            phi = sum(ei * ci for ei, ci in zip(e, cl)) / sum(e)
+            assert abs(got[b, n] - phi) < 1e-12
+
+
+def test_negative_candidate_ids_are_padding():
+    rng = np.random.default_rng(15)
+    model, F, gu = small_model(rng)
+    cand = np.array([[3, -1, 7], [0, 1, -1], [-1, -1, 5]])
+    sc = orc.mol_scores(model, F, gu, cand)
+    full = orc.mol_scores(model, F, gu)
+    for b in range(3):
+        for j in range(3):
+            if cand[b, j] < 0:
+                assert sc[b, j] == -np.inf
+            else:
+                assert sc[b, j] == full[b, cand[b, j]]
+
+
+# ----------------------------------------------------------------------------- compositions
+def _two_stage_case(rng, N=300):
+    model, F, gu = small_model(rng, N=N)
+    Q1 = rand_bf16_bits(rng, (3, 16))
+    X1 = rand_bf16_bits(rng, (N, 16))
+    return model, F, gu, Q1, X1
+
+
+def test_two_stage_with_all_candidates_equals_exhaustive():
+    """K' = N is the MoL-only model (Section 5.2.1)."""
+    rng = np.random.default_rng(16)
+    model, F, gu, Q1, X1 = _two_stage_case(rng)
+    a = orc.two_stage(model, Q1, X1, F, gu, Kp=300, k=10)
+    e = orc.mol_topk(model, F, gu, None, 10)
+    for (ai, asc), (ei, esc) in zip(a, e):
+        assert ai.tolist() == ei.tolist() and asc.tolist() == esc.tolist()
+
+
+def test_two_stage_is_subset_consistent():
+    """Every returned item is a stage-1 candidate, and is the best-scored among them."""
+    rng = np.random.default_rng(17)
+    model, F, gu, Q1, X1 = _two_stage_case(rng)
+    res = orc.two_stage(model, Q1, X1, F, gu, Kp=40, k=5)
+    s1 = orc.stage1_scores(Q1, X1)
+    full = orc.mol_scores(model, F, gu)
+    for b, (ids, sc) in enumerate(res):
+        cand = sorted(range(300), key=lambda n: (-s1[b, n], n))[:40]
+        best = sorted(cand, key=lambda n: (-full[b, n], n))[:5]
+        assert ids.tolist() == best
+
+
+def test_corpus_permutation_invariance():
+    rng = np.random.default_rng(18)
+    model, F, gu, Q1, X1 = _two_stage_case(rng)
+    base = orc.two_stage(model, Q1, X1, F, gu, Kp=50, k=8)
+    perm = rng.permutation(300)                            # new row j holds old row perm[j]
+    G2 = model.G[perm]
+    gx2 = model.gx[perm]
+    m2 = orc.MolModel(G2, gx2, model.W1, model.b1, model.W2, model.b2, model.logit_scale, model.act)
+    res = orc.two_stage(m2, Q1, X1[perm], F, gu, Kp=50, k=8)
+    for (bi, bs), (ri, rs) in zip(base, res):
+        assert perm[ri].tolist() == bi.tolist()            # distinct scores: same items, same order
+        np.testing.assert_allclose(rs, bs, rtol=1e-12)
+
+
+def test_batch_split_invariance():
+    rng = np.random.default_rng(19)
+    model, F, gu, Q1, X1 = _two_stage_case(rng)
+    whole = orc.two_stage(model, Q1, X1, F, gu, Kp=50, k=8)
+    for b in range(3):
+        one = orc.two_stage(model, Q1[b:b + 1], X1, F[b:b + 1], gu[b:b + 1], Kp=50, k=8)[0]
+        assert one[0].tolist() == whole[b][0].tolist() and one[1].tolist() == whole[b][1].tolist()
+    S = orc.sample_indices(1, 100, 300)
+    hw = orc.hindexer(Q1, X1, 30, S)
+    for b in range(3):
+        h1 = orc.hindexer(Q1[b:b + 1], X1, 30, S)[0]
+        assert h1[0].tolist() == hw[b][0].tolist() and h1[2] == hw[b][2]
