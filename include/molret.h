@@ -1,0 +1,153 @@
+/*
+ * molret.h -- C ABI of the two-stage retrieval library for AMD MI355X (gfx950).
+ *
+ * The calls follow the paper's inference flow (Section 2.2, Figure 1(a)): an item-side cache is built
+ * once (mol_corpus_pack); per query batch, stage 1 (h-indexer, Section 4.1, Algorithm 2) proposes K'
+ * candidates per query from the whole corpus (hindexer_topk); stage 2 scores them with Mixture of
+ * Logits (Section 3, Algorithm 1) (mol_score) and keeps the k best (mol_topk).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless the comment says "host".  Tensors are row-major
+ *     and contiguous.  bf16 tensors are raw 16-bit patterns.  Item indices are int32 (N < 2^31).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on it
+ *     and return; none of them synchronises the device, except mol_corpus_pack / mol_corpus_free.
+ *   - The caller owns all inputs, outputs and workspaces.  A corpus handle owns only what pack
+ *     allocated.  Workspaces must be 256-byte aligned and at least as large as the matching
+ *     *_workspace_bytes() call reports; their contents need not be preserved between calls.
+ *   - Every function returns MOL_OK or a negative mol_status_t; mol_last_error() gives a message for
+ *     the calling thread.  On MOL_EINVAL / MOL_EWORKSPACE / MOL_EUNSUPPORTED nothing was enqueued and
+ *     outputs are untouched.  Nothing aborts or throws across this boundary.
+ *   - Total order used everywhere: score descending, then item index ascending.
+ */
+#ifndef MOLRET_H
+#define MOLRET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mol_corpus mol_corpus_t; /* opaque handle */
+
+typedef enum {
+  MOL_OK = 0,
+  MOL_EINVAL = -1,       /* bad argument (null pointer, size out of range, misaligned workspace) */
+  MOL_ENOMEM = -2,       /* device allocation failed in pack */
+  MOL_EWORKSPACE = -3,   /* workspace too small */
+  MOL_EUNSUPPORTED = -4, /* shape outside what the kernels are built for */
+  MOL_EHIP = -5          /* a HIP runtime call failed */
+} mol_status_t;
+
+enum { MOL_F32 = 0, MOL_BF16 = 1 };       /* stage1_dtype */
+enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
+
+/* pack flags */
+#define MOL_PACK_BORROW_STAGE1 1u /* keep the caller's stage-1 table (no copy); it must outlive the handle */
+#define MOL_PACK_BORROW_EMBS 2u   /* keep the caller's item embedding tensor (no copy); same lifetime rule */
+
+/* h-indexer modes */
+#define MOL_HINDEXER_EXACT 0 /* sampled threshold at a deeper rank, exact top-K' of the survivors, exact redo on a miss */
+#define MOL_HINDEXER_PAPER 1 /* Algorithm 2 as written: rank K'*lambda/N, strict filter, at most K' kept */
+
+/*
+ * Model description (host struct; read during mol_corpus_pack only).
+ * Gating network (Section 3.2, Eq. 8, in the concatenated 2-layer form): for a (user, item) pair
+ *   in  = [ cl (P = k_u*k_x component logits, index p = ku*k_x + kx) | user gate feature (d_gu) | item gate feature (d_gx) ]
+ *   pi  = softmax_P( W2 * act(W1 * in + b1) + b2 ),    phi = sum_p pi_p * cl_p         (Eq. 3, Eq. 6)
+ *   cl_p = logit_scale * <user_emb[ku], item_emb[kx]>                                   (Eq. 9; logit_scale = 1/tau)
+ * Supported shapes: d1 = 64; d_p in {32, 64, 128}; k_x in {1, 2, 4, 8, 16}; k_u <= 16; P a multiple of 16
+ * and at most 128; H a multiple of 32, at most 256; d_gu, d_gx multiples of 16, at most 256.
+ */
+typedef struct {
+  int64_t N;            /* corpus size */
+  int32_t d1;           /* stage-1 embedding width (Section 4.1.1); 0 = no stage-1 table */
+  int32_t stage1_dtype; /* MOL_F32 or MOL_BF16 */
+  int32_t k_u, k_x, d_p;
+  int32_t d_gu, d_gx, H;
+  int32_t act;
+  float logit_scale;
+  const void *W1;  /* device, bf16 [H, P + d_gu + d_gx] */
+  const float *b1; /* device, f32 [H], or NULL for zeros */
+  const void *W2;  /* device, bf16 [P, H] */
+  const float *b2; /* device, f32 [P], or NULL for zeros */
+  uint32_t flags;  /* MOL_PACK_* */
+} mol_config_t;
+
+/*
+ * Build the item-side cache (Section 2.2 "cache item-side gating weights"; the loops marked cachable in
+ * Algorithm 1): keeps the stage-1 table [N, d1] and the item component embeddings [N, k_x, d_p] (already
+ * L2-normalised by the caller, Eq. 9), and precomputes the item half of the first gating layer,
+ * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H].
+ *   stage1_items : [N, d1] of stage1_dtype, or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
+ *   item_embs    : bf16 [N, k_x, d_p].      item_gate : bf16 [N, d_gx]; not referenced after the call returns.
+ * Allocates device memory with hipMalloc; synchronises `stream` before returning.  *out is set on MOL_OK only.
+ */
+mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *stage1_items, const void *item_embs,
+                             const void *item_gate, void *stream, mol_corpus_t **out);
+
+/* Frees what pack allocated (device synchronising).  NULL is accepted. */
+mol_status_t mol_corpus_free(mol_corpus_t *corpus);
+
+/* Host-only size queries; return 0 on invalid arguments.  lambda <= 0 selects the library's default sample size. */
+size_t hindexer_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int64_t lambda);
+size_t mol_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int k);
+
+/* Default sample size for (N, K'): max(ceil(0.01 N), ceil(256 N / K')), capped at N/2 (Section 4.1.2: r in [0.01, 0.1]). */
+int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
+
+/*
+ * Stage 1 (Algorithm 2; Sections 4.1.1-4.1.2): for each of B queries, score `lambda` sampled items, take the
+ * sampled score of rank r as threshold t_b, stream the whole stage-1 table once computing <q1[b], x[n]> for all
+ * b and n, keep (n, score) with score > t_b (strict), and reduce the survivors to at most K' candidates.
+ *   q1          : [B, d1] of the corpus' stage1_dtype.   1 <= B <= 1024, 1 <= Kp <= N.
+ *   sample_idx  : int32 [lambda] explicit sample (each in [0, N)), or NULL: the library then draws
+ *                 idx_i = floor(N * hi32(SplitMix64_i(seed)) / 2^32), i = 1..lambda (stream state seed + i*0x9E3779B97F4A7C15).
+ *   lambda      : sample size (a count); <= 0 = hindexer_default_lambda().  Ignored when 4*Kp >= N (no sampling: every
+ *                 item passes and the exact top-K' is taken).
+ *   mode        : MOL_HINDEXER_PAPER  r = max(1, floor(Kp*lambda/N)); more than K' survivors are cut to the K' best,
+ *                                     fewer are returned as they are (cand_count[b] < Kp).
+ *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive, then the exact
+ *                                     top-K' of the survivors; a query whose survivors number fewer than K' or overflow the
+ *                                     workspace is redone on the device with an exact multi-pass radix threshold.  The
+ *                                     result is the exact stage-1 top-K' under fp32 scores.
+ *   cand_idx    : out int32 [B, Kp]; a set, in no particular order; unused slots are -1.
+ *   cand_score  : out f32 [B, Kp] stage-1 scores aligned with cand_idx (unused slots -inf), or NULL.
+ *   cand_count  : out int32 [B] number of valid slots.
+ * Scores are fp32 accumulations of the stored bf16 / fp32 values.
+ */
+mol_status_t hindexer_topk(const mol_corpus_t *corpus, const void *q1, int B, int Kp, const int32_t *sample_idx,
+                           int64_t lambda, uint64_t seed, int mode, int32_t *cand_idx, float *cand_score,
+                           int32_t *cand_count, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Stage 2 scores (Algorithm 1 without its last line; Eq. 3, 6, 9; gating as described at mol_config_t).
+ *   user_embs : bf16 [B, k_u, d_p] (L2-normalised by the caller).   user_gate : bf16 [B, d_gu].
+ *   cand_idx  : int32 [B, Kp] item indices, negative = padding (score -inf); or NULL = every item 0..N-1 for
+ *               every query (Kp is then ignored and the row length is N).
+ *   scores    : out f32 [B, Kp] (or [B, N]).
+ * Component logits, both gating layers, the softmax and the weighted sum run in one kernel; logits and hidden
+ * activations enter the matrix cores as bf16, accumulation and the final sum are fp32.
+ */
+mol_status_t mol_score(const mol_corpus_t *corpus, const void *user_embs, const void *user_gate, int B,
+                       const int32_t *cand_idx, int Kp, float *scores, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Stage 2 with the final selection (Algorithm 1 including its last line): the k best candidates per query.
+ *   cand_idx / Kp as in mol_score (NULL = exhaustive MoL over the corpus).
+ *   out_idx   : out int32 [B, k] item indices, best first (score desc, index asc); -1 where fewer than k exist.
+ *   out_score : out f32 [B, k] their MoL scores (-inf padding).
+ */
+mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const void *user_gate, int B,
+                      const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* Message for the last non-OK status returned on this thread (host string, valid until the next call). */
+const char *mol_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOLRET_H */

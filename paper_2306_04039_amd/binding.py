@@ -1,0 +1,252 @@
+"""ctypes binding of include/molret.h.  Argument marshalling only: every step of the retrieval path runs in
+the HIP kernels of libmolret.so; torch provides device memory and the current stream.  There is no fallback:
+if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+HINDEXER_EXACT = 0
+HINDEXER_PAPER = 1
+PACK_BORROW_STAGE1 = 1
+PACK_BORROW_EMBS = 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = (
+    "mol_corpus_pack", "mol_corpus_free", "hindexer_workspace_bytes", "mol_workspace_bytes",
+    "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
+)
+
+
+class MolError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"molret status {status}: {message}")
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [
+        ("N", C.c_int64), ("d1", C.c_int32), ("stage1_dtype", C.c_int32),
+        ("k_u", C.c_int32), ("k_x", C.c_int32), ("d_p", C.c_int32),
+        ("d_gu", C.c_int32), ("d_gx", C.c_int32), ("H", C.c_int32),
+        ("act", C.c_int32), ("logit_scale", C.c_float),
+        ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
+        ("flags", C.c_uint32),
+    ]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libmolret.so")
+
+
+def load_library() -> C.CDLL:
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` at the repo root")
+    lib = C.CDLL(path)
+    vp, i32, i64, u64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_size_t
+    lib.mol_corpus_pack.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, C.POINTER(vp)]
+    lib.mol_corpus_pack.restype = i32
+    lib.mol_corpus_free.argtypes = [vp]
+    lib.mol_corpus_free.restype = i32
+    lib.hindexer_workspace_bytes.argtypes = [vp, i32, i32, i64]
+    lib.hindexer_workspace_bytes.restype = sz
+    lib.mol_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    lib.mol_workspace_bytes.restype = sz
+    lib.hindexer_default_lambda.argtypes = [vp, i32]
+    lib.hindexer_default_lambda.restype = i64
+    lib.hindexer_topk.argtypes = [vp, vp, i32, i32, vp, i64, u64, i32, vp, vp, vp, vp, sz, vp]
+    lib.hindexer_topk.restype = i32
+    lib.mol_score.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, sz, vp]
+    lib.mol_score.restype = i32
+    lib.mol_topk.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.mol_topk.restype = i32
+    lib.mol_last_error.argtypes = []
+    lib.mol_last_error.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        raise MolError(status, load_library().mol_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+class Corpus:
+    """Owns a mol_corpus_t handle (and references to borrowed tensors)."""
+
+    def __init__(self, handle: int, N: int, d1: int, stage1_dtype, k_u: int, k_x: int, d_p: int, H: int, d_gu: int,
+                 keep):
+        self.handle = handle
+        self.N, self.d1, self.stage1_dtype = N, d1, stage1_dtype
+        self.k_u, self.k_x, self.d_p, self.H, self.d_gu = k_u, k_x, d_p, H, d_gu
+        self._keep = keep
+
+    def free(self):
+        if self.handle:
+            load_library().mol_corpus_free(self.handle)
+            self.handle = None
+            self._keep = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tensor, item_gate: torch.Tensor,
+                    W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
+                    k_u: int, logit_scale: float = 1.0, act: str = "relu", borrow: bool = False) -> Corpus:
+    lib = load_library()
+    N, k_x, d_p = item_embs.shape
+    _dev(item_embs, torch.bfloat16, "item_embs")
+    _dev(item_gate, torch.bfloat16, "item_gate")
+    _dev(W1, torch.bfloat16, "W1")
+    _dev(W2, torch.bfloat16, "W2")
+    if b1 is not None:
+        _dev(b1, torch.float32, "b1")
+    if b2 is not None:
+        _dev(b2, torch.float32, "b2")
+    P, H = W2.shape
+    d_gx = item_gate.shape[1]
+    d_gu = W1.shape[1] - P - d_gx
+    if P != k_u * k_x or W1.shape[0] != H or d_gu < 1 or item_gate.shape[0] != N:
+        raise ValueError("inconsistent model shapes")
+    cfg = _Config()
+    cfg.N = N
+    if stage1_items is not None:
+        if stage1_items.dtype not in (torch.float32, torch.bfloat16):
+            raise ValueError("stage1_items must be float32 or bfloat16")
+        _dev(stage1_items, stage1_items.dtype, "stage1_items")
+        if stage1_items.shape[0] != N:
+            raise ValueError("stage1_items rows != N")
+        cfg.d1 = stage1_items.shape[1]
+        cfg.stage1_dtype = 0 if stage1_items.dtype == torch.float32 else 1
+    else:
+        cfg.d1 = 0
+        cfg.stage1_dtype = 1
+    cfg.k_u, cfg.k_x, cfg.d_p = k_u, k_x, d_p
+    cfg.d_gu, cfg.d_gx, cfg.H = d_gu, d_gx, H
+    cfg.act = {"relu": 0, "silu": 1}[act]
+    cfg.logit_scale = logit_scale
+    cfg.W1, cfg.b1, cfg.W2, cfg.b2 = _ptr(W1), _ptr(b1), _ptr(W2), _ptr(b2)
+    cfg.flags = (PACK_BORROW_STAGE1 | PACK_BORROW_EMBS) if borrow else 0
+    out = C.c_void_p()
+    _check(lib.mol_corpus_pack(C.byref(cfg), _ptr(stage1_items), _ptr(item_embs), _ptr(item_gate), _stream(),
+                               C.byref(out)))
+    keep = (stage1_items, item_embs) if borrow else None
+    return Corpus(out.value, N, cfg.d1, None if stage1_items is None else stage1_items.dtype, k_u, k_x, d_p, H, d_gu,
+                  keep)
+
+
+def hindexer_default_lambda(corpus: Corpus, Kp: int) -> int:
+    return int(load_library().hindexer_default_lambda(corpus.handle, Kp))
+
+
+def hindexer_workspace_bytes(corpus: Corpus, B: int, Kp: int, lam: int = 0) -> int:
+    return int(load_library().hindexer_workspace_bytes(corpus.handle, B, Kp, lam))
+
+
+def mol_workspace_bytes(corpus: Corpus, B: int, Kp: int, k: int) -> int:
+    return int(load_library().mol_workspace_bytes(corpus.handle, B, Kp, k))
+
+
+def _workspace(nbytes: int, device, workspace: Optional[torch.Tensor]) -> torch.Tensor:
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def hindexer_topk(corpus: Corpus, q1: torch.Tensor, Kp: int, lam: int = 0, seed: int = 0, mode: int = HINDEXER_EXACT,
+                  sample_idx: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                  out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None
+                  ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    lib = load_library()
+    _dev(q1, corpus.stage1_dtype, "q1")
+    B = q1.shape[0]
+    if q1.shape[1] != corpus.d1:
+        raise ValueError("q1 width != d1")
+    if sample_idx is not None:
+        _dev(sample_idx, torch.int32, "sample_idx")
+        lam = sample_idx.numel()
+    if out is None:
+        out = (torch.empty(B, Kp, dtype=torch.int32, device=q1.device),
+               torch.empty(B, Kp, dtype=torch.float32, device=q1.device),
+               torch.empty(B, dtype=torch.int32, device=q1.device))
+    ci, cs, cc = out
+    need = lib.hindexer_workspace_bytes(corpus.handle, B, Kp, lam)
+    ws = _workspace(need, q1.device, workspace)
+    _check(lib.hindexer_topk(corpus.handle, _ptr(q1), B, Kp, _ptr(sample_idx), lam, seed, mode, _ptr(ci), _ptr(cs),
+                             _ptr(cc), _ptr(ws), ws.numel(), _stream()))
+    return ci, cs, cc
+
+
+def mol_score(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor,
+              cand_idx: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    lib = load_library()
+    _dev(user_embs, torch.bfloat16, "user_embs")
+    _dev(user_gate, torch.bfloat16, "user_gate")
+    B = user_embs.shape[0]
+    if tuple(user_embs.shape[1:]) != (corpus.k_u, corpus.d_p) or tuple(user_gate.shape) != (B, corpus.d_gu):
+        raise ValueError("user tensor shapes do not match the corpus")
+    Kp = 0
+    if cand_idx is not None:
+        _dev(cand_idx, torch.int32, "cand_idx")
+        Kp = cand_idx.shape[1]
+    row = Kp if cand_idx is not None else corpus.N
+    if out is None:
+        out = torch.empty(B, row, dtype=torch.float32, device=user_embs.device)
+    ws = _workspace(lib.mol_workspace_bytes(corpus.handle, B, 1, 1), user_embs.device, workspace)
+    _check(lib.mol_score(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), Kp, _ptr(out), _ptr(ws),
+                         ws.numel(), _stream()))
+    return out
+
+
+def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, cand_idx: Optional[torch.Tensor],
+             k: int, workspace: Optional[torch.Tensor] = None,
+             out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    lib = load_library()
+    _dev(user_embs, torch.bfloat16, "user_embs")
+    _dev(user_gate, torch.bfloat16, "user_gate")
+    B = user_embs.shape[0]
+    if tuple(user_embs.shape[1:]) != (corpus.k_u, corpus.d_p) or tuple(user_gate.shape) != (B, corpus.d_gu):
+        raise ValueError("user tensor shapes do not match the corpus")
+    Kp = 0
+    if cand_idx is not None:
+        _dev(cand_idx, torch.int32, "cand_idx")
+        Kp = cand_idx.shape[1]
+    if out is None:
+        out = (torch.empty(B, k, dtype=torch.int32, device=user_embs.device),
+               torch.empty(B, k, dtype=torch.float32, device=user_embs.device))
+    ws = _workspace(lib.mol_workspace_bytes(corpus.handle, B, Kp, k), user_embs.device, workspace)
+    _check(lib.mol_topk(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), Kp, k, _ptr(out[0]),
+                        _ptr(out[1]), _ptr(ws), ws.numel(), _stream()))
+    return out

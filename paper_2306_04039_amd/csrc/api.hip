@@ -1,0 +1,119 @@
+// C ABI entry points: argument checking, workspace carving, error reporting.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.hpp"
+
+static thread_local char g_err[512] = "";
+
+mol_status_t mol_fail(mol_status_t st, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+extern "C" const char *mol_last_error(void) { return g_err; }
+
+extern "C" int64_t hindexer_default_lambda(const mol_corpus_t *c, int Kp) {
+  if (!c || Kp < 1) return 0;
+  const int64_t N = c->N;
+  int64_t a = (N + 99) / 100;
+  int64_t b = (256 * N + Kp - 1) / Kp;
+  int64_t lam = a > b ? a : b;
+  if (lam > N / 2) lam = N / 2;
+  if (lam < 1) lam = 1;
+  return lam;
+}
+
+extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp, int64_t lambda) {
+  if (!c || B < 1 || B > 1024 || Kp < 1 || Kp > c->N || c->d1 == 0) return 0;
+  HindexerPlan p0, p1;
+  hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_EXACT, &p0);
+  hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_PAPER, &p1);
+  return p0.total > p1.total ? p0.total : p1.total;
+}
+
+static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, size_t *off_scores) {
+  size_t off = align_up((size_t)B * c->H * 4, 256);
+  if (off_scores) *off_scores = off;
+  off = align_up(off + (size_t)B * row * 4, 256);
+  return off;
+}
+
+extern "C" size_t mol_workspace_bytes(const mol_corpus_t *c, int B, int Kp, int k) {
+  if (!c || B < 1 || B > 1024 || k < 0) return 0;
+  const int64_t row = Kp > 0 ? Kp : c->N;
+  return mol_ws_layout(c, B, row, nullptr);
+}
+
+static mol_status_t check_ws(const void *ws, size_t have, size_t need) {
+  if (!ws) return mol_fail(MOL_EINVAL, "workspace is NULL (%zu bytes needed)", need);
+  if (reinterpret_cast<uintptr_t>(ws) % 256) return mol_fail(MOL_EINVAL, "workspace must be 256-byte aligned");
+  if (have < need) return mol_fail(MOL_EWORKSPACE, "workspace has %zu bytes, %zu needed", have, need);
+  return MOL_OK;
+}
+
+extern "C" mol_status_t hindexer_topk(const mol_corpus_t *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
+                                      int64_t lambda, uint64_t seed, int mode, int32_t *cand_idx, float *cand_score,
+                                      int32_t *cand_count, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!c || !q1 || !cand_idx || !cand_count) return mol_fail(MOL_EINVAL, "hindexer_topk: NULL argument");
+  if (c->d1 == 0 || !c->stage1) return mol_fail(MOL_EINVAL, "hindexer_topk: the corpus was packed without a stage-1 table");
+  if (B < 1 || B > 1024) return mol_fail(MOL_EINVAL, "B=%d must be in [1, 1024]", B);
+  if (Kp < 1 || Kp > c->N) return mol_fail(MOL_EINVAL, "Kp=%d must be in [1, N=%lld]", Kp, (long long)c->N);
+  if (mode != MOL_HINDEXER_EXACT && mode != MOL_HINDEXER_PAPER) return mol_fail(MOL_EINVAL, "unknown mode %d", mode);
+  if (sample_idx && lambda < 1) return mol_fail(MOL_EINVAL, "an explicit sample needs lambda >= 1");
+  HindexerPlan p;
+  hindexer_plan(c, B, Kp, lambda, mode, &p);
+  mol_status_t rc = check_ws(workspace, workspace_bytes, p.total);
+  if (rc != MOL_OK) return rc;
+  return hindexer_run(c, q1, B, Kp, sample_idx, seed, mode, p, cand_idx, cand_score, cand_count,
+                      static_cast<char *>(workspace), static_cast<hipStream_t>(stream));
+}
+
+static mol_status_t mol_common_checks(const mol_corpus_t *c, const void *ue, const void *ug, int B,
+                                      const int32_t *cand, int Kp) {
+  if (!c || !ue || !ug) return mol_fail(MOL_EINVAL, "NULL corpus / user_embs / user_gate");
+  if (B < 1 || B > 1024) return mol_fail(MOL_EINVAL, "B=%d must be in [1, 1024]", B);
+  if (cand && Kp < 1) return mol_fail(MOL_EINVAL, "Kp=%d must be >= 1 when cand_idx is given", Kp);
+  return MOL_OK;
+}
+
+extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                  const int32_t *cand_idx, int Kp, float *scores, void *workspace,
+                                  size_t workspace_bytes, void *stream) {
+  mol_status_t rc = mol_common_checks(c, user_embs, user_gate, B, cand_idx, Kp);
+  if (rc != MOL_OK) return rc;
+  if (!scores) return mol_fail(MOL_EINVAL, "scores is NULL");
+  const size_t need = align_up((size_t)B * c->H * 4, 256);
+  rc = check_ws(workspace, workspace_bytes, need);
+  if (rc != MOL_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *U = static_cast<float *>(workspace);
+  rc = launch_user_gate(c, user_gate, B, U, st);
+  if (rc != MOL_OK) return rc;
+  return launch_mol_score(c, user_embs, U, B, cand_idx, Kp, scores, st);
+}
+
+extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                 const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score,
+                                 void *workspace, size_t workspace_bytes, void *stream) {
+  mol_status_t rc = mol_common_checks(c, user_embs, user_gate, B, cand_idx, Kp);
+  if (rc != MOL_OK) return rc;
+  if (!out_idx || !out_score) return mol_fail(MOL_EINVAL, "out_idx / out_score is NULL");
+  if (k < 1 || k > 1024) return mol_fail(MOL_EINVAL, "k=%d must be in [1, 1024]", k);
+  const int64_t row = cand_idx ? Kp : c->N;
+  size_t off_scores = 0;
+  const size_t need = mol_ws_layout(c, B, row, &off_scores);
+  rc = check_ws(workspace, workspace_bytes, need);
+  if (rc != MOL_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float *U = static_cast<float *>(workspace);
+  float *scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_scores);
+  rc = launch_user_gate(c, user_gate, B, U, st);
+  if (rc != MOL_OK) return rc;
+  rc = launch_mol_score(c, user_embs, U, B, cand_idx, row, scores, st);
+  if (rc != MOL_OK) return rc;
+  return launch_final_topk(scores, cand_idx, B, row, k, out_idx, out_score, st);
+}

@@ -1,0 +1,100 @@
+// Shared device helpers and internal structs for the retrieval library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "molret.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+#define WAVE 64
+
+// ---------------------------------------------------------------------------------------------
+// Order-preserving map float -> uint32 (larger float <=> larger key).  -0 is folded into +0 first.
+__device__ __forceinline__ uint32_t f32_to_key(float f) {
+  uint32_t u = __float_as_uint(f + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_f32(uint32_t k) {
+  uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(u);
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
+  union {
+    uint4 u;
+    bf16x8 b;
+  } c;
+  c.u = v;
+  return c.b;
+}
+
+// 16-byte global load through a plain pointer.
+__device__ __forceinline__ uint4 ld16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+// ---------------------------------------------------------------------------------------------
+struct mol_corpus {
+  int64_t N;
+  int32_t d1, stage1_dtype;
+  int32_t k_u, k_x, d_p, P;
+  int32_t d_gu, d_gx, H, act;
+  float logit_scale;
+  uint32_t flags;
+  int device;
+  // device memory
+  const void *stage1;   // [N, d1]
+  const void *embs;     // bf16 [N, k_x, d_p]
+  void *xi;             // bf16 [N, H]   item half of gating layer 1 (+ b1)
+  void *w1c_frag;       // bf16, MFMA fragment order, [H/32][P/16][64][8]
+  void *w2_frag;        // bf16, MFMA fragment order, [ceil(P/32)][H/16][64][8]
+  void *w1u;            // bf16 [H, d_gu] row-major (user part of layer 1)
+  float *b2;            // f32 [32*ceil(P/32)] (padded with zeros)
+  bool own_stage1, own_embs;
+};
+
+// error plumbing (api.hip)
+mol_status_t mol_fail(mol_status_t st, const char *fmt, ...);
+#define HIP_TRY(expr)                                                                           \
+  do {                                                                                          \
+    hipError_t e__ = (expr);                                                                    \
+    if (e__ != hipSuccess) return mol_fail(MOL_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- launchers implemented in the kernel files ------------------------------------------------
+// stage1.hip
+struct HindexerPlan {
+  bool sampling;       // false: every item passes (threshold -inf)
+  int64_t lambda;      // sample size actually used
+  int64_t rank;        // threshold rank inside the sample (1-based from the largest)
+  int64_t cap;         // survivor capacity per query
+  // workspace offsets (bytes)
+  size_t off_sample, off_skeys, off_thr, off_count, off_flags, off_surv, off_hist, off_state, total;
+};
+mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, int mode, HindexerPlan *p);
+mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
+                          uint64_t seed, int mode, const HindexerPlan &p, int32_t *cand_idx, float *cand_score,
+                          int32_t *cand_count, char *ws, hipStream_t st);
+// pack.hip
+mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, const void *w1x_rowmajor,
+                                    const float *b1, hipStream_t st);
+// mol.hip
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, hipStream_t st);
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
+                              const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st);
+// select.hip
+mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
+                               int32_t *out_idx, float *out_score, hipStream_t st);

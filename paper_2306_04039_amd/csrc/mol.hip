@@ -1,0 +1,339 @@
+// Stage 2, Mixture of Logits (Section 3, Algorithm 1), one fused kernel per call.
+//
+// A wavefront scores tiles of 32 candidates of one query.  Per tile:
+//   A. component logits cl[c, ku*k_x + kx] = logit_scale * <F[b,ku], G[n_c,kx]>  (Eq. 6, Eq. 9): candidate rows are
+//      gathered from the item cache straight into MFMA operand registers (16x16x32 bf16, rows = (candidate, kx),
+//      columns = ku); the fp32 result goes to a small LDS tile, already in the permuted (candidate, P) order that
+//      Algorithm 1 produces with view/permute, so the permute costs nothing (Section 4.2).
+//   B. gating layer 1, transposed: pre^T[h, c] = W1c[h, :] . cl[c, :] on 32x32x16 MFMA, plus the per-query user
+//      part U[b, h] and the cached item part Xi[n_c, h] (Section 3.2 decomposition), activation in registers.
+//   C. gating layer 2, transposed: z^T[p, c] = W2[p, :] . hid[c, :]; the layer-1 accumulators are exactly the
+//      B-operand of this product (same lane = same candidate), so hidden activations never leave registers.
+//   D. softmax over the P components and phi = sum_p pi_p * cl_p (Eq. 3) with the fp32 logits from the LDS tile;
+//      each candidate's P values sit in two lanes (lane, lane^32).
+// Nothing but the final score is written to HBM (the fusion Section 4.2 argues for).
+#include <math.h>
+
+#include "common.hpp"
+
+namespace {
+
+struct MolArgs {
+  const char *embs;      // bf16 [N, K_X, D_P]
+  const char *xi;        // bf16 [N, H]
+  const char *w1c_frag;  // bf16 fragments
+  const char *w2_frag;   // bf16 fragments
+  const float *b2;       // f32 [32*PT]
+  const char *F;         // bf16 [B, K_U, D_P]
+  const float *U;        // f32 [B, H]
+  const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
+  float *scores;         // [B, Kp]
+  int64_t Kp;            // row length of cand / scores
+  int64_t N;
+  int B;
+  int act;
+  float logit_scale;
+  int query_fastest;     // tile order: 1 = consecutive tiles are different queries of the same item block
+};
+
+template <int K_U, int K_X, int D_P, int H>
+struct MolShape {
+  static constexpr int P = K_U * K_X;
+  static constexpr int MT = H / 32;          // row tiles of layer 1 (hidden units)
+  static constexpr int S1 = P / 16;          // k-steps of layer 1
+  static constexpr int PT = (P + 31) / 32;   // row tiles of layer 2 (components)
+  static constexpr int S2 = H / 16;          // k-steps of layer 2
+  static constexpr int SA = D_P / 32;        // k-steps of the component-logit product
+  static constexpr int CPR = 16 / K_X;       // candidates per 16-row MFMA tile
+  static constexpr int RT = 32 / CPR;        // 16-row tiles per 32 candidates
+  static constexpr int CLS = P + 4;          // LDS row stride of the logit tile (floats)
+  static constexpr int W1B = MT * S1 * 1024; // bytes
+  static constexpr int W2B = PT * S2 * 1024;
+  static constexpr int WAVE_FLOATS = 32 * CLS + H;
+  static constexpr size_t LDS = W1B + W2B + PT * 32 * 4 + 4 * WAVE_FLOATS * 4;
+};
+
+__device__ __forceinline__ float act_fn(float x, int act) {
+  return act == MOL_ACT_RELU ? fmaxf(x, 0.f) : x / (1.f + __expf(-x));
+}
+
+template <int K_U, int K_X, int D_P, int H>
+__global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
+  using S = MolShape<K_U, K_X, D_P, H>;
+  constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
+                CLS = S::CLS;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char *w1s = smem;
+  char *w2s = smem + S::W1B;
+  float *b2s = reinterpret_cast<float *>(smem + S::W1B + S::W2B);
+  const int wv = threadIdx.x >> 6;
+  float *cl = b2s + PT * 32 + wv * S::WAVE_FLOATS;  // [32][CLS]
+  float *Us = cl + 32 * CLS;                        // [H]
+
+  // stage the weight fragments once per workgroup
+  for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
+    reinterpret_cast<uint4 *>(w1s)[i] = reinterpret_cast<const uint4 *>(a.w1c_frag)[i];
+  for (int i = threadIdx.x; i < S::W2B / 16; i += 256)
+    reinterpret_cast<uint4 *>(w2s)[i] = reinterpret_cast<const uint4 *>(a.w2_frag)[i];
+  for (int i = threadIdx.x; i < PT * 32; i += 256) b2s[i] = a.b2[i];
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 31, h = lane >> 5;     // 32x32 tiles: candidate / half
+  const int r16 = lane & 15, g = lane >> 4;   // 16x16 tiles: row (or ku column) / k-group
+  const int64_t tpq = (a.Kp + 31) >> 5;       // tiles per query
+  const int64_t ntiles = tpq * a.B;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+
+  int cur_b = -1;
+  uint4 Ff[SA];
+  for (int64_t tile = wave; tile < ntiles; tile += nwaves) {
+    int b;
+    int64_t c0;
+    if (a.query_fastest) {
+      b = (int)(tile % a.B);
+      c0 = (tile / a.B) << 5;
+    } else {
+      b = (int)(tile / tpq);
+      c0 = (tile % tpq) << 5;
+    }
+    const int64_t cpos = c0 + c;
+    int idx = -1;
+    if (cpos < a.Kp) idx = a.cand ? a.cand[(size_t)b * a.Kp + cpos] : (int)cpos;
+    const bool ok = idx >= 0 && idx < a.N;
+    const int idxc = ok ? idx : 0;
+
+    if (b != cur_b) {
+      cur_b = b;
+#pragma unroll
+      for (int s = 0; s < SA; ++s)
+        Ff[s] = (r16 < K_U) ? ld16(a.F + ((size_t)(b * K_U + r16) * D_P + 32 * s + 8 * g) * 2) : make_uint4(0, 0, 0, 0);
+      for (int i = lane; i < H; i += 64) Us[i] = a.U[(size_t)b * H + i];
+    }
+
+    // item half of layer 1 for this lane's candidate: hidden units 32*mt + 8*q + 4*h + {0..3}
+    uint2 xi[MT][4];
+    {
+      const char *xp = a.xi + ((size_t)idxc * H + 4 * h) * 2;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xi[mt][q] = *reinterpret_cast<const uint2 *>(xp + (32 * mt + 8 * q) * 2);
+    }
+
+    // ---- A: component logits -> LDS tile --------------------------------------------------------------
+    constexpr int PD = RT < 8 ? RT : 8;
+    uint4 A[PD][SA];
+    auto load_rows = [&](uint4(&dst)[SA], int rt) {
+      const int ci = rt * CPR + r16 / K_X;
+      const int nidx = __shfl(idxc, ci);
+      const char *rowp = a.embs + (((size_t)nidx * K_X + (r16 % K_X)) * D_P + 8 * g) * 2;
+#pragma unroll
+      for (int s = 0; s < SA; ++s) dst[s] = ld16(rowp + 64 * s);
+    };
+#pragma unroll
+    for (int i = 0; i < PD; ++i) load_rows(A[i], i);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < SA; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[rt % PD][s]), as_bf16x8(Ff[s]), acc, 0, 0, 0);
+      if (rt + PD < RT) load_rows(A[rt % PD], rt + PD);
+      // acc[j]: row 4*g + j of the tile = (candidate rt*CPR + (4g+j)/K_X, kx (4g+j)%K_X); column ku = r16
+      if (r16 < K_U) {
+        if constexpr (K_X % 4 == 0) {
+          float4 v = make_float4(acc[0] * a.logit_scale, acc[1] * a.logit_scale, acc[2] * a.logit_scale,
+                                 acc[3] * a.logit_scale);
+          *reinterpret_cast<float4 *>(&cl[(rt * CPR + (4 * g) / K_X) * CLS + r16 * K_X + (4 * g) % K_X]) = v;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            cl[(rt * CPR + (4 * g + j) / K_X) * CLS + r16 * K_X + (4 * g + j) % K_X] = acc[j] * a.logit_scale;
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // ---- B: layer 1 (transposed): acc1[mt][j] = pre[h = 32mt + 8(j/4) + 4h + j%4][candidate c] ---------
+    f32x16 acc1[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc1[mt][j] = 0.f;
+#pragma unroll
+    for (int s = 0; s < S1; ++s) {
+      const float4 lo = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h]);
+      const float4 hi = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h + 4]);
+      const uint4 bf = make_uint4(pack_bf16x2(lo.x, lo.y), pack_bf16x2(lo.z, lo.w), pack_bf16x2(hi.x, hi.y),
+                                  pack_bf16x2(hi.z, hi.w));
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const uint4 af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bf), acc1[mt], 0, 0, 0);
+      }
+    }
+
+    // ---- C: activation, then layer 2 (transposed): acc2[pt][j] = z[p = 32pt + 8(j/4) + 4h + j%4][c] -----
+    f32x16 acc2[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc2[pt][j] = 0.f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int qq = 0; qq < 2; ++qq) {
+        float hid[8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int q = 2 * qq + t;
+          const float4 u4 = *reinterpret_cast<const float4 *>(&Us[32 * mt + 8 * q + 4 * h]);
+          const uint2 x = xi[mt][q];
+          hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x + bf16_bits_to_f32(x.x & 0xffffu), a.act);
+          hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y + bf16_bits_to_f32(x.x >> 16), a.act);
+          hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + bf16_bits_to_f32(x.y & 0xffffu), a.act);
+          hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + bf16_bits_to_f32(x.y >> 16), a.act);
+        }
+        const uint4 bf = make_uint4(pack_bf16x2(hid[0], hid[1]), pack_bf16x2(hid[2], hid[3]),
+                                    pack_bf16x2(hid[4], hid[5]), pack_bf16x2(hid[6], hid[7]));
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) {
+          const uint4 af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
+          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bf), acc2[pt], 0, 0, 0);
+        }
+      }
+    }
+
+    // ---- D: softmax over components and the weighted sum --------------------------------------------------
+    float m = -INFINITY;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (32 * pt + 8 * q < P) {  // P is a multiple of 16: a group of 8 is all valid or all padding
+          const float4 b4 = *reinterpret_cast<const float4 *>(&b2s[32 * pt + 8 * q + 4 * h]);
+          acc2[pt][4 * q + 0] += b4.x;
+          acc2[pt][4 * q + 1] += b4.y;
+          acc2[pt][4 * q + 2] += b4.z;
+          acc2[pt][4 * q + 3] += b4.w;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) m = fmaxf(m, acc2[pt][4 * q + i]);
+        }
+      }
+    m = fmaxf(m, __shfl_xor(m, 32));
+    float den = 0.f, num = 0.f;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (32 * pt + 8 * q < P) {
+          const float4 c4 = *reinterpret_cast<const float4 *>(&cl[c * CLS + 32 * pt + 8 * q + 4 * h]);
+          const float e0 = __expf(acc2[pt][4 * q + 0] - m), e1 = __expf(acc2[pt][4 * q + 1] - m),
+                      e2 = __expf(acc2[pt][4 * q + 2] - m), e3 = __expf(acc2[pt][4 * q + 3] - m);
+          den += (e0 + e1) + (e2 + e3);
+          num += (e0 * c4.x + e1 * c4.y) + (e2 * c4.z + e3 * c4.w);
+        }
+      }
+    den += __shfl_xor(den, 32);
+    num += __shfl_xor(num, 32);
+    if (h == 0 && cpos < a.Kp) a.scores[(size_t)b * a.Kp + cpos] = ok ? num / den : -INFINITY;
+    // the next tile overwrites the LDS logit tile: all lanes must be done reading it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
+__global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, int B, int H, int d_gu) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * H) return;
+  const int b = i / H, hh = i % H;
+  float acc = 0.f;
+  for (int j = 0; j < d_gu; ++j)
+    acc = fmaf(bf16_bits_to_f32(w1u[(size_t)hh * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+  U[i] = acc;
+}
+
+template <int K_U, int K_X, int D_P, int H>
+mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
+  using S = MolShape<K_U, K_X, D_P, H>;
+  auto kern = k_mol_score<K_U, K_X, D_P, H>;
+  static bool configured = false;
+  static int per_sm = 1, sm_count = 0;
+  if (!configured) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)S::LDS));
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, S::LDS));
+    if (per_sm < 1) per_sm = 1;
+    configured = true;
+  }
+  const int64_t ntiles = ((a.Kp + 31) / 32) * a.B;
+  int64_t grid = (int64_t)sm_count * per_sm;
+  const int64_t need = (ntiles + 3) / 4;
+  if (grid > need) grid = need;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), S::LDS, st, a);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
+
+}  // namespace
+
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, hipStream_t st) {
+  const int n = B * c->H;
+  hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
+                     static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
+
+bool mol_shape_supported(int k_u, int k_x, int d_p, int H);
+
+#define MOL_SHAPES(X) \
+  X(4, 4, 32, 32)     \
+  X(4, 4, 64, 64)     \
+  X(8, 4, 64, 128)    \
+  X(8, 8, 64, 128)    \
+  X(2, 8, 32, 64)     \
+  X(16, 1, 32, 32)    \
+  X(8, 2, 128, 96)
+
+bool mol_shape_supported(int k_u, int k_x, int d_p, int H) {
+#define X(KU, KX, DP, HH) \
+  if (k_u == KU && k_x == KX && d_p == DP && H == HH) return true;
+  MOL_SHAPES(X)
+#undef X
+  return false;
+}
+
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
+                              const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st) {
+  MolArgs a;
+  a.embs = static_cast<const char *>(c->embs);
+  a.xi = static_cast<const char *>(c->xi);
+  a.w1c_frag = static_cast<const char *>(c->w1c_frag);
+  a.w2_frag = static_cast<const char *>(c->w2_frag);
+  a.b2 = c->b2;
+  a.F = static_cast<const char *>(user_embs);
+  a.U = U;
+  a.cand = cand_idx;
+  a.scores = scores;
+  a.Kp = cand_idx ? Kp : c->N;
+  a.N = c->N;
+  a.B = B;
+  a.act = c->act;
+  a.logit_scale = c->logit_scale;
+  a.query_fastest = cand_idx ? 0 : 1;
+#define X(KU, KX, DP, HH) \
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_shape<KU, KX, DP, HH>(a, st);
+  MOL_SHAPES(X)
+#undef X
+  return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", c->k_u, c->k_x, c->d_p, c->H);
+}

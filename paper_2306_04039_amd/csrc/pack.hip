@@ -1,0 +1,237 @@
+// mol_corpus_pack: the item-side cache (Section 2.2; the loops marked cachable in Algorithm 1).
+//   * gating weights re-laid into the matrix-core fragment order the scoring kernel reads from LDS,
+//   * Xi[n, :] = W1x * item_gate[n] + b1 for every item, bf16 (the cached "item-side gating weights").
+#include <math.h>
+#include <stdlib.h>
+
+#include "common.hpp"
+
+bool mol_shape_supported(int k_u, int k_x, int d_p, int H);
+
+namespace {
+
+// One thread per output element of the fragment buffers and the small copies.
+__global__ void k_pack_weights(const uint16_t *W1, const uint16_t *W2, const float *b2, int P, int H, int d_gu,
+                               int d_gx, uint16_t *w1c_frag, uint16_t *w2_frag, uint16_t *w1u, uint16_t *w1x,
+                               float *b2p) {
+  const int d_in = P + d_gu + d_gx;
+  const int MT = H / 32, S1 = P / 16, PT = (P + 31) / 32, S2 = H / 16;
+  const int n1 = MT * S1 * 512, n2 = PT * S2 * 512, n3 = H * d_gu, n4 = H * d_gx, n5 = PT * 32;
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n1) {
+    // layer-1 cross part, A operand of a 32x32x16 product: lane l holds row l%32, k = 8*(l/32) + e
+    const int e = i & 7, l = (i >> 3) & 63, f = i >> 9;
+    const int mt = f / S1, s = f % S1;
+    w1c_frag[i] = W1[(size_t)(32 * mt + (l & 31)) * d_in + 16 * s + 8 * (l >> 5) + e];
+    return;
+  }
+  i -= n1;
+  if (i < n2) {
+    // layer-2 weights; k-slot (half, e) of k-step (mt, qq) is hidden unit 32mt + 16qq + 8*(e/4) + 4*half + e%4,
+    // which is where the layer-1 accumulators of the scoring kernel hold that unit
+    const int e = i & 7, l = (i >> 3) & 63, f = i >> 9;
+    const int pt = f / S2, s2 = f % S2;
+    const int mt = s2 >> 1, qq = s2 & 1;
+    const int p = 32 * pt + (l & 31);
+    const int hu = 32 * mt + 16 * qq + 8 * (e >> 2) + 4 * (l >> 5) + (e & 3);
+    w2_frag[i] = (p < P) ? W2[(size_t)p * H + hu] : (uint16_t)0;
+    return;
+  }
+  i -= n2;
+  if (i < n3) {
+    w1u[i] = W1[(size_t)(i / d_gu) * d_in + P + (i % d_gu)];
+    return;
+  }
+  i -= n3;
+  if (i < n4) {
+    w1x[i] = W1[(size_t)(i / d_gx) * d_in + P + d_gu + (i % d_gx)];
+    return;
+  }
+  i -= n4;
+  if (i < n5) b2p[i] = (b2 && i < P) ? b2[i] : 0.f;
+}
+
+// Xi^T[h, n] = W1x[h, :] . gx[n, :] + b1[h] on 32x32x16 MFMA: A = W1x rows (hidden units), B = item rows.
+// A wavefront takes 32 items; lane (c = lane%32, half) loads its item's row chunks once and walks the hidden tiles.
+template <int KS>  // d_gx / 16
+__global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const char *w1x, const float *b1,
+                                                         uint16_t *xi, int64_t N, int H) {
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 31, h = lane >> 5;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t ntiles = (N + 31) >> 5;
+  constexpr int DG = KS * 16;
+  for (int64_t tile = wave; tile < ntiles; tile += nwaves) {
+    int64_t n = tile * 32 + c;
+    const bool ok = n < N;
+    if (!ok) n = N - 1;
+    uint4 bfrag[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) bfrag[s] = ld16(gx + ((size_t)n * DG + 16 * s + 8 * h) * 2);
+    for (int mt = 0; mt < H / 32; ++mt) {
+      f32x16 acc;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const uint4 af = ld16(w1x + ((size_t)(32 * mt + c) * DG + 16 * s + 8 * h) * 2);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bfrag[s]), acc, 0, 0, 0);
+      }
+      if (ok) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int hu = 32 * mt + 8 * q + 4 * h;
+          float v[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = acc[4 * q + i] + (b1 ? b1[hu + i] : 0.f);
+          uint2 o = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          *reinterpret_cast<uint2 *>(xi + (size_t)n * H + hu) = o;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, const void *w1x, const float *b1,
+                                    hipStream_t st) {
+  int dev = 0, sms = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&sms, hipDeviceAttributeMultiprocessorCount, dev));
+  int64_t grid = (int64_t)sms * 4;
+  const int64_t need = ((c->N + 31) / 32 + 3) / 4;
+  if (grid > need) grid = need;
+  if (grid < 1) grid = 1;
+  const char *gx = static_cast<const char *>(item_gate);
+  const char *w = static_cast<const char *>(w1x);
+  uint16_t *xi = static_cast<uint16_t *>(c->xi);
+#define LAUNCH(KS)                                                                                              \
+  hipLaunchKernelGGL(k_item_gate_cache<KS>, dim3((unsigned)grid), dim3(256), 0, st, gx, w, b1, xi, c->N, c->H); \
+  break;
+  switch (c->d_gx / 16) {
+    case 1: LAUNCH(1)
+    case 2: LAUNCH(2)
+    case 4: LAUNCH(4)
+    case 6: LAUNCH(6)
+    case 8: LAUNCH(8)
+    case 16: LAUNCH(16)
+    default:
+      return mol_fail(MOL_EUNSUPPORTED, "d_gx=%d: supported widths are 16, 32, 64, 96, 128, 256", c->d_gx);
+  }
+#undef LAUNCH
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
+
+extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *stage1_items, const void *item_embs,
+                                        const void *item_gate, void *stream, mol_corpus_t **out) {
+  if (!cfg || !out) return mol_fail(MOL_EINVAL, "mol_corpus_pack: cfg and out must not be NULL");
+  if (!item_embs || !item_gate || !cfg->W1 || !cfg->W2)
+    return mol_fail(MOL_EINVAL, "mol_corpus_pack: item_embs, item_gate, W1 and W2 must not be NULL");
+  if (cfg->N < 1 || cfg->N >= (int64_t)1 << 31) return mol_fail(MOL_EINVAL, "N=%lld must be in [1, 2^31)", (long long)cfg->N);
+  if (cfg->d1 != 0 && cfg->d1 != 64) return mol_fail(MOL_EUNSUPPORTED, "d1=%d: the stage-1 kernels are built for d1 = 64", cfg->d1);
+  if (cfg->d1 != 0 && !stage1_items) return mol_fail(MOL_EINVAL, "stage1_items is NULL but d1 != 0");
+  if (cfg->stage1_dtype != MOL_F32 && cfg->stage1_dtype != MOL_BF16) return mol_fail(MOL_EINVAL, "bad stage1_dtype");
+  if (cfg->act != MOL_ACT_RELU && cfg->act != MOL_ACT_SILU) return mol_fail(MOL_EINVAL, "bad act");
+  if (!mol_shape_supported(cfg->k_u, cfg->k_x, cfg->d_p, cfg->H))
+    return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", cfg->k_u, cfg->k_x,
+                    cfg->d_p, cfg->H);
+  if (cfg->d_gu < 1 || cfg->d_gu > 1024) return mol_fail(MOL_EINVAL, "d_gu=%d out of range", cfg->d_gu);
+  switch (cfg->d_gx) {
+    case 16: case 32: case 64: case 96: case 128: case 256: break;
+    default: return mol_fail(MOL_EUNSUPPORTED, "d_gx=%d: supported widths are 16, 32, 64, 96, 128, 256", cfg->d_gx);
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  mol_corpus *c = static_cast<mol_corpus *>(calloc(1, sizeof(mol_corpus)));
+  if (!c) return mol_fail(MOL_ENOMEM, "host allocation failed");
+  c->N = cfg->N;
+  c->d1 = cfg->d1;
+  c->stage1_dtype = cfg->stage1_dtype;
+  c->k_u = cfg->k_u;
+  c->k_x = cfg->k_x;
+  c->d_p = cfg->d_p;
+  c->P = cfg->k_u * cfg->k_x;
+  c->d_gu = cfg->d_gu;
+  c->d_gx = cfg->d_gx;
+  c->H = cfg->H;
+  c->act = cfg->act;
+  c->logit_scale = cfg->logit_scale;
+  c->flags = cfg->flags;
+  hipGetDevice(&c->device);
+
+  const int P = c->P, H = c->H;
+  const int MT = H / 32, S1 = P / 16, PT = (P + 31) / 32, S2 = H / 16;
+  const size_t n1 = (size_t)MT * S1 * 512, n2 = (size_t)PT * S2 * 512, n3 = (size_t)H * c->d_gu,
+               n4 = (size_t)H * c->d_gx, n5 = (size_t)PT * 32;
+  void *w1x = nullptr;
+  mol_status_t rc = MOL_OK;
+#define ALLOC(ptr, bytes)                                                                                  \
+  if (rc == MOL_OK && hipMalloc(reinterpret_cast<void **>(&(ptr)), (bytes)) != hipSuccess) {               \
+    (void)hipGetLastError();                                                                               \
+    rc = mol_fail(MOL_ENOMEM, "hipMalloc of %zu bytes failed (%s)", (size_t)(bytes), #ptr);               \
+  }
+  ALLOC(c->w1c_frag, n1 * 2)
+  ALLOC(c->w2_frag, n2 * 2)
+  ALLOC(c->w1u, n3 * 2)
+  ALLOC(w1x, n4 * 2)
+  ALLOC(c->b2, n5 * 4)
+  ALLOC(c->xi, (size_t)c->N * H * 2)
+  void *s1copy = nullptr, *embcopy = nullptr;
+  const size_t s1_bytes = (size_t)c->N * c->d1 * (c->stage1_dtype == MOL_F32 ? 4 : 2);
+  const size_t emb_bytes = (size_t)c->N * c->k_x * c->d_p * 2;
+  if (c->d1 && !(cfg->flags & MOL_PACK_BORROW_STAGE1)) { ALLOC(s1copy, s1_bytes) }
+  if (!(cfg->flags & MOL_PACK_BORROW_EMBS)) { ALLOC(embcopy, emb_bytes) }
+#undef ALLOC
+  if (rc == MOL_OK) {
+    c->stage1 = s1copy ? s1copy : stage1_items;
+    c->own_stage1 = s1copy != nullptr;
+    c->embs = embcopy ? embcopy : item_embs;
+    c->own_embs = embcopy != nullptr;
+    hipError_t e = hipSuccess;
+    if (s1copy) e = hipMemcpyAsync(s1copy, stage1_items, s1_bytes, hipMemcpyDeviceToDevice, st);
+    if (e == hipSuccess && embcopy) e = hipMemcpyAsync(embcopy, item_embs, emb_bytes, hipMemcpyDeviceToDevice, st);
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "device copy failed: %s", hipGetErrorString(e));
+  }
+  if (rc == MOL_OK) {
+    const size_t total = n1 + n2 + n3 + n4 + n5;
+    hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(cfg->W1), static_cast<const uint16_t *>(cfg->W2), cfg->b2, P, H,
+                       c->d_gu, c->d_gx, static_cast<uint16_t *>(c->w1c_frag), static_cast<uint16_t *>(c->w2_frag),
+                       static_cast<uint16_t *>(c->w1u), static_cast<uint16_t *>(w1x), c->b2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "k_pack_weights: %s", hipGetErrorString(e));
+  }
+  if (rc == MOL_OK) rc = launch_item_gate_cache(c, item_gate, w1x, cfg->b1, st);
+  if (rc == MOL_OK) {
+    hipError_t e = hipStreamSynchronize(st);
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "pack kernels failed: %s", hipGetErrorString(e));
+  }
+  if (w1x) (void)hipFree(w1x);
+  if (rc != MOL_OK) {
+    c->stage1 = s1copy;
+    c->own_stage1 = s1copy != nullptr;
+    c->embs = embcopy;
+    c->own_embs = embcopy != nullptr;
+    mol_corpus_free(c);
+    return rc;
+  }
+  *out = c;
+  return MOL_OK;
+}
+
+extern "C" mol_status_t mol_corpus_free(mol_corpus_t *c) {
+  if (!c) return MOL_OK;
+  (void)hipDeviceSynchronize();
+  if (c->w1c_frag) (void)hipFree(c->w1c_frag);
+  if (c->w2_frag) (void)hipFree(c->w2_frag);
+  if (c->w1u) (void)hipFree(c->w1u);
+  if (c->b2) (void)hipFree(c->b2);
+  if (c->xi) (void)hipFree(c->xi);
+  if (c->own_stage1 && c->stage1) (void)hipFree(const_cast<void *>(c->stage1));
+  if (c->own_embs && c->embs) (void)hipFree(const_cast<void *>(c->embs));
+  free(c);
+  return MOL_OK;
+}

@@ -1,0 +1,91 @@
+// Final selection of stage 2 (Algorithm 1, last line): the k best of each query's scored candidates, returned
+// best first under (score descending, item index ascending).
+#include <math.h>
+
+#include "common.hpp"
+#include "select.hpp"
+
+namespace {
+
+#define TOPK_MAX 1024
+
+__global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scores, const int32_t *cand, int64_t Kp,
+                                                               int k, int32_t *out_idx, float *out_score) {
+  __shared__ SelectShared sh;
+  __shared__ uint32_t skey[TOPK_MAX];
+  __shared__ uint32_t sidx[TOPK_MAX];
+  __shared__ uint32_t nvalid_s;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float *sc = scores + (size_t)b * Kp;
+  const int32_t *ci = cand ? cand + (size_t)b * Kp : nullptr;
+  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
+    const int32_t id = ci ? ci[i] : (int32_t)i;
+    valid = id >= 0;
+    idx = (uint32_t)id;
+    key = f32_to_key(sc[i]);
+  };
+  // number of valid candidates
+  if (tid == 0) nvalid_s = 0;
+  __syncthreads();
+  uint32_t mine = 0;
+  for (int64_t i = tid; i < Kp; i += SELECT_THREADS) mine += (ci ? ci[i] >= 0 : true) ? 1u : 0u;
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor((int)mine, o);
+  if ((tid & 63) == 0 && mine) atomicAdd(&nvalid_s, mine);
+  __syncthreads();
+  const uint32_t nvalid = nvalid_s;
+  const uint32_t kk = nvalid < (uint32_t)k ? nvalid : (uint32_t)k;  // how many real results
+  for (int i = tid; i < TOPK_MAX; i += SELECT_THREADS) {
+    skey[i] = 0u;            // sorts last
+    sidx[i] = 0xffffffffu;
+  }
+  if (tid == 0) sh.out_count = 0;
+  __syncthreads();
+  if (kk > 0) {
+    block_select_kth<true>(get, Kp, kk, sh);
+    for (int64_t i = tid; i < Kp; i += SELECT_THREADS) {
+      uint32_t key, idx;
+      bool valid;
+      get(i, key, idx, valid);
+      if (valid && select_accept(key, idx, sh)) {
+        uint32_t slot = atomicAdd(&sh.out_count, 1u);
+        if (slot < TOPK_MAX) {
+          skey[slot] = key;
+          sidx[slot] = idx;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // bitonic sort of TOPK_MAX (key desc, idx asc); one element per thread
+  for (int size = 2; size <= TOPK_MAX; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      const int i = tid, j = tid ^ stride;
+      if (j > i) {
+        const uint32_t ki = skey[i], kj = skey[j], ii = sidx[i], ij = sidx[j];
+        const bool i_first = ki > kj || (ki == kj && ii < ij);  // i belongs before j in the final order
+        const bool up = ((i & size) == 0);
+        if (up ? !i_first : i_first) {
+          skey[i] = kj; skey[j] = ki;
+          sidx[i] = ij; sidx[j] = ii;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int i = tid; i < k; i += SELECT_THREADS) {
+    const bool real = (uint32_t)i < kk;
+    out_idx[(size_t)b * k + i] = real ? (int32_t)sidx[i] : -1;
+    out_score[(size_t)b * k + i] = real ? key_to_f32(skey[i]) : -INFINITY;
+  }
+}
+
+}  // namespace
+
+mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
+                               int32_t *out_idx, float *out_score, hipStream_t st) {
+  if (k > TOPK_MAX) return mol_fail(MOL_EUNSUPPORTED, "k=%d exceeds the supported maximum %d", k, TOPK_MAX);
+  hipLaunchKernelGGL(k_final_topk, dim3(B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, Kp, k, out_idx, out_score);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}

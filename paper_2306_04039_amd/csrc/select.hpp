@@ -1,0 +1,153 @@
+// Block-wide radix selection under the total order (key descending, index ascending).
+// One workgroup of SELECT_THREADS threads works on one list; the list stays in global memory (L2 resident)
+// and is re-read once per radix pass.  Used for: the sampled threshold of stage 1, the reduction of the
+// stage-1 survivors to K' candidates (Section 4.1.2), and the final top-k of stage 2 (Algorithm 1, last line).
+#pragma once
+#include "common.hpp"
+
+#define SELECT_THREADS 1024
+#define SELECT_BITS 11
+#define SELECT_BINS (1 << SELECT_BITS)
+
+struct SelectShared {
+  uint32_t hist[SELECT_BINS];
+  uint32_t chunk[64];
+  uint32_t red_min[SELECT_THREADS / WAVE];
+  uint32_t red_max[SELECT_THREADS / WAVE];
+  uint32_t prefix;     // bits decided so far
+  uint32_t krem;       // rank still to resolve inside the matching set
+  uint32_t kmin, kmax;
+  uint32_t kth_key;    // result: key of the K-th element
+  uint32_t idx_limit;  // result: ties with key == kth_key are accepted while idx <= idx_limit
+  uint32_t ties, out_count;
+};
+
+// One radix pass over `n` elements.  get(i, key, idx, valid).  Elements take part when `valid`, when
+// (sel_key == key) if USE_SEL, and when their `k` agrees with sh.prefix above bit `hi`.
+// DESC picks the K-th largest of k; otherwise K-th smallest.
+template <bool ON_IDX, class Get>
+__device__ void select_pass(Get get, int64_t n, int lo, int hi, SelectShared &sh) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < SELECT_BINS; i += SELECT_THREADS) sh.hist[i] = 0;
+  __syncthreads();
+  const uint32_t prefix = sh.prefix;
+  const uint32_t kth_key = sh.kth_key;
+  const int w = hi - lo + 1;
+  const uint32_t dmask = (1u << w) - 1u;
+  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
+    uint32_t key, idx;
+    bool valid;
+    get(i, key, idx, valid);
+    uint32_t k = key;
+    if (ON_IDX) {
+      valid = valid && key == kth_key;
+      k = ~idx;  // ascending index == descending ~index
+    }
+    bool match = (hi >= 31) ? true : ((k >> (hi + 1)) == (prefix >> (hi + 1)));
+    if (valid && match) atomicAdd(&sh.hist[(k >> lo) & dmask], 1u);
+  }
+  __syncthreads();
+  // locate the digit that holds rank krem counting from the largest digit
+  const int nb = 1 << w;
+  const int per = (nb + 63) / 64;  // bins per chunk (<= 32)
+  if (tid < 64) {
+    uint32_t s = 0;
+    int top = nb - 1 - tid * per;  // chunk tid covers digits top, top-1, ..., top-per+1
+    for (int j = 0; j < per; ++j) {
+      int d = top - j;
+      if (d >= 0) s += sh.hist[d];
+    }
+    sh.chunk[tid] = s;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t krem = sh.krem, acc = 0;
+    int c = 0;
+    while (c < 63 && acc + sh.chunk[c] < krem) acc += sh.chunk[c++];
+    int d = nb - 1 - c * per;
+    int stop = d - per + 1;
+    if (stop < 0) stop = 0;
+    while (d > stop && acc + sh.hist[d] < krem) acc += sh.hist[d--];
+    sh.krem = krem - acc;  // rank inside digit d
+    sh.prefix = prefix | ((uint32_t)d << lo);
+    sh.ties = sh.hist[d];
+  }
+  __syncthreads();
+}
+
+// Finds the K-th element (1 <= K <= number of valid elements) of the list.  On return sh.kth_key / sh.idx_limit
+// describe the accepted set { key > kth_key } U { key == kth_key and idx <= idx_limit }, which has exactly K members.
+// WITH_TIES = false skips the index stage (idx_limit = all ones): used when only the key value matters.
+template <bool WITH_TIES, class Get>
+__device__ void block_select_kth(Get get, int64_t n, uint32_t K, SelectShared &sh) {
+  const int tid = threadIdx.x;
+  // 1. range of the keys: bits above the highest differing bit are common and need no pass
+  uint32_t mn = 0xffffffffu, mx = 0u;
+  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
+    uint32_t key, idx;
+    bool valid;
+    get(i, key, idx, valid);
+    if (valid) {
+      mn = min(mn, key);
+      mx = max(mx, key);
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    mn = min(mn, (uint32_t)__shfl_xor((int)mn, o));
+    mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+  }
+  if ((tid & 63) == 0) {
+    sh.red_min[tid >> 6] = mn;
+    sh.red_max[tid >> 6] = mx;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int i = 1; i < SELECT_THREADS / WAVE; ++i) {
+      mn = min(mn, sh.red_min[i]);
+      mx = max(mx, sh.red_max[i]);
+    }
+    sh.kmin = mn;
+    sh.kmax = mx;
+    sh.krem = K;
+    uint32_t diff = mn ^ mx;
+    // common high bits stay in prefix
+    int hb = diff ? 31 - __clz(diff) : -1;
+    sh.prefix = (hb >= 31) ? 0u : (hb < 0 ? mx : (mx >> (hb + 1)) << (hb + 1));
+    sh.kth_key = 0;
+    sh.idx_limit = 0xffffffffu;
+    sh.ties = 0;
+  }
+  __syncthreads();
+  {
+    uint32_t diff = sh.kmin ^ sh.kmax;
+    int hi = diff ? 31 - __clz(diff) : -1;
+    while (hi >= 0) {
+      int lo = hi - (SELECT_BITS - 1);
+      if (lo < 0) lo = 0;
+      select_pass<false>(get, n, lo, hi, sh);
+      hi = lo - 1;
+    }
+  }
+  if (tid == 0) sh.kth_key = sh.prefix;
+  __syncthreads();
+  if (!WITH_TIES) return;
+  // 2. ties at the K-th key: keep the krem smallest indices among them
+  //    (when the keys were all equal no pass ran and `ties` is not known: always resolve by index then)
+  const bool all_equal = (sh.kmin == sh.kmax);
+  if (!all_equal && sh.krem == sh.ties) return;  // every tie is accepted
+  __syncthreads();
+  if (tid == 0) sh.prefix = 0;
+  __syncthreads();
+  for (int hi = 31; hi >= 0;) {
+    int lo = hi - (SELECT_BITS - 1);
+    if (lo < 0) lo = 0;
+    select_pass<true>(get, n, lo, hi, sh);
+    hi = lo - 1;
+  }
+  if (tid == 0) sh.idx_limit = ~sh.prefix;
+  __syncthreads();
+}
+
+__device__ __forceinline__ bool select_accept(uint32_t key, uint32_t idx, const SelectShared &sh) {
+  return key > sh.kth_key || (key == sh.kth_key && idx <= sh.idx_limit);
+}

@@ -1,0 +1,383 @@
+// Stage 1, h-indexer (Section 4.1, Algorithm 2): sampled threshold, streaming corpus scan fused with the
+// strict threshold filter, and the reduction of the survivors to K' candidates.
+//
+// The scan is a skinny GEMM (32*NQG queries x N items x d1) that is bound by reading the item table once
+// (Section 4.1.1: arithmetic intensity ~ 2B/byteW).  Each wavefront owns tiles of 32 consecutive rows:
+// it loads them straight into the matrix-core operand layout (lane = row, 16 bytes of the row per load), keeps
+// the query fragments in registers for the whole kernel, accumulates in fp32 on MFMA and compares the 32x32
+// score tile against the per-query thresholds in registers.  Only survivors are written (index + score key),
+// so no N-length score vector ever reaches HBM.
+#include <math.h>
+
+#include "common.hpp"
+#include "select.hpp"
+
+namespace {
+
+enum { EPI_FILTER = 0, EPI_KEYS = 1 };
+
+struct ScanArgs {
+  const char *X;         // item table, row-major, ROWB bytes per row
+  int64_t n_rows;        // rows to score (N, or lambda for the gathered sample)
+  const int32_t *rows;   // GATHER: row numbers into X
+  int64_t x_rows;        // GATHER: number of rows of X (row numbers are clamped into range)
+  const char *Q;         // queries, row-major, same dtype / width as X
+  int B;                 // total number of queries
+  int qbase;             // first query handled by this launch
+  const float *thr;      // FILTER: per-query threshold (strict >)
+  uint32_t *count;       // FILTER: per-query survivor counters
+  uint2 *surv;           // FILTER: [B][cap] (key, idx)
+  int64_t cap;
+  uint32_t *skeys;       // KEYS: [B][skeys_stride] score keys
+  int64_t skeys_stride;
+};
+
+// F32 = false: bf16 rows of 64 (128 B), 4 x 16-byte chunks per lane, one 32x32x16 MFMA per chunk.
+// F32 = true : fp32 rows of 64 (256 B), 8 x 16-byte chunks per lane, four 32x32x2 MFMAs per chunk.
+// Lane (r = lane%32, h = lane/32) takes chunks 2*ci + h of row r; the query operand uses the same chunk
+// numbering, so the contraction pairs equal positions whatever order the hardware walks them in.
+template <bool F32, int NQG, int EPI, bool GATHER, int DEPTH>
+__global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
+  constexpr int NCH = F32 ? 8 : 4;
+  constexpr int ROWB = F32 ? 256 : 128;
+  const int lane = threadIdx.x & 63;
+  const int r = lane & 31, h = lane >> 5;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t ntiles = (a.n_rows + 31) >> 5;
+
+  uint4 q[NQG][NCH];
+  float thr[NQG];
+#pragma unroll
+  for (int g = 0; g < NQG; ++g) {
+    const int b = a.qbase + 32 * g + r;
+#pragma unroll
+    for (int ci = 0; ci < NCH; ++ci)
+      q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
+    thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
+  }
+
+  auto load_tile = [&](uint4(&dst)[NCH], int64_t tile) {
+    int64_t row = tile * 32 + r;
+    if (row >= a.n_rows) row = a.n_rows - 1;
+    if (GATHER) {
+      row = a.rows[row];
+      row = row < 0 ? 0 : (row >= a.x_rows ? a.x_rows - 1 : row);
+    }
+    const char *p = a.X + (size_t)row * ROWB + h * 16;
+#pragma unroll
+    for (int ci = 0; ci < NCH; ++ci) dst[ci] = ld16(p + ci * 32);
+  };
+
+  uint4 buf[DEPTH][NCH];
+#pragma unroll
+  for (int i = 0; i < DEPTH; ++i)
+    if (wave + i * nwaves < ntiles) load_tile(buf[i], wave + i * nwaves);
+
+  for (int64_t tile0 = wave; tile0 < ntiles; tile0 += DEPTH * nwaves) {
+#pragma unroll
+    for (int i = 0; i < DEPTH; ++i) {
+      const int64_t tile = tile0 + i * nwaves;
+      if (tile >= ntiles) break;
+      f32x16 acc[NQG];
+#pragma unroll
+      for (int g = 0; g < NQG; ++g)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[g][j] = 0.f;
+#pragma unroll
+      for (int ci = 0; ci < NCH; ++ci) {
+#pragma unroll
+        for (int g = 0; g < NQG; ++g) {
+          if constexpr (F32) {
+            const float av[4] = {__uint_as_float(buf[i][ci].x), __uint_as_float(buf[i][ci].y),
+                                 __uint_as_float(buf[i][ci].z), __uint_as_float(buf[i][ci].w)};
+            const float qv[4] = {__uint_as_float(q[g][ci].x), __uint_as_float(q[g][ci].y),
+                                 __uint_as_float(q[g][ci].z), __uint_as_float(q[g][ci].w)};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], qv[e], acc[g], 0, 0, 0);
+          } else {
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(buf[i][ci]), as_bf16x8(q[g][ci]), acc[g], 0,
+                                                             0, 0);
+          }
+        }
+      }
+      const int64_t tnext = tile + DEPTH * nwaves;
+      if (tnext < ntiles) load_tile(buf[i], tnext);
+
+      // acc[g][j]: item row 8*(j/4) + 4*h + j%4 of the tile, query qbase + 32*g + r
+      const int64_t row0 = tile * 32 + 4 * h;
+#pragma unroll
+      for (int g = 0; g < NQG; ++g) {
+        const int b = a.qbase + 32 * g + r;
+        if constexpr (EPI == EPI_FILTER) {
+          uint32_t mask = 0;
+#pragma unroll
+          for (int j = 0; j < 16; ++j) mask |= (acc[g][j] > thr[g]) ? (1u << j) : 0u;
+          if (mask) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
+              if (((mask >> j) & 1u) && n < a.n_rows) {
+                const uint32_t slot = atomicAdd(&a.count[b], 1u);
+                if ((int64_t)slot < a.cap) a.surv[(size_t)b * a.cap + slot] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
+              }
+            }
+          }
+        } else {
+          if (b < a.B) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+              uint4 kv = make_uint4(f32_to_key(acc[g][4 * qd]), f32_to_key(acc[g][4 * qd + 1]),
+                                    f32_to_key(acc[g][4 * qd + 2]), f32_to_key(acc[g][4 * qd + 3]));
+              *reinterpret_cast<uint4 *>(a.skeys + (size_t)b * a.skeys_stride + row0 + 8 * qd) = kv;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// i-th sampled row: floor(N * hi32(SplitMix64 output i) / 2^32), stream state = seed + (i+1) * golden gamma.
+__global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64_t N) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= lambda) return;
+  uint64_t z = seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  out[i] = (int32_t)(((z >> 32) * N) >> 32);
+}
+
+// Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement); resets the counters.
+__global__ __launch_bounds__(SELECT_THREADS) void k_sample_threshold(const uint32_t *skeys, int64_t stride,
+                                                                     int64_t lambda, uint32_t rank, float *thr,
+                                                                     uint32_t *count, uint32_t *flags) {
+  __shared__ SelectShared sh;
+  const int b = blockIdx.x;
+  const uint32_t *keys = skeys + (size_t)b * stride;
+  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
+    key = keys[i];
+    idx = (uint32_t)i;
+    valid = true;
+  };
+  block_select_kth<false>(get, lambda, rank, sh);
+  if (threadIdx.x == 0) {
+    thr[b] = key_to_f32(sh.kth_key);
+    count[b] = 0;
+    flags[b] = 0;
+  }
+}
+
+__global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    thr[b] = -INFINITY;
+    count[b] = 0;
+    flags[b] = 0;
+  }
+}
+
+// Survivors -> at most K' candidates (Section 4.1.2).  flags[b] is set to 1 when the survivor list cannot give
+// the answer (overflowed the buffer, or fewer than K' in exact mode); such a query is redone by the exact path.
+__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, int64_t cap,
+                                                                     const uint32_t *count, uint32_t *flags, int Kp,
+                                                                     int mode, bool only_flagged, int32_t *cand_idx,
+                                                                     float *cand_score, int32_t *cand_count) {
+  __shared__ SelectShared sh;
+  const int b = blockIdx.x;
+  const int tid = threadIdx.x;
+  if (only_flagged && flags[b] != 2u) return;  // 2 = survivor list rebuilt by the exact path
+  const uint32_t cnt = count[b];
+  const uint2 *list = surv + (size_t)b * cap;
+  int32_t *oi = cand_idx + (size_t)b * Kp;
+  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
+  const bool overflow = (int64_t)cnt > cap;
+  const bool underflow = (mode == MOL_HINDEXER_EXACT) && cnt < (uint32_t)Kp;
+  if (overflow || underflow) {
+    if (tid == 0) {
+      flags[b] = only_flagged ? 3u : 1u;  // 3 = even the exact path could not fit (pathological ties)
+      cand_count[b] = -1;
+    }
+    for (int i = tid; i < Kp; i += SELECT_THREADS) {
+      oi[i] = -1;
+      if (os) os[i] = -INFINITY;
+    }
+    return;
+  }
+  const int64_t n = cnt;
+  if (n <= Kp) {
+    for (int64_t i = tid; i < Kp; i += SELECT_THREADS) {
+      if (i < n) {
+        uint2 e = list[i];
+        oi[i] = (int32_t)e.y;
+        if (os) os[i] = key_to_f32(e.x);
+      } else {
+        oi[i] = -1;
+        if (os) os[i] = -INFINITY;
+      }
+    }
+    if (tid == 0) {
+      cand_count[b] = (int32_t)n;
+      if (only_flagged) flags[b] = 0;
+    }
+    return;
+  }
+  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
+    uint2 e = list[i];
+    key = e.x;
+    idx = e.y;
+    valid = true;
+  };
+  block_select_kth<true>(get, n, (uint32_t)Kp, sh);
+  if (tid == 0) sh.out_count = 0;
+  __syncthreads();
+  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
+    uint2 e = list[i];
+    if (select_accept(e.x, e.y, sh)) {
+      uint32_t slot = atomicAdd(&sh.out_count, 1u);
+      if (slot < (uint32_t)Kp) {
+        oi[slot] = (int32_t)e.y;
+        if (os) os[slot] = key_to_f32(e.x);
+      }
+    }
+  }
+  if (tid == 0) {
+    cand_count[b] = Kp;
+    if (only_flagged) flags[b] = 0;
+  }
+}
+
+template <bool F32, int EPI, bool GATHER>
+mol_status_t launch_scan(const ScanArgs &a0, int B, hipStream_t st) {
+  static int sm_count = 0;
+  if (!sm_count) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
+  }
+  constexpr int DEPTH = F32 ? 2 : 4;
+  const int64_t ntiles = (a0.n_rows + 31) / 32;
+  for (int qb = 0; qb < B; qb += 128) {
+    ScanArgs a = a0;
+    a.qbase = qb;
+    const int rem = B - qb;
+    const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
+    void (*kern)(ScanArgs) = nqg == 4   ? k_stage1_scan<F32, 4, EPI, GATHER, DEPTH>
+                             : nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH>
+                                        : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>;
+    int per_sm = 0;
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, 0));
+    if (per_sm < 1) per_sm = 1;
+    if (per_sm > 4) per_sm = 4;
+    int64_t grid = (int64_t)sm_count * per_sm;
+    const int64_t need = (ntiles + 3) / 4;
+    if (grid > need) grid = need;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), 0, st, a);
+    HIP_TRY(hipGetLastError());
+  }
+  return MOL_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------ host
+mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, int mode, HindexerPlan *p) {
+  const int64_t N = c->N;
+  p->sampling = (4 * (int64_t)Kp < N);
+  if (lambda <= 0) lambda = hindexer_default_lambda(c, Kp);
+  if (lambda > N) lambda = N;
+  if (lambda < 1) lambda = 1;
+  p->lambda = p->sampling ? lambda : 0;
+  int64_t r_paper = ((int64_t)Kp * lambda) / N;
+  if (r_paper < 1) r_paper = 1;
+  int64_t rank = r_paper;
+  if (mode == MOL_HINDEXER_EXACT) rank = r_paper + (int64_t)ceil(5.0 * sqrt((double)r_paper)) + 8;
+  if (rank > lambda) rank = lambda;
+  p->rank = rank;
+  if (p->sampling) {
+    const double expect = (double)N * (double)rank / (double)lambda;
+    int64_t cap = (int64_t)(expect * (1.0 + 6.0 / sqrt((double)rank))) + 1024;
+    if (cap < (int64_t)Kp + 1024) cap = (int64_t)Kp + 1024;
+    if (cap > N) cap = N;
+    p->cap = cap;
+  } else {
+    p->cap = N;
+  }
+  const int64_t lam_pad = (p->lambda + 31) / 32 * 32;
+  size_t off = 0;
+  p->off_sample = off;
+  off = align_up(off + (size_t)lam_pad * 4, 256);
+  p->off_skeys = off;
+  off = align_up(off + (size_t)B * lam_pad * 4, 256);
+  p->off_thr = off;
+  off = align_up(off + (size_t)B * 4, 256);
+  p->off_count = off;
+  off = align_up(off + (size_t)B * 4, 256);
+  p->off_flags = off;
+  off = align_up(off + (size_t)B * 4, 256);
+  p->off_surv = off;
+  off = align_up(off + (size_t)B * p->cap * 8, 256);
+  p->off_hist = off;
+  off = align_up(off + (size_t)B * SELECT_BINS * 4, 256);
+  p->off_state = off;
+  off = align_up(off + (size_t)B * 16, 256);
+  p->total = off;
+  return MOL_OK;
+}
+
+mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
+                          uint64_t seed, int mode, const HindexerPlan &p, int32_t *cand_idx, float *cand_score,
+                          int32_t *cand_count, char *ws, hipStream_t st) {
+  const bool f32 = (c->stage1_dtype == MOL_F32);
+  float *thr = reinterpret_cast<float *>(ws + p.off_thr);
+  uint32_t *count = reinterpret_cast<uint32_t *>(ws + p.off_count);
+  uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
+  uint2 *surv = reinterpret_cast<uint2 *>(ws + p.off_surv);
+
+  ScanArgs a = {};
+  a.X = static_cast<const char *>(c->stage1);
+  a.Q = static_cast<const char *>(q1);
+  a.B = B;
+  a.thr = thr;
+  a.count = count;
+  a.surv = surv;
+  a.cap = p.cap;
+
+  if (p.sampling) {
+    int32_t *samp = reinterpret_cast<int32_t *>(ws + p.off_sample);
+    uint32_t *skeys = reinterpret_cast<uint32_t *>(ws + p.off_skeys);
+    const int64_t lam_pad = (p.lambda + 31) / 32 * 32;
+    const int32_t *rows = sample_idx;
+    if (!rows) {
+      hipLaunchKernelGGL(k_gen_sample, dim3((unsigned)((p.lambda + 255) / 256)), dim3(256), 0, st, samp, p.lambda,
+                         seed, (uint64_t)c->N);
+      HIP_TRY(hipGetLastError());
+      rows = samp;
+    }
+    ScanArgs s = a;
+    s.n_rows = p.lambda;
+    s.rows = rows;
+    s.x_rows = c->N;
+    s.skeys = skeys;
+    s.skeys_stride = lam_pad;
+    mol_status_t rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, st) : launch_scan<false, EPI_KEYS, true>(s, B, st);
+    if (rc != MOL_OK) return rc;
+    hipLaunchKernelGGL(k_sample_threshold, dim3(B), dim3(SELECT_THREADS), 0, st, skeys, lam_pad, p.lambda,
+                       (uint32_t)p.rank, thr, count, flags);
+    HIP_TRY(hipGetLastError());
+  } else {
+    hipLaunchKernelGGL(k_init_all_pass, dim3((B + 255) / 256), dim3(256), 0, st, thr, count, flags, B);
+    HIP_TRY(hipGetLastError());
+  }
+
+  a.n_rows = c->N;
+  mol_status_t rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, st) : launch_scan<false, EPI_FILTER, false>(a, B, st);
+  if (rc != MOL_OK) return rc;
+
+  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, Kp, mode,
+                     false, cand_idx, cand_score, cand_count);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}

@@ -1,0 +1,270 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import retrieval_oracle as orc
+from parity_util import assert_scores_close, assert_sorted_desc, assert_topk_set, bits
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def m():
+    import paper_2306_04039_amd as lib
+    return lib
+
+
+def make(wl):
+    cen = synth.make_centres(wl, DEV)
+    items = synth.make_items(wl, cen)
+    q = synth.make_queries(wl, cen)
+    gw = synth.make_gate_weights(wl, DEV)
+    return items, q, gw
+
+
+def pack(wl, items, gw, borrow=False):
+    return m().mol_corpus_pack(items["x1"], items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                               logit_scale=wl.logit_scale, act=wl.act, borrow=borrow)
+
+
+def oracle_model(wl, items, gw):
+    return orc.MolModel(bits(items["G"]), bits(items["gx"]), bits(gw.W1), bits(gw.b1), bits(gw.W2), bits(gw.b2),
+                        wl.logit_scale, wl.act)
+
+
+S1_TOL = 2e-6   # fp32 accumulation of 64 products of magnitude <= 1 vs fp64
+
+
+# ------------------------------------------------------------------------------------------ stage 1
+@pytest.mark.parametrize("dtype,N,B,Kp", [
+    ("bf16", 50_003, 20, 512),      # ragged N (last tile partial), B not a multiple of 32
+    ("f32", 40_001, 16, 1024),
+    ("bf16", 70_000, 70, 300),      # three query groups -> NQG = 4 with padding
+    ("bf16", 33_000, 130, 200),     # two launches over the query dimension
+])
+def test_hindexer_exact_mode_matches_exact_topk(dtype, N, B, Kp):
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype=dtype, n_clusters=64)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], Kp, mode=m().HINDEXER_EXACT, seed=5)
+    torch.cuda.synchronize()
+    s = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    ci, cs, cc = ci.cpu().numpy(), cs.cpu().numpy(), cc.cpu().numpy()
+    assert np.all(cc == Kp)
+    for b in range(B):
+        rec = assert_topk_set(ci[b], s[b], Kp, S1_TOL, f"query {b}")
+        assert rec > 0.99
+        np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=S1_TOL)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_hindexer_paper_mode_matches_algorithm2(dtype):
+    N, B, Kp, lam = 60_000, 12, 600, 6000
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype=dtype, n_clusters=64)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    S = orc.sample_indices(1234, lam, N)
+    ref = orc.hindexer(bits(q["q1"]), bits(items["x1"]), Kp, S, truncate=True)
+    s = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    # (a) explicit sample handed in; (b) the library draws the same sample from the seed
+    outs = [m().hindexer_topk(corpus, q["q1"], Kp, mode=m().HINDEXER_PAPER,
+                              sample_idx=torch.from_numpy(S.astype(np.int32)).to(DEV)),
+            m().hindexer_topk(corpus, q["q1"], Kp, lam=lam, seed=1234, mode=m().HINDEXER_PAPER)]
+    torch.cuda.synchronize()
+    sets = []
+    for ci, cs, cc in outs:
+        ci, cs, cc = ci.cpu().numpy(), cs.cpu().numpy(), cc.cpu().numpy()
+        per_query = []
+        for b in range(B):
+            ids, sc, t = ref[b]
+            got = ci[b, : cc[b]]
+            assert np.all(ci[b, cc[b]:] == -1) and np.all(np.isneginf(cs[b, cc[b]:]))
+            assert len(set(got.tolist())) == len(got)
+            # the survivors are {s > t}: anything the two sides disagree on must sit within tolerance of t
+            # (or of the K'-th score when the list was cut to K')
+            edge = t if len(ids) < Kp else min(sc[-1], 1e9)
+            for n in set(got.tolist()) ^ set(ids.tolist()):
+                assert abs(s[b, n] - edge) <= S1_TOL or abs(s[b, n] - t) <= S1_TOL, (b, n, s[b, n], t, edge)
+            assert abs(len(got) - len(ids)) <= 2
+            np.testing.assert_allclose(cs[b, : cc[b]], s[b, got], rtol=0, atol=S1_TOL)
+            per_query.append(frozenset(got.tolist()))
+        sets.append(per_query)
+    assert sets[0] == sets[1], "library sampler differs from the documented SplitMix64 sample"
+
+
+def test_hindexer_without_sampling_and_all_items():
+    """4*K' >= N: no sampling, every item passes the filter, exact top-K'.  K' = N returns the whole corpus."""
+    N, B = 3000, 5
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=1000, n_clusters=16)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    s = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    for Kp in (1000, N):
+        ci, cs, cc = m().hindexer_topk(corpus, q["q1"], Kp)
+        torch.cuda.synchronize()
+        ci, cc = ci.cpu().numpy(), cc.cpu().numpy()
+        assert np.all(cc == Kp)
+        for b in range(B):
+            assert_topk_set(ci[b], s[b], Kp, S1_TOL, f"Kp={Kp} query {b}")
+
+
+def test_hindexer_is_deterministic_as_a_set_and_batch_split_invariant():
+    wl = synth.CONFIGS["C2"].replace(N=40_000, B=9, Kp=400, n_clusters=32)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    a = m().hindexer_topk(corpus, q["q1"], 400, seed=3)[0].cpu().numpy()
+    b = m().hindexer_topk(corpus, q["q1"], 400, seed=3)[0].cpu().numpy()
+    for i in range(9):
+        assert set(a[i].tolist()) == set(b[i].tolist())
+        one = m().hindexer_topk(corpus, q["q1"][i:i + 1].contiguous(), 400, seed=99)[0].cpu().numpy()
+        assert set(one[0].tolist()) == set(a[i].tolist())      # exact mode: independent of sample and batch
+
+
+# ------------------------------------------------------------------------------------------ stage 2
+SHAPES = {
+    "C1": dict(k_u=4, k_x=4, d_p=32, H=32, d_gu=32, d_gx=32),
+    "C2": dict(k_u=4, k_x=4, d_p=64, H=64, d_gu=64, d_gx=64),
+    "C3": dict(k_u=8, k_x=4, d_p=64, H=128, d_gu=128, d_gx=128),
+    "C4": dict(k_u=8, k_x=8, d_p=64, H=128, d_gu=128, d_gx=128),
+    "odd-kx8": dict(k_u=2, k_x=8, d_p=32, H=64, d_gu=48, d_gx=16),
+    "odd-kx1": dict(k_u=16, k_x=1, d_p=32, H=32, d_gu=32, d_gx=32),
+    "odd-h96": dict(k_u=8, k_x=2, d_p=128, H=96, d_gu=20, d_gx=96),
+}
+
+
+@pytest.mark.parametrize("shape", list(SHAPES))
+@pytest.mark.parametrize("scale,act", [(1.0, "relu"), (20.0, "relu"), (0.05, "silu")])
+def test_mol_score_matches_oracle(shape, scale, act):
+    N, B, Kp = 9000, 7, 1001                       # 1001: several 32-candidate tiles and a ragged tail
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, n_clusters=32, logit_scale=scale, act=act, bias_scale=0.2,
+                                     **SHAPES[shape])
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(7)
+    cand = torch.randint(0, N, (B, Kp), generator=g, dtype=torch.int32)
+    cand[:, :40] = torch.arange(40, dtype=torch.int32)            # consecutive rows too
+    cand[1, 5::7] = -1                                            # padding scattered in one query
+    cand[2, 900:] = -1                                            # padded tail
+    got = m().mol_score(corpus, q["F"], q["gu"], cand.to(DEV))
+    torch.cuda.synchronize()
+    ref = orc.mol_scores(oracle_model(wl, items, gw), bits(q["F"]), bits(q["gu"]), cand.numpy())
+    assert_scores_close(got.cpu().numpy(), ref, scale, f"{shape} scale={scale} act={act}")
+
+
+def test_mol_score_same_cluster_candidates_and_invariants():
+    """Candidates from the query's own cluster (logits near 1) and the convex-combination bound."""
+    wl = synth.CONFIGS["C4"].replace(N=6000, B=4, Kp=256, n_clusters=4, bias_scale=0.1)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    cand = torch.arange(256, dtype=torch.int32).repeat(4, 1)
+    got = m().mol_score(corpus, q["F"], q["gu"], cand.to(DEV)).cpu().numpy()
+    ref = orc.mol_scores(oracle_model(wl, items, gw), bits(q["F"]), bits(q["gu"]), cand.numpy())
+    assert_scores_close(got, ref, 1.0, "same-cluster")
+    assert np.abs(ref).max() > 0.5                                    # the high-score regime is exercised
+    Ff, Gf = orc.as_f64(bits(q["F"])), orc.as_f64(bits(items["G"]))
+    for b in range(4):
+        cl = orc.component_logits(Ff[b], Gf[:256], 1.0)
+        assert np.all(got[b] <= cl.max(axis=1) + 1e-3) and np.all(got[b] >= cl.min(axis=1) - 1e-3)
+
+
+def test_mol_score_exhaustive_and_topk():
+    """cand_idx = NULL: every item for every query (the MoL-only model), then the k best."""
+    wl = synth.CONFIGS["C5"].replace(N=5003, B=37, k=50, n_clusters=16, bias_scale=0.1)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    got = m().mol_score(corpus, q["F"], q["gu"], None)
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], None, 50)
+    torch.cuda.synchronize()
+    ref = orc.mol_scores(oracle_model(wl, items, gw), bits(q["F"]), bits(q["gu"]), None)
+    assert_scores_close(got.cpu().numpy(), ref, 1.0, "exhaustive")
+    idx, sc, got = idx.cpu().numpy(), sc.cpu().numpy(), got.cpu().numpy()
+    for b in range(37):
+        tol = 2e-3 * abs(np.sort(ref[b])[::-1][49]) + 1e-4
+        assert_topk_set(idx[b], ref[b], 50, tol, f"query {b}")
+        assert_sorted_desc(sc[b], idx[b], f"query {b}")
+        assert np.array_equal(sc[b], got[b, idx[b]])                  # mol_topk reports mol_score's values
+        # exact agreement with the selection applied to the GPU's own scores
+        want = np.lexsort((np.arange(5003), -got[b].astype(np.float64)))[:50]
+        assert idx[b].tolist() == want.tolist()
+
+
+def test_mol_topk_with_padding_ties_and_short_lists():
+    wl = synth.CONFIGS["C2"].replace(N=2000, B=3, k=100, n_clusters=8)
+    items, q, gw = make(wl)
+    # duplicate item rows => exactly equal scores; the order must then be by ascending id
+    for key in ("G", "gx"):
+        items[key][1000:1100] = items[key][0:100]
+    corpus = pack(wl, items, gw)
+    cand = torch.full((3, 300), -1, dtype=torch.int32)
+    cand[0, :250] = torch.randperm(2000)[:250].to(torch.int32)
+    cand[0, :100] = torch.arange(100, dtype=torch.int32)
+    cand[0, 100:200] = torch.arange(1000, 1100, dtype=torch.int32)   # ties with the first hundred
+    cand[1, :60] = torch.randperm(2000)[:60].to(torch.int32)         # fewer valid candidates than k
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], cand.to(DEV), 100)
+    scores = m().mol_score(corpus, q["F"], q["gu"], cand.to(DEV)).cpu().numpy()
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
+    for b, nvalid in enumerate((250, 60, 0)):
+        kk = min(100, nvalid)
+        assert np.all(idx[b, kk:] == -1) and np.all(np.isneginf(sc[b, kk:]))
+        ids = cand[b, :nvalid].numpy()
+        want = np.lexsort((ids, -scores[b, :nvalid].astype(np.float64)))[:kk]
+        assert idx[b, :kk].tolist() == ids[want].tolist()
+        assert np.array_equal(sc[b, :kk], scores[b, :nvalid][want])
+    dup = scores[0, :100] == scores[0, 100:200]
+    assert dup.all(), "duplicated rows must score identically"
+
+
+# ------------------------------------------------------------------------------------------ end to end
+@pytest.mark.parametrize("cfg,N,B,Kp", [("C1", 100_000, 16, 1024), ("C2", 200_000, 24, 2048), ("C4", 120_000, 8, 3000)])
+def test_two_stage_matches_oracle(cfg, N, B, Kp):
+    wl = synth.CONFIGS[cfg].replace(N=N, B=B, Kp=Kp)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw, borrow=True)
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], Kp)
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], ci, wl.k)
+    torch.cuda.synchronize()
+    model = oracle_model(wl, items, gw)
+    s1 = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    ci, idx, sc = ci.cpu().numpy(), idx.cpu().numpy(), sc.cpu().numpy()
+    Ff, guf = orc.as_f64(bits(q["F"])), orc.as_f64(bits(q["gu"]))
+    for b in range(B):
+        assert_topk_set(ci[b], s1[b], Kp, S1_TOL, f"stage1 q{b}")
+        # stage 2 judged on the GPU's own candidate list (separates it from stage-1 boundary ties)
+        phi = orc.mol_scores_for(model, Ff[b], guf[b], ci[b])
+        lookup = dict(zip(ci[b].tolist(), phi.tolist()))
+        kth = np.sort(phi)[::-1][wl.k - 1]
+        assert_topk_set(idx[b], lookup, wl.k, 2e-3 * abs(kth) + 1e-4, f"stage2 q{b}")
+        assert_scores_close(sc[b], [lookup[i] for i in idx[b].tolist()], 1.0, f"stage2 scores q{b}")
+        assert_sorted_desc(sc[b], idx[b], f"q{b}")
+    # the cascade as a whole against the oracle's exact-first-stage cascade, on a few queries
+    ref = orc.two_stage(model, bits(q["q1"])[:4], bits(items["x1"]), bits(q["F"])[:4], bits(q["gu"])[:4], Kp, wl.k)
+    for b in range(4):
+        overlap = len(set(ref[b][0].tolist()) & set(idx[b].tolist())) / wl.k
+        assert overlap >= 0.9, f"q{b}: overlap with the oracle cascade {overlap}"
+
+
+# ------------------------------------------------------------------------------------------ errors
+def test_error_paths_return_status_and_leave_outputs_alone():
+    lib = m()
+    wl = synth.CONFIGS["C2"].replace(N=2000, B=4, Kp=100, n_clusters=8)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    with pytest.raises(lib.MolError) as e:
+        lib.hindexer_topk(corpus, q["q1"], 5000)                      # K' > N
+    assert e.value.status == -1
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    out = (torch.full((4, 100), 7, dtype=torch.int32, device=DEV), torch.zeros(4, 100, device=DEV),
+           torch.zeros(4, dtype=torch.int32, device=DEV))
+    with pytest.raises(lib.MolError) as e:
+        lib.hindexer_topk(corpus, q["q1"], 100, workspace=small, out=out)
+    assert e.value.status == -3 and int(out[0].min()) == 7
+    with pytest.raises(lib.MolError) as e:
+        lib.mol_topk(corpus, q["F"], q["gu"], out[0], 2000)           # k too large
+    assert e.value.status == -1
+    with pytest.raises(lib.MolError) as e:                            # shape with no kernel
+        lib.mol_corpus_pack(items["x1"], items["G"][:, :3].contiguous(), items["gx"], gw.W1[:, :-4].contiguous(),
+                            gw.b1, gw.W2[:12].contiguous(), gw.b2[:12].contiguous(), k_u=4)
+    assert e.value.status == -4
