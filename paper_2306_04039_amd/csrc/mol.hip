@@ -12,6 +12,9 @@
 //   D. softmax over the P components and phi = sum_p pi_p * cl_p (Eq. 3) with the fp32 logits from the LDS tile;
 //      each candidate's P values sit in two lanes (lane, lane^32).
 // Nothing but the final score is written to HBM (the fusion Section 4.2 argues for).
+// The weights are bf16 by contract; the activations that feed the matrix cores (logits, hidden units) are fp32
+// values, so each is split into a bf16 head and a bf16 remainder and multiplied twice: the gate then sees them
+// to ~16 mantissa bits, which keeps phi within 2e-3 of the fp64 definition even for large logit scales.
 #include <math.h>
 
 #include "common.hpp"
@@ -168,12 +171,16 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     for (int s = 0; s < S1; ++s) {
       const float4 lo = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h]);
       const float4 hi = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h + 4]);
-      const uint4 bf = make_uint4(pack_bf16x2(lo.x, lo.y), pack_bf16x2(lo.z, lo.w), pack_bf16x2(hi.x, hi.y),
-                                  pack_bf16x2(hi.z, hi.w));
+      uint4 bh, bl;
+      split_bf16x2(lo.x, lo.y, bh.x, bl.x);
+      split_bf16x2(lo.z, lo.w, bh.y, bl.y);
+      split_bf16x2(hi.x, hi.y, bh.z, bl.z);
+      split_bf16x2(hi.z, hi.w, bh.w, bl.w);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const uint4 af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
-        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bf), acc1[mt], 0, 0, 0);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bl), acc1[mt], 0, 0, 0);
+        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc1[mt], 0, 0, 0);
       }
     }
 
@@ -198,12 +205,16 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
           hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + bf16_bits_to_f32(x.y & 0xffffu), a.act);
           hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + bf16_bits_to_f32(x.y >> 16), a.act);
         }
-        const uint4 bf = make_uint4(pack_bf16x2(hid[0], hid[1]), pack_bf16x2(hid[2], hid[3]),
-                                    pack_bf16x2(hid[4], hid[5]), pack_bf16x2(hid[6], hid[7]));
+        uint4 bh, bl;
+        split_bf16x2(hid[0], hid[1], bh.x, bl.x);
+        split_bf16x2(hid[2], hid[3], bh.y, bl.y);
+        split_bf16x2(hid[4], hid[5], bh.z, bl.z);
+        split_bf16x2(hid[6], hid[7], bh.w, bl.w);
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
           const uint4 af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
-          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bf), acc2[pt], 0, 0, 0);
+          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bl), acc2[pt], 0, 0, 0);
+          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc2[pt], 0, 0, 0);
         }
       }
     }
