@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the two-stage retrieval hot path (h-indexer + MoL top-k) on one MI355X.
+
+One "step" = one query batch through the whole path: hindexer_topk (sample, threshold, corpus scan + filter,
+select K') followed by mol_topk (gather, component logits, gating, softmax, weighted sum, top-k).  All inputs
+(corpus cache, queries) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Default workload: the 100M-item configuration (N=1e8, B=32, K'=1e5, P=8x8, d_P=64, H=128, k=100), synthetic
+cluster-mixture data generated on the device.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# context only: the paper's serving latency for MoL + h-indexer on its (unnamed) production GPU, Section 5.3
+PAPER_CONTEXT = {"median_latency_ms_incl_batching_wait": 30.0, "hardware": "unnamed production GPU", "source": "Section 5.3"}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def build_workload(name, n_override):
+    import synth
+    wl = synth.CONFIGS[name]
+    if n_override:
+        wl = wl.replace(N=n_override, Kp=min(wl.Kp, max(1, n_override // 8)))
+    return wl
+
+
+def generate(wl, dev):
+    import torch
+    import synth
+    cen = synth.make_centres(wl, dev)
+    t0 = time.time()
+
+    def progress(i, n):
+        if i % 10 == 0 or i == n:
+            log(f"generated {i}/{n} item chunks ({time.time() - t0:.0f}s)")
+
+    items = synth.make_items(wl, cen, progress=progress)
+    q = synth.make_queries(wl, cen)
+    gw = synth.make_gate_weights(wl, dev)
+    torch.cuda.synchronize()
+    return items, q, gw
+
+
+def cpu_baseline(wl, items, q, gw, n_sub, kp_sub):
+    """The oracle, as it stands, on a bounded slice of the same workload; scaled linearly to the full batch."""
+    import numpy as np
+    import torch
+    from oracle import retrieval_oracle as orc
+
+    def bits(t):
+        t = t.detach().cpu().contiguous()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    B = wl.B
+    n_sub = min(n_sub, wl.N)
+    x1 = bits(items["x1"][:n_sub])
+    q1 = bits(q["q1"])
+    n_mol = min(n_sub, 200_000)               # MoL candidates of the slice are drawn from the first n_mol items
+    G = bits(items["G"][:n_mol])
+    gx = bits(items["gx_sub"][:n_mol])
+    kp_sub = min(kp_sub, wl.Kp, n_mol)
+    kp_stage1 = max(1, int(round(wl.Kp * n_sub / wl.N)))
+    t0 = time.perf_counter()
+    stage1 = orc.exact_topk_stage1(q1, x1, kp_stage1)            # fp64 scores of the slice + full sort per query
+    t1 = time.perf_counter()
+    model = orc.MolModel(G, gx, bits(gw.W1), bits(gw.b1), bits(gw.W2), bits(gw.b2), wl.logit_scale, wl.act)
+    rng = np.random.default_rng(0)
+    cand = rng.integers(0, n_mol, size=(B, kp_sub))
+    t2 = time.perf_counter()
+    orc.mol_topk(model, bits(q["F"]), bits(q["gu"]), cand, wl.k)
+    t3 = time.perf_counter()
+    del stage1
+    t_stage1_full = (t1 - t0) * (wl.N / n_sub)
+    t_mol_full = (t3 - t2) * (wl.Kp / kp_sub)
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    return {
+        "value": B / (t_stage1_full + t_mol_full),
+        "unit": "queries/s",
+        "cores": int(threads),
+        "kind": "oracle",
+        "sample": (f"all {B} queries; stage 1 (fp64 scores + full sort) on the first {n_sub} of {wl.N} items "
+                   f"({t1 - t0:.1f}s, scaled x{wl.N / n_sub:.1f}); MoL + top-k on {kp_sub} of {wl.Kp} candidates per query "
+                   f"({t3 - t2:.1f}s, scaled x{wl.Kp / kp_sub:.1f})"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--n-items", type=int, default=0, help="override N (debugging; the result is then not the named workload)")
+    ap.add_argument("--mode", type=int, default=0, help="0 = exact-on-success h-indexer (default), 1 = Algorithm 2 as written")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the retrieval path on ONE GPU only (the paper's inference path is single-GPU); "
+              "--gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2306_04039_amd as m
+
+    m.load_library()                      # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = build_workload(args.workload, args.n_items)
+    log(f"workload {wl.name}: N={wl.N} B={wl.B} K'={wl.Kp} P={wl.k_u}x{wl.k_x} d_P={wl.d_p} H={wl.H} k={wl.k}")
+
+    items, q, gw = generate(wl, dev)
+    t0 = time.time()
+    corpus = m.mol_corpus_pack(items["x1"], items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                               logit_scale=wl.logit_scale, act=wl.act, borrow=True)
+    log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
+    n_sub = min(wl.N, 2_000_000)
+    items["gx_sub"] = items["gx"][:n_sub].clone()
+    del items["gx"]                       # the raw item gate features are not needed after pack
+    torch.cuda.empty_cache()
+
+    B, Kp, k = wl.B, wl.Kp, wl.k
+    lam = m.hindexer_default_lambda(corpus, Kp)
+    ws1 = torch.empty(m.hindexer_workspace_bytes(corpus, B, Kp, lam), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(m.mol_workspace_bytes(corpus, B, Kp, k), dtype=torch.uint8, device=dev)
+    out1 = (torch.empty(B, Kp, dtype=torch.int32, device=dev), torch.empty(B, Kp, dtype=torch.float32, device=dev),
+            torch.empty(B, dtype=torch.int32, device=dev))
+    out2 = (torch.empty(B, k, dtype=torch.int32, device=dev), torch.empty(B, k, dtype=torch.float32, device=dev))
+
+    def step(i):
+        m.hindexer_topk(corpus, q["q1"], Kp, lam=lam, seed=1000 + i, mode=args.mode, workspace=ws1, out=out1)
+        m.mol_topk(corpus, q["F"], q["gu"], out1[0], k, workspace=ws2, out=out2)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    m.profile_read()
+    m.profile_enable(True)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    m.profile_enable(False)
+    prof = m.profile_read()
+    lat = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+    ms_per_step = wall * 1e3 / args.steps
+    counts = out1[2].cpu()
+    assert int(counts.min()) >= 0, "h-indexer reported a failed query"
+
+    scan_ms, scan_n = prof["scan_filter"]
+    scan_bytes = wl.N * wl.d1 * (4 if wl.stage1_dtype == "f32" else 2)
+    achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
+    mol_ms, mol_n = prof["mol_score"]
+    gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + wl.H * 2 + 4 + 4)
+    mol_flops = B * Kp * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
+
+    result = {
+        "metric": "queries/s + p50 batch latency, 100M-item h-indexer+MoL top-100, 1 GPU",
+        "value": B / (ms_per_step * 1e-3),
+        "unit": "queries/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "p50_batch_latency_ms": lat[len(lat) // 2],
+        "p95_batch_latency_ms": lat[min(len(lat) - 1, int(0.95 * len(lat)))],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.stage1_dtype != "f32" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, K'={Kp}, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}, "
+                               f"h-indexer mode {args.mode}, lambda={lam}"},
+        "roofline": {"kernel": "k_stage1_scan (corpus scan + threshold filter)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": scan_ms / max(1, scan_n), "launches": scan_n},
+        "kernels_ms_per_step": {name: v[0] / args.steps for name, v in prof.items() if v[1]},
+        "mol_stage": {"gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,
+                      "gather_frac_of_hbm_peak": (gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 / HBM_PEAK_GBS) if mol_n else 0.0,
+                      "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0},
+        "paper_context": PAPER_CONTEXT,
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a slice of the workload ...")
+        result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, n_sub, 4096)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

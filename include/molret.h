@@ -144,6 +144,25 @@ mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const v
                       const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/*
+ * Optional per-kernel timing, for benchmarks.  While enabled, every kernel launch of the calls above is bracketed by
+ * HIP events on the caller's stream (a few microseconds of overhead per launch).  mol_profile_read synchronises on
+ * the recorded events, adds up the elapsed time per slot since the last read and clears the record.
+ *   slot_ms, slot_launches : host arrays of MOL_PROF_SLOTS entries (either may be NULL).
+ */
+enum {
+  MOL_PROF_SAMPLE_SCORES = 0, /* stage 1: scores of the sampled rows */
+  MOL_PROF_THRESHOLD = 1,     /* stage 1: per-query sampled threshold */
+  MOL_PROF_SCAN_FILTER = 2,   /* stage 1: corpus scan + threshold filter */
+  MOL_PROF_SELECT = 3,        /* stage 1: survivors -> K' candidates (and the exact redo, when taken) */
+  MOL_PROF_USER_GATE = 4,     /* stage 2: user half of gating layer 1 */
+  MOL_PROF_MOL_SCORE = 5,     /* stage 2: fused gather + component logits + gating + softmax + sum */
+  MOL_PROF_FINAL_TOPK = 6,    /* stage 2: k best */
+  MOL_PROF_SLOTS = 8
+};
+mol_status_t mol_profile_enable(int on);
+mol_status_t mol_profile_read(double *slot_ms, int *slot_launches);
+
 /* Message for the last non-OK status returned on this thread (host string, valid until the next call). */
 const char *mol_last_error(void);
 

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     mol_score,
     mol_topk,
     mol_workspace_bytes,
+    profile_enable,
+    profile_read,
     HINDEXER_EXACT,
     HINDEXER_PAPER,
 )

@@ -20,7 +20,10 @@ _LIB = None
 EXPORTS = (
     "mol_corpus_pack", "mol_corpus_free", "hindexer_workspace_bytes", "mol_workspace_bytes",
     "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
+    "mol_profile_enable", "mol_profile_read",
 )
+
+PROF_SLOTS = ("sample_scores", "threshold", "scan_filter", "select", "user_gate", "mol_score", "final_topk", "spare")
 
 
 class MolError(RuntimeError):
@@ -69,6 +72,10 @@ def load_library() -> C.CDLL:
     lib.mol_score.restype = i32
     lib.mol_topk.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.mol_topk.restype = i32
+    lib.mol_profile_enable.argtypes = [i32]
+    lib.mol_profile_enable.restype = i32
+    lib.mol_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
+    lib.mol_profile_read.restype = i32
     lib.mol_last_error.argtypes = []
     lib.mol_last_error.restype = C.c_char_p
     _LIB = lib
@@ -250,3 +257,15 @@ def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, c
     _check(lib.mol_topk(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), Kp, k, _ptr(out[0]),
                         _ptr(out[1]), _ptr(ws), ws.numel(), _stream()))
     return out
+
+
+def profile_enable(on: bool) -> None:
+    _check(load_library().mol_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """{slot name: (total ms, launches)} of the kernels launched since the last read."""
+    ms = (C.c_double * len(PROF_SLOTS))()
+    n = (C.c_int * len(PROF_SLOTS))()
+    _check(load_library().mol_profile_read(ms, n))
+    return {name: (ms[i], n[i]) for i, name in enumerate(PROF_SLOTS)}

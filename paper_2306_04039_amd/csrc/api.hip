@@ -16,6 +16,87 @@ mol_status_t mol_fail(mol_status_t st, const char *fmt, ...) {
 
 extern "C" const char *mol_last_error(void) { return g_err; }
 
+// ------------------------------------------------------------------------------------------------ timing
+#include <mutex>
+#include <vector>
+namespace {
+struct ProfRec {
+  int slot;
+  hipEvent_t a, b;
+};
+struct Prof {
+  bool on = false;
+  std::mutex mu;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t open_ev[MOL_PROF_SLOTS] = {};
+  hipEvent_t get() {
+    if (!pool.empty()) {
+      hipEvent_t e = pool.back();
+      pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+} g_prof;
+}  // namespace
+
+void mol_prof_begin(int slot, hipStream_t st) {
+  if (!g_prof.on) return;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  hipEvent_t e = g_prof.get();
+  if (e) (void)hipEventRecord(e, st);
+  g_prof.open_ev[slot] = e;
+}
+
+void mol_prof_end(int slot, hipStream_t st) {
+  if (!g_prof.on) return;
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  hipEvent_t a = g_prof.open_ev[slot];
+  g_prof.open_ev[slot] = nullptr;
+  if (!a) return;
+  hipEvent_t b = g_prof.get();
+  if (!b) {
+    g_prof.pool.push_back(a);
+    return;
+  }
+  (void)hipEventRecord(b, st);
+  g_prof.recs.push_back({slot, a, b});
+}
+
+extern "C" mol_status_t mol_profile_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  g_prof.on = on != 0;
+  return MOL_OK;
+}
+
+extern "C" mol_status_t mol_profile_read(double *slot_ms, int *slot_launches) {
+  std::lock_guard<std::mutex> lk(g_prof.mu);
+  double ms[MOL_PROF_SLOTS] = {};
+  int n[MOL_PROF_SLOTS] = {};
+  mol_status_t rc = MOL_OK;
+  for (const ProfRec &r : g_prof.recs) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "profile event: %s", hipGetErrorString(e));
+    else {
+      ms[r.slot] += t;
+      n[r.slot] += 1;
+    }
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.recs.clear();
+  for (int i = 0; i < MOL_PROF_SLOTS; ++i) {
+    if (slot_ms) slot_ms[i] = ms[i];
+    if (slot_launches) slot_launches[i] = n[i];
+  }
+  return rc;
+}
+
 extern "C" int64_t hindexer_default_lambda(const mol_corpus_t *c, int Kp) {
   if (!c || Kp < 1) return 0;
   const int64_t N = c->N;

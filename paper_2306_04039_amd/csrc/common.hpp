@@ -81,6 +81,16 @@ mol_status_t mol_fail(mol_status_t st, const char *fmt, ...);
     if (e__ != hipSuccess) return mol_fail(MOL_EHIP, "%s: %s", #expr, hipGetErrorString(e__)); \
   } while (0)
 
+// per-kernel timing (api.hip): no-ops unless mol_profile_enable(1) was called
+void mol_prof_begin(int slot, hipStream_t st);
+void mol_prof_end(int slot, hipStream_t st);
+struct ProfScope {
+  int slot;
+  hipStream_t st;
+  ProfScope(int s, hipStream_t t) : slot(s), st(t) { mol_prof_begin(slot, st); }
+  ~ProfScope() { mol_prof_end(slot, st); }
+};
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- launchers implemented in the kernel files ------------------------------------------------
@@ -89,7 +99,7 @@ struct HindexerPlan {
   bool sampling;       // false: every item passes (threshold -inf)
   int64_t lambda;      // sample size actually used
   int64_t rank;        // threshold rank inside the sample (1-based from the largest)
-  int64_t cap;         // survivor capacity per query
+  int64_t cap;         // survivor capacity per (query, shard) list
   // workspace offsets (bytes)
   size_t off_sample, off_skeys, off_thr, off_count, off_flags, off_surv, off_hist, off_state, total;
 };

@@ -290,6 +290,7 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   const int64_t need = (ntiles + 3) / 4;
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
+  ProfScope ps(MOL_PROF_MOL_SCORE, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), S::LDS, st, a);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
@@ -299,6 +300,7 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
 
 mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, hipStream_t st) {
   const int n = B * c->H;
+  ProfScope ps(MOL_PROF_USER_GATE, st);
   hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
                      static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu);
   HIP_TRY(hipGetLastError());

@@ -19,11 +19,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
   const int tid = threadIdx.x;
   const float *sc = scores + (size_t)b * Kp;
   const int32_t *ci = cand ? cand + (size_t)b * Kp : nullptr;
-  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
-    const int32_t id = ci ? ci[i] : (int32_t)i;
-    valid = id >= 0;
-    idx = (uint32_t)id;
-    key = f32_to_key(sc[i]);
+  auto each = [&](auto f) {
+    block_for_each<4>(sc, Kp, [&](int64_t i, float v) {
+      const int32_t id = ci ? ci[i] : (int32_t)i;
+      if (id >= 0) f(f32_to_key(v), (uint32_t)id);
+    });
   };
   // number of valid candidates
   if (tid == 0) nvalid_s = 0;
@@ -42,19 +42,16 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
   if (tid == 0) sh.out_count = 0;
   __syncthreads();
   if (kk > 0) {
-    block_select_kth<true>(get, Kp, kk, sh);
-    for (int64_t i = tid; i < Kp; i += SELECT_THREADS) {
-      uint32_t key, idx;
-      bool valid;
-      get(i, key, idx, valid);
-      if (valid && select_accept(key, idx, sh)) {
+    block_select_kth<true>(each, kk, sh);
+    each([&](uint32_t key, uint32_t idx) {
+      if (select_accept(key, idx, sh)) {
         uint32_t slot = atomicAdd(&sh.out_count, 1u);
         if (slot < TOPK_MAX) {
           skey[slot] = key;
           sidx[slot] = idx;
         }
       }
-    }
+    });
   }
   __syncthreads();
   // bitonic sort of TOPK_MAX (key desc, idx asc); one element per thread
@@ -85,6 +82,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
 mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
                                int32_t *out_idx, float *out_score, hipStream_t st) {
   if (k > TOPK_MAX) return mol_fail(MOL_EUNSUPPORTED, "k=%d exceeds the supported maximum %d", k, TOPK_MAX);
+  ProfScope ps(MOL_PROF_FINAL_TOPK, st);
   hipLaunchKernelGGL(k_final_topk, dim3(B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, Kp, k, out_idx, out_score);
   HIP_TRY(hipGetLastError());
   return MOL_OK;

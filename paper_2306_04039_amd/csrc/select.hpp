@@ -22,11 +22,31 @@ struct SelectShared {
   uint32_t ties, out_count;
 };
 
-// One radix pass over `n` elements.  get(i, key, idx, valid).  Elements take part when `valid`, when
-// (sel_key == key) if USE_SEL, and when their `k` agrees with sh.prefix above bit `hi`.
-// DESC picks the K-th largest of k; otherwise K-th smallest.
-template <bool ON_IDX, class Get>
-__device__ void select_pass(Get get, int64_t n, int lo, int hi, SelectShared &sh) {
+// Walks p[0..n) with the whole block, U independent loads in flight per thread: f(i, p[i]).
+template <int U, class T, class F>
+__device__ __forceinline__ void block_for_each(const T *p, int64_t n, F f) {
+  for (int64_t base = threadIdx.x; base < n; base += (int64_t)U * SELECT_THREADS) {
+    T v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = base + (int64_t)u * SELECT_THREADS;
+      if (i < n) v[u] = p[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = base + (int64_t)u * SELECT_THREADS;
+      if (i < n) f(i, v[u]);
+    }
+  }
+}
+
+// The list is given as a callable `each(f)` that calls f(key, idx) for every element this thread owns (the block's
+// threads together cover the list exactly once; the same partition on every call is not required).
+//
+// One radix pass.  ON_IDX = false: digit of the key, among elements agreeing with sh.prefix above bit `hi`.
+// ON_IDX = true: digit of ~idx among the elements whose key equals sh.kth_key.
+template <bool ON_IDX, class Each>
+__device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
   const int tid = threadIdx.x;
   for (int i = tid; i < SELECT_BINS; i += SELECT_THREADS) sh.hist[i] = 0;
   __syncthreads();
@@ -34,18 +54,16 @@ __device__ void select_pass(Get get, int64_t n, int lo, int hi, SelectShared &sh
   const uint32_t kth_key = sh.kth_key;
   const int w = hi - lo + 1;
   const uint32_t dmask = (1u << w) - 1u;
-  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
-    uint32_t key, idx;
-    bool valid;
-    get(i, key, idx, valid);
+  each([&](uint32_t key, uint32_t idx) {
     uint32_t k = key;
+    bool valid = true;
     if (ON_IDX) {
-      valid = valid && key == kth_key;
+      valid = key == kth_key;
       k = ~idx;  // ascending index == descending ~index
     }
-    bool match = (hi >= 31) ? true : ((k >> (hi + 1)) == (prefix >> (hi + 1)));
+    const bool match = (hi >= 31) ? true : ((k >> (hi + 1)) == (prefix >> (hi + 1)));
     if (valid && match) atomicAdd(&sh.hist[(k >> lo) & dmask], 1u);
-  }
+  });
   __syncthreads();
   // locate the digit that holds rank krem counting from the largest digit
   const int nb = 1 << w;
@@ -78,20 +96,15 @@ __device__ void select_pass(Get get, int64_t n, int lo, int hi, SelectShared &sh
 // Finds the K-th element (1 <= K <= number of valid elements) of the list.  On return sh.kth_key / sh.idx_limit
 // describe the accepted set { key > kth_key } U { key == kth_key and idx <= idx_limit }, which has exactly K members.
 // WITH_TIES = false skips the index stage (idx_limit = all ones): used when only the key value matters.
-template <bool WITH_TIES, class Get>
-__device__ void block_select_kth(Get get, int64_t n, uint32_t K, SelectShared &sh) {
+template <bool WITH_TIES, class Each>
+__device__ void block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   const int tid = threadIdx.x;
   // 1. range of the keys: bits above the highest differing bit are common and need no pass
   uint32_t mn = 0xffffffffu, mx = 0u;
-  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
-    uint32_t key, idx;
-    bool valid;
-    get(i, key, idx, valid);
-    if (valid) {
-      mn = min(mn, key);
-      mx = max(mx, key);
-    }
-  }
+  each([&](uint32_t key, uint32_t) {
+    mn = min(mn, key);
+    mx = max(mx, key);
+  });
   for (int o = 32; o > 0; o >>= 1) {
     mn = min(mn, (uint32_t)__shfl_xor((int)mn, o));
     mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
@@ -124,7 +137,7 @@ __device__ void block_select_kth(Get get, int64_t n, uint32_t K, SelectShared &s
     while (hi >= 0) {
       int lo = hi - (SELECT_BITS - 1);
       if (lo < 0) lo = 0;
-      select_pass<false>(get, n, lo, hi, sh);
+      select_pass<false>(each, lo, hi, sh);
       hi = lo - 1;
     }
   }
@@ -141,7 +154,7 @@ __device__ void block_select_kth(Get get, int64_t n, uint32_t K, SelectShared &s
   for (int hi = 31; hi >= 0;) {
     int lo = hi - (SELECT_BITS - 1);
     if (lo < 0) lo = 0;
-    select_pass<true>(get, n, lo, hi, sh);
+    select_pass<true>(each, lo, hi, sh);
     hi = lo - 1;
   }
   if (tid == 0) sh.idx_limit = ~sh.prefix;

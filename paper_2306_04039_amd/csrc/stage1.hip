@@ -16,6 +16,13 @@ namespace {
 
 enum { EPI_FILTER = 0, EPI_KEYS = 1 };
 
+// Survivors of one query are appended to SHARDS independent lists, the list chosen by the tile number
+// (item index / 32) mod SHARDS.  Appending costs one returning atomic per survivor; atomics on one cache line
+// serialise in L2, so the counters are spread over B*SHARDS lines.  Which list an item lands in depends only on its
+// index, so each list is a deterministic set.
+#define SHARDS 16
+#define COUNT_STRIDE 64  // uint32 per counter slot (256 bytes)
+
 struct ScanArgs {
   const char *X;         // item table, row-major, ROWB bytes per row
   int64_t n_rows;        // rows to score (N, or lambda for the gathered sample)
@@ -25,9 +32,9 @@ struct ScanArgs {
   int B;                 // total number of queries
   int qbase;             // first query handled by this launch
   const float *thr;      // FILTER: per-query threshold (strict >)
-  uint32_t *count;       // FILTER: per-query survivor counters
-  uint2 *surv;           // FILTER: [B][cap] (key, idx)
-  int64_t cap;
+  uint32_t *count;       // FILTER: survivor counters, one per (query, shard), each on its own 256-byte line
+  uint2 *surv;           // FILTER: [B][SHARDS][cap_s] (key, idx)
+  int64_t cap_s;         // capacity of one shard
   uint32_t *skeys;       // KEYS: [B][skeys_stride] score keys
   int64_t skeys_stride;
 };
@@ -118,8 +125,10 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
             for (int j = 0; j < 16; ++j) {
               const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
               if (((mask >> j) & 1u) && n < a.n_rows) {
-                const uint32_t slot = atomicAdd(&a.count[b], 1u);
-                if ((int64_t)slot < a.cap) a.surv[(size_t)b * a.cap + slot] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
+                const int sh = (int)(tile & (SHARDS - 1));
+                const uint32_t slot = atomicAdd(&a.count[(size_t)(b * SHARDS + sh) * COUNT_STRIDE], 1u);
+                if ((int64_t)slot < a.cap_s)
+                  a.surv[((size_t)b * SHARDS + sh) * a.cap_s + slot] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
               }
             }
           }
@@ -156,44 +165,56 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_sample_threshold(const uint3
   __shared__ SelectShared sh;
   const int b = blockIdx.x;
   const uint32_t *keys = skeys + (size_t)b * stride;
-  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
-    key = keys[i];
-    idx = (uint32_t)i;
-    valid = true;
+  auto each = [&](auto f) {  // rows are 16-byte aligned (stride is a multiple of 32 keys)
+    const int64_t n4 = lambda >> 2;
+    block_for_each<4>(reinterpret_cast<const uint4 *>(keys), n4, [&](int64_t i, uint4 v) {
+      f(v.x, (uint32_t)(4 * i));
+      f(v.y, (uint32_t)(4 * i + 1));
+      f(v.z, (uint32_t)(4 * i + 2));
+      f(v.w, (uint32_t)(4 * i + 3));
+    });
+    for (int64_t i = 4 * n4 + threadIdx.x; i < lambda; i += SELECT_THREADS) f(keys[i], (uint32_t)i);
   };
-  block_select_kth<false>(get, lambda, rank, sh);
+  block_select_kth<false>(each, rank, sh);
   if (threadIdx.x == 0) {
     thr[b] = key_to_f32(sh.kth_key);
-    count[b] = 0;
     flags[b] = 0;
   }
+  if (threadIdx.x < SHARDS) count[(size_t)(b * SHARDS + threadIdx.x) * COUNT_STRIDE] = 0;
 }
 
 __global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, int B) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < B) {
-    thr[b] = -INFINITY;
-    count[b] = 0;
-    flags[b] = 0;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) {
+    thr[i] = -INFINITY;
+    flags[i] = 0;
   }
+  if (i < B * SHARDS) count[(size_t)i * COUNT_STRIDE] = 0;
 }
 
-// Survivors -> at most K' candidates (Section 4.1.2).  flags[b] is set to 1 when the survivor list cannot give
-// the answer (overflowed the buffer, or fewer than K' in exact mode); such a query is redone by the exact path.
-__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, int64_t cap,
+// Survivors -> at most K' candidates (Section 4.1.2).  flags[b] is set to 1 when the survivor lists cannot give
+// the answer (a list overflowed, or fewer than K' survived in exact mode); such a query is redone by the exact path.
+__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, int64_t cap_s,
                                                                      const uint32_t *count, uint32_t *flags, int Kp,
                                                                      int mode, bool only_flagged, int32_t *cand_idx,
                                                                      float *cand_score, int32_t *cand_count) {
   __shared__ SelectShared sh;
+  __shared__ uint32_t cnt_s[SHARDS];
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
-  if (only_flagged && flags[b] != 2u) return;  // 2 = survivor list rebuilt by the exact path
-  const uint32_t cnt = count[b];
-  const uint2 *list = surv + (size_t)b * cap;
+  if (only_flagged && flags[b] != 2u) return;  // 2 = survivor lists rebuilt by the exact path
+  if (tid < SHARDS) cnt_s[tid] = count[(size_t)(b * SHARDS + tid) * COUNT_STRIDE];
+  __syncthreads();
+  uint64_t total = 0;
+  bool overflow = false;
+  for (int i = 0; i < SHARDS; ++i) {
+    total += cnt_s[i];
+    overflow = overflow || (int64_t)cnt_s[i] > cap_s;
+  }
+  const uint2 *list = surv + (size_t)b * SHARDS * cap_s;
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
-  const bool overflow = (int64_t)cnt > cap;
-  const bool underflow = (mode == MOL_HINDEXER_EXACT) && cnt < (uint32_t)Kp;
+  const bool underflow = (mode == MOL_HINDEXER_EXACT) && total < (uint64_t)Kp;
   if (overflow || underflow) {
     if (tid == 0) {
       flags[b] = only_flagged ? 3u : 1u;  // 3 = even the exact path could not fit (pathological ties)
@@ -205,45 +226,32 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
     }
     return;
   }
-  const int64_t n = cnt;
-  if (n <= Kp) {
-    for (int64_t i = tid; i < Kp; i += SELECT_THREADS) {
-      if (i < n) {
-        uint2 e = list[i];
-        oi[i] = (int32_t)e.y;
-        if (os) os[i] = key_to_f32(e.x);
-      } else {
-        oi[i] = -1;
-        if (os) os[i] = -INFINITY;
-      }
+  auto each = [&](auto f) {
+    for (int s = 0; s < SHARDS; ++s) {
+      block_for_each<4>(list + (size_t)s * cap_s, (int64_t)cnt_s[s], [&](int64_t, uint2 e) { f(e.x, e.y); });
     }
-    if (tid == 0) {
-      cand_count[b] = (int32_t)n;
-      if (only_flagged) flags[b] = 0;
-    }
-    return;
-  }
-  auto get = [&](int64_t i, uint32_t &key, uint32_t &idx, bool &valid) {
-    uint2 e = list[i];
-    key = e.x;
-    idx = e.y;
-    valid = true;
   };
-  block_select_kth<true>(get, n, (uint32_t)Kp, sh);
+  const bool take_all = total <= (uint64_t)Kp;
+  if (!take_all) block_select_kth<true>(each, (uint32_t)Kp, sh);
   if (tid == 0) sh.out_count = 0;
   __syncthreads();
-  for (int64_t i = tid; i < n; i += SELECT_THREADS) {
-    uint2 e = list[i];
-    if (select_accept(e.x, e.y, sh)) {
+  each([&](uint32_t key, uint32_t idx) {
+    if (take_all || select_accept(key, idx, sh)) {
       uint32_t slot = atomicAdd(&sh.out_count, 1u);
       if (slot < (uint32_t)Kp) {
-        oi[slot] = (int32_t)e.y;
-        if (os) os[slot] = key_to_f32(e.x);
+        oi[slot] = (int32_t)idx;
+        if (os) os[slot] = key_to_f32(key);
       }
     }
+  });
+  __syncthreads();
+  const uint32_t nout = take_all ? (uint32_t)total : (uint32_t)Kp;
+  for (int64_t i = nout + tid; i < Kp; i += SELECT_THREADS) {
+    oi[i] = -1;
+    if (os) os[i] = -INFINITY;
   }
   if (tid == 0) {
-    cand_count[b] = Kp;
+    cand_count[b] = (int32_t)nout;
     if (only_flagged) flags[b] = 0;
   }
 }
@@ -296,14 +304,18 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   if (mode == MOL_HINDEXER_EXACT) rank = r_paper + (int64_t)ceil(5.0 * sqrt((double)r_paper)) + 8;
   if (rank > lambda) rank = lambda;
   p->rank = rank;
+  // rows that can land in one shard: tiles t with t % SHARDS == s, 32 rows each
+  const int64_t shard_rows = ((N + 31) / 32 + SHARDS - 1) / SHARDS * 32;
   if (p->sampling) {
     const double expect = (double)N * (double)rank / (double)lambda;
-    int64_t cap = (int64_t)(expect * (1.0 + 6.0 / sqrt((double)rank))) + 1024;
-    if (cap < (int64_t)Kp + 1024) cap = (int64_t)Kp + 1024;
-    if (cap > N) cap = N;
-    p->cap = cap;
+    double cap = expect * (1.0 + 6.0 / sqrt((double)rank)) + 1024;
+    if (cap < (double)Kp + 1024) cap = (double)Kp + 1024;
+    const double per = cap / SHARDS;
+    int64_t cap_s = (int64_t)(per + 6.0 * sqrt(per)) + 64;
+    if (cap_s > shard_rows) cap_s = shard_rows;
+    p->cap = cap_s;
   } else {
-    p->cap = N;
+    p->cap = shard_rows;
   }
   const int64_t lam_pad = (p->lambda + 31) / 32 * 32;
   size_t off = 0;
@@ -314,11 +326,11 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->off_thr = off;
   off = align_up(off + (size_t)B * 4, 256);
   p->off_count = off;
-  off = align_up(off + (size_t)B * 4, 256);
+  off = align_up(off + (size_t)B * SHARDS * COUNT_STRIDE * 4, 256);
   p->off_flags = off;
   off = align_up(off + (size_t)B * 4, 256);
   p->off_surv = off;
-  off = align_up(off + (size_t)B * p->cap * 8, 256);
+  off = align_up(off + (size_t)B * SHARDS * p->cap * 8, 256);
   p->off_hist = off;
   off = align_up(off + (size_t)B * SELECT_BINS * 4, 256);
   p->off_state = off;
@@ -343,7 +355,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   a.thr = thr;
   a.count = count;
   a.surv = surv;
-  a.cap = p.cap;
+  a.cap_s = p.cap;
 
   if (p.sampling) {
     int32_t *samp = reinterpret_cast<int32_t *>(ws + p.off_sample);
@@ -362,20 +374,30 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     s.x_rows = c->N;
     s.skeys = skeys;
     s.skeys_stride = lam_pad;
-    mol_status_t rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, st) : launch_scan<false, EPI_KEYS, true>(s, B, st);
+    mol_status_t rc;
+    {
+      ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
+      rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, st) : launch_scan<false, EPI_KEYS, true>(s, B, st);
+    }
     if (rc != MOL_OK) return rc;
+    ProfScope ps(MOL_PROF_THRESHOLD, st);
     hipLaunchKernelGGL(k_sample_threshold, dim3(B), dim3(SELECT_THREADS), 0, st, skeys, lam_pad, p.lambda,
                        (uint32_t)p.rank, thr, count, flags);
     HIP_TRY(hipGetLastError());
   } else {
-    hipLaunchKernelGGL(k_init_all_pass, dim3((B + 255) / 256), dim3(256), 0, st, thr, count, flags, B);
+    hipLaunchKernelGGL(k_init_all_pass, dim3((B * SHARDS + 255) / 256), dim3(256), 0, st, thr, count, flags, B);
     HIP_TRY(hipGetLastError());
   }
 
   a.n_rows = c->N;
-  mol_status_t rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, st) : launch_scan<false, EPI_FILTER, false>(a, B, st);
+  mol_status_t rc;
+  {
+    ProfScope ps(MOL_PROF_SCAN_FILTER, st);
+    rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, st) : launch_scan<false, EPI_FILTER, false>(a, B, st);
+  }
   if (rc != MOL_OK) return rc;
 
+  ProfScope ps(MOL_PROF_SELECT, st);
   hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, Kp, mode,
                      false, cand_idx, cand_score, cand_count);
   HIP_TRY(hipGetLastError());
