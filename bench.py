@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--n-items", type=int, default=0, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--mode", type=int, default=0, help="0 = exact-on-success h-indexer (default), 1 = Algorithm 2 as written")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run a plain 1 GiB device copy three times (gives profilers' byte counters a kernel of known traffic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the retrieval path on ONE GPU only (the paper's inference path is single-GPU); "
@@ -200,6 +202,13 @@ def main():
                       "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0},
         "paper_context": PAPER_CONTEXT,
     }
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a slice of the workload ...")
         result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, n_sub, 4096)
