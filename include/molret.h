@@ -50,6 +50,7 @@ enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
 /* h-indexer modes */
 #define MOL_HINDEXER_EXACT 0 /* sampled threshold at a deeper rank, exact top-K' of the survivors, exact redo on a miss */
 #define MOL_HINDEXER_PAPER 1 /* Algorithm 2 as written: rank K'*lambda/N, strict filter, at most K' kept */
+#define MOL_HINDEXER_FORCE_REDO 0x100 /* OR into mode: send every query through the exact radix redo (diagnostics, timing of an exact top-K') */
 
 /*
  * Model description (host struct; read during mol_corpus_pack only).

@@ -14,7 +14,23 @@
 
 namespace {
 
-enum { EPI_FILTER = 0, EPI_KEYS = 1 };
+enum { EPI_FILTER = 0, EPI_KEYS = 1, EPI_HIST_KEY = 2, EPI_HIST_IDX = 3, EPI_FILTER_EXACT = 4 };
+
+// Exact redo of a query whose sampled threshold missed (too few survivors, or a survivor list overflowed): a radix
+// select over recomputed scores.  Four scans histogram the 8-bit digits of the score key (most significant first)
+// and give the exact K'-th key; if only some of the items tied at that key may be taken, four more scans do the same
+// on the item index among the ties (lowest indices win).  A last scan then keeps exactly the K' items
+// {key > tkey} U {key == tkey, idx <= idx_limit}.  Every kernel of the chain returns at once when no query is
+// flagged, which is the normal case.
+struct ExactState {
+  uint32_t active;     // 0 not redone, 1 key passes, 2 index passes, 3 threshold known
+  uint32_t prefix;     // digits found so far (of the key, then of ~idx)
+  uint32_t krem;       // rank still to resolve
+  uint32_t tkey;       // exact K'-th key
+  uint32_t idx_limit;  // ties at tkey are taken while idx <= idx_limit
+  uint32_t pad[3];
+};
+#define EXACT_BINS 256
 
 // Survivors of one query are appended to SHARDS independent lists, the list chosen by the tile number
 // (item index / 32) mod SHARDS.  Appending costs one returning atomic per survivor; atomics on one cache line
@@ -37,6 +53,10 @@ struct ScanArgs {
   int64_t cap_s;         // capacity of one shard
   uint32_t *skeys;       // KEYS: [B][skeys_stride] score keys
   int64_t skeys_stride;
+  const ExactState *state;  // exact redo: per-query state
+  uint32_t *hist;           // exact redo: [B][EXACT_BINS] digit histogram
+  const uint32_t *gate;     // exact redo: the kernel returns at once when *gate == 0
+  int shift;                // exact redo: bit position of the digit
 };
 
 // F32 = false: bf16 rows of 64 (128 B), 4 x 16-byte chunks per lane, one 32x32x16 MFMA per chunk.
@@ -52,9 +72,20 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   const int64_t ntiles = (a.n_rows + 31) >> 5;
+  constexpr bool REDO = EPI >= EPI_HIST_KEY;
+  constexpr bool HIST = EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX;
+  extern __shared__ uint32_t lds_hist[];  // HIST: [32*NQG][EXACT_BINS]
+  if constexpr (REDO) {
+    if (*a.gate == 0) return;
+  }
+  if constexpr (HIST) {
+    for (int i = threadIdx.x; i < 32 * NQG * EXACT_BINS; i += 256) lds_hist[i] = 0;
+    __syncthreads();
+  }
 
   uint4 q[NQG][NCH];
   float thr[NQG];
+  uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
 #pragma unroll
   for (int g = 0; g < NQG; ++g) {
     const int b = a.qbase + 32 * g + r;
@@ -62,6 +93,16 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
     for (int ci = 0; ci < NCH; ++ci)
       q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
     thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
+    st_active[g] = 0;
+    if constexpr (REDO) {
+      if (b < a.B) {
+        const ExactState s = a.state[b];
+        st_active[g] = s.active;
+        st_prefix[g] = s.prefix;
+        st_tkey[g] = s.tkey;
+        st_ilim[g] = s.idx_limit;
+      }
+    }
   }
 
   auto load_tile = [&](uint4(&dst)[NCH], int64_t tile) {
@@ -132,6 +173,33 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
               }
             }
           }
+        } else if constexpr (EPI == EPI_FILTER_EXACT) {
+          if (st_active[g] == 3u) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
+              const uint32_t k = f32_to_key(acc[g][j]);
+              if ((k > st_tkey[g] || (k == st_tkey[g] && (uint32_t)n <= st_ilim[g])) && n < a.n_rows) {
+                const int sh = (int)(tile & (SHARDS - 1));
+                const uint32_t slot = atomicAdd(&a.count[(size_t)(b * SHARDS + sh) * COUNT_STRIDE], 1u);
+                if ((int64_t)slot < a.cap_s) a.surv[((size_t)b * SHARDS + sh) * a.cap_s + slot] = make_uint2(k, (uint32_t)n);
+              }
+            }
+          }
+        } else if constexpr (HIST) {
+          if (st_active[g] == (EPI == EPI_HIST_KEY ? 1u : 2u)) {
+            uint32_t *hrow = lds_hist + (32 * g + r) * EXACT_BINS;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+              const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
+              const uint32_t key = f32_to_key(acc[g][j]);
+              const uint32_t k = (EPI == EPI_HIST_KEY) ? key : ~(uint32_t)n;
+              bool take = n < a.n_rows;
+              if (EPI == EPI_HIST_IDX) take = take && key == st_tkey[g];
+              if (a.shift < 24) take = take && (k >> (a.shift + 8)) == (st_prefix[g] >> (a.shift + 8));
+              if (take) atomicAdd(&hrow[(k >> a.shift) & (EXACT_BINS - 1)], 1u);
+            }
+          }
         } else {
           if (b < a.B) {
 #pragma unroll
@@ -143,6 +211,91 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
           }
         }
       }
+    }
+  }
+  if constexpr (HIST) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * NQG * EXACT_BINS; i += 256) {
+      const uint32_t v = lds_hist[i];
+      const int b = a.qbase + i / EXACT_BINS;
+      if (v && b < a.B) atomicAdd(&a.hist[(size_t)b * EXACT_BINS + (i & (EXACT_BINS - 1))], v);
+    }
+  }
+}
+
+// One step of the exact redo between two scans (one workgroup of EXACT_BINS threads per query).
+//   stage 0      : flagged queries start the key passes (rank K').
+//   stage 1..4   : digit of the key found from the histogram of the scan just done; after the fourth the K'-th key is
+//                  known and either every tie is taken or the index passes start.
+//   stage 5..8   : the same on ~idx among the ties; after the fourth the index limit is known.
+//   stage 9      : queries with a known threshold get their survivor counters cleared for the final filter scan.
+__global__ __launch_bounds__(EXACT_BINS) void k_exact_step(int stage, ExactState *state, uint32_t *hist, uint32_t *gate,
+                                                           uint32_t *flags, uint32_t *count, uint32_t Kp) {
+  __shared__ uint32_t suf[EXACT_BINS];
+  if (gate[0] == 0) return;
+  const int b = blockIdx.x;
+  const int t = threadIdx.x;
+  ExactState *st = state + b;
+  uint32_t *hb = hist + (size_t)b * EXACT_BINS;
+  if (stage == 0) {
+    if (t == 0) {
+      ExactState s = {};
+      if (flags[b] == 1u) {
+        s.active = 1;
+        s.krem = Kp;
+        s.idx_limit = 0xffffffffu;
+      }
+      *st = s;
+    }
+    hb[t] = 0;
+    return;
+  }
+  if (stage == 9) {
+    if (st->active == 3u) {
+      if (t < SHARDS) count[(size_t)(b * SHARDS + t) * COUNT_STRIDE] = 0;
+      if (t == 0) flags[b] = 2u;
+    }
+    return;
+  }
+  const uint32_t want = stage <= 4 ? 1u : 2u;
+  const uint32_t active = st->active;
+  const uint32_t mine = hb[t];
+  __syncthreads();
+  hb[t] = 0;  // ready for the next scan
+  if (active != want) return;
+  // inclusive suffix sums: suf[t] = sum of bins >= t
+  suf[t] = mine;
+  __syncthreads();
+  for (int o = 1; o < EXACT_BINS; o <<= 1) {
+    const uint32_t add = (t + o < EXACT_BINS) ? suf[t + o] : 0u;
+    __syncthreads();
+    suf[t] += add;
+    __syncthreads();
+  }
+  const uint32_t krem = st->krem, prefix = st->prefix;
+  const uint32_t above = suf[t] - mine;  // elements in larger digits
+  __syncthreads();
+  if (above < krem && krem <= above + mine) {  // exactly one thread
+    const int shift = 24 - 8 * ((stage - 1) & 3);
+    const uint32_t np = prefix | ((uint32_t)t << shift);
+    const uint32_t nk = krem - above;
+    if (stage == 4) {
+      st->tkey = np;
+      if (nk == mine) {  // all items tied at the K'-th key fit
+        st->active = 3;
+        st->idx_limit = 0xffffffffu;
+      } else {
+        st->active = 2;
+        st->prefix = 0;
+        st->krem = nk;
+        gate[1] = 1;
+      }
+    } else if (stage == 8) {
+      st->idx_limit = ~np;
+      st->active = 3;
+    } else {
+      st->prefix = np;
+      st->krem = nk;
     }
   }
 }
@@ -161,7 +314,7 @@ __global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64
 // Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement); resets the counters.
 __global__ __launch_bounds__(SELECT_THREADS) void k_sample_threshold(const uint32_t *skeys, int64_t stride,
                                                                      int64_t lambda, uint32_t rank, float *thr,
-                                                                     uint32_t *count, uint32_t *flags) {
+                                                                     uint32_t *count, uint32_t *flags, uint32_t *gate) {
   __shared__ SelectShared sh;
   const int b = blockIdx.x;
   const uint32_t *keys = skeys + (size_t)b * stride;
@@ -179,12 +332,14 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_sample_threshold(const uint3
   if (threadIdx.x == 0) {
     thr[b] = key_to_f32(sh.kth_key);
     flags[b] = 0;
+    if (b == 0) gate[0] = gate[1] = 0;
   }
   if (threadIdx.x < SHARDS) count[(size_t)(b * SHARDS + threadIdx.x) * COUNT_STRIDE] = 0;
 }
 
-__global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, int B) {
+__global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, uint32_t *gate, int B) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) gate[0] = gate[1] = 0;
   if (i < B) {
     thr[i] = -INFINITY;
     flags[i] = 0;
@@ -195,9 +350,10 @@ __global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, in
 // Survivors -> at most K' candidates (Section 4.1.2).  flags[b] is set to 1 when the survivor lists cannot give
 // the answer (a list overflowed, or fewer than K' survived in exact mode); such a query is redone by the exact path.
 __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, int64_t cap_s,
-                                                                     const uint32_t *count, uint32_t *flags, int Kp,
-                                                                     int mode, bool only_flagged, int32_t *cand_idx,
-                                                                     float *cand_score, int32_t *cand_count) {
+                                                                     const uint32_t *count, uint32_t *flags, uint32_t *gate,
+                                                                     int Kp, int mode, bool force_redo, bool only_flagged,
+                                                                     int32_t *cand_idx, float *cand_score,
+                                                                     int32_t *cand_count) {
   __shared__ SelectShared sh;
   __shared__ uint32_t cnt_s[SHARDS];
   const int b = blockIdx.x;
@@ -215,10 +371,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
   const bool underflow = (mode == MOL_HINDEXER_EXACT) && total < (uint64_t)Kp;
-  if (overflow || underflow) {
+  if (overflow || underflow || (force_redo && !only_flagged)) {
     if (tid == 0) {
-      flags[b] = only_flagged ? 3u : 1u;  // 3 = even the exact path could not fit (pathological ties)
+      flags[b] = only_flagged ? 3u : 1u;  // 3 = the exact K' items did not fit the lists (see molret.h)
       cand_count[b] = -1;
+      if (!only_flagged) gate[0] = 1;
     }
     for (int i = tid; i < Kp; i += SELECT_THREADS) {
       oi[i] = -1;
@@ -275,14 +432,21 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, hipStream_t st) {
                              : nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH>
                                         : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>;
     int per_sm = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, 0));
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(
+        &per_sm, kern, 256, (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0));
     if (per_sm < 1) per_sm = 1;
     if (per_sm > 4) per_sm = 4;
     int64_t grid = (int64_t)sm_count * per_sm;
     const int64_t need = (ntiles + 3) / 4;
     if (grid > need) grid = need;
     if (grid < 1) grid = 1;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), 0, st, a);
+    size_t lds = 0;
+    if (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) {
+      lds = (size_t)32 * nqg * EXACT_BINS * 4;
+      if (lds > 48 * 1024)
+        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     HIP_TRY(hipGetLastError());
   }
   return MOL_OK;
@@ -332,9 +496,9 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->off_surv = off;
   off = align_up(off + (size_t)B * SHARDS * p->cap * 8, 256);
   p->off_hist = off;
-  off = align_up(off + (size_t)B * SELECT_BINS * 4, 256);
+  off = align_up(off + (size_t)B * EXACT_BINS * 4, 256);
   p->off_state = off;
-  off = align_up(off + (size_t)B * 16, 256);
+  off = align_up(off + (size_t)B * sizeof(ExactState) + 256, 256);  // + the two gate words
   p->total = off;
   return MOL_OK;
 }
@@ -347,6 +511,11 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   uint32_t *count = reinterpret_cast<uint32_t *>(ws + p.off_count);
   uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
   uint2 *surv = reinterpret_cast<uint2 *>(ws + p.off_surv);
+  uint32_t *hist = reinterpret_cast<uint32_t *>(ws + p.off_hist);
+  uint32_t *gate = reinterpret_cast<uint32_t *>(ws + p.off_state);
+  ExactState *state = reinterpret_cast<ExactState *>(ws + p.off_state + 256);
+  const bool force_redo = (mode & MOL_HINDEXER_FORCE_REDO) != 0;
+  mode &= ~MOL_HINDEXER_FORCE_REDO;
 
   ScanArgs a = {};
   a.X = static_cast<const char *>(c->stage1);
@@ -382,10 +551,10 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     if (rc != MOL_OK) return rc;
     ProfScope ps(MOL_PROF_THRESHOLD, st);
     hipLaunchKernelGGL(k_sample_threshold, dim3(B), dim3(SELECT_THREADS), 0, st, skeys, lam_pad, p.lambda,
-                       (uint32_t)p.rank, thr, count, flags);
+                       (uint32_t)p.rank, thr, count, flags, gate);
     HIP_TRY(hipGetLastError());
   } else {
-    hipLaunchKernelGGL(k_init_all_pass, dim3((B * SHARDS + 255) / 256), dim3(256), 0, st, thr, count, flags, B);
+    hipLaunchKernelGGL(k_init_all_pass, dim3((B * SHARDS + 255) / 256), dim3(256), 0, st, thr, count, flags, gate, B);
     HIP_TRY(hipGetLastError());
   }
 
@@ -398,8 +567,36 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   if (rc != MOL_OK) return rc;
 
   ProfScope ps(MOL_PROF_SELECT, st);
-  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, Kp, mode,
-                     false, cand_idx, cand_score, cand_count);
+  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, gate, Kp,
+                     mode, force_redo, false, cand_idx, cand_score, cand_count);
+  HIP_TRY(hipGetLastError());
+
+  // exact redo of flagged queries; every kernel below returns at once when none is flagged
+  a.state = state;
+  a.hist = hist;
+  auto step = [&](int stage) -> mol_status_t {
+    hipLaunchKernelGGL(k_exact_step, dim3(B), dim3(EXACT_BINS), 0, st, stage, state, hist, gate, flags, count,
+                       (uint32_t)Kp);
+    HIP_TRY(hipGetLastError());
+    return MOL_OK;
+  };
+  rc = step(0);
+  for (int pass = 0; pass < 8 && rc == MOL_OK; ++pass) {
+    a.shift = 24 - 8 * (pass & 3);
+    a.gate = gate + (pass < 4 ? 0 : 1);
+    if (pass < 4)
+      rc = f32 ? launch_scan<true, EPI_HIST_KEY, false>(a, B, st) : launch_scan<false, EPI_HIST_KEY, false>(a, B, st);
+    else
+      rc = f32 ? launch_scan<true, EPI_HIST_IDX, false>(a, B, st) : launch_scan<false, EPI_HIST_IDX, false>(a, B, st);
+    if (rc == MOL_OK) rc = step(pass + 1);
+  }
+  if (rc == MOL_OK) rc = step(9);
+  if (rc != MOL_OK) return rc;
+  a.gate = gate;
+  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, st) : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, st);
+  if (rc != MOL_OK) return rc;
+  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, gate, Kp,
+                     mode, false, true, cand_idx, cand_score, cand_count);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }

@@ -268,3 +268,55 @@ def test_error_paths_return_status_and_leave_outputs_alone():
         lib.mol_corpus_pack(items["x1"], items["G"][:, :3].contiguous(), items["gx"], gw.W1[:, :-4].contiguous(),
                             gw.b1, gw.W2[:12].contiguous(), gw.b2[:12].contiguous(), k_u=4)
     assert e.value.status == -4
+
+
+# ------------------------------------------------------------------------------------------ exact redo path
+FORCE_REDO = 0x100
+
+
+@pytest.mark.parametrize("dtype,N,B,Kp", [("bf16", 50_003, 20, 512), ("f32", 40_001, 16, 1024), ("bf16", 45_000, 70, 300)])
+def test_hindexer_exact_redo_gives_the_exact_topk(dtype, N, B, Kp):
+    """Every query forced through the radix redo (the path taken when the sampled threshold misses)."""
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype=dtype, n_clusters=64)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], Kp, mode=m().HINDEXER_EXACT | FORCE_REDO, seed=5)
+    torch.cuda.synchronize()
+    s = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    ci, cs, cc = ci.cpu().numpy(), cs.cpu().numpy(), cc.cpu().numpy()
+    assert np.all(cc == Kp)
+    for b in range(B):
+        assert_topk_set(ci[b], s[b], Kp, S1_TOL, f"query {b}")
+        np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=S1_TOL)
+
+
+def test_hindexer_massive_ties_take_the_lowest_indices():
+    """Degenerate corpus: every item identical, so every score ties.  The sampled threshold keeps nothing (strict >),
+    the redo finds the K'-th key and resolves the tie by index: items 0..K'-1.  With half the corpus replaced by a
+    better item, the better half comes first and the rest is filled by index."""
+    N, B, Kp = 6000, 3, 200
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, n_clusters=4)
+    items, q, gw = make(wl)
+    items["x1"][:] = items["x1"][0]
+    corpus = pack(wl, items, gw)
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], Kp)
+    ci, cc = ci.cpu().numpy(), cc.cpu().numpy()
+    assert np.all(cc == Kp)
+    for b in range(B):
+        assert sorted(ci[b].tolist()) == list(range(Kp))
+    corpus.free()
+    # 150 items that score strictly higher for every query: the query itself, normalised, cannot be beaten... use
+    # the first query's own vector for all queries to keep it simple
+    q1 = q["q1"].clone()
+    q1[:] = q1[0]
+    better = (q1[0].float() / q1[0].float().norm()).to(torch.bfloat16)
+    pos = torch.arange(5000, 5150)
+    items["x1"][pos] = better
+    s = orc.stage1_scores(bits(q1), bits(items["x1"]))
+    assert s[0, 5000] > s[0, 0]
+    corpus = pack(wl, items, gw)
+    ci, cs, cc = m().hindexer_topk(corpus, q1, Kp)
+    ci, cc = ci.cpu().numpy(), cc.cpu().numpy()
+    assert np.all(cc == Kp)
+    for b in range(B):
+        assert sorted(ci[b].tolist()) == list(range(50)) + list(range(5000, 5150))
