@@ -91,7 +91,8 @@ mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *stage1_items, 
 /* Frees what pack allocated (device synchronising).  NULL is accepted. */
 mol_status_t mol_corpus_free(mol_corpus_t *corpus);
 
-/* Host-only size queries; return 0 on invalid arguments.  lambda <= 0 selects the library's default sample size. */
+/* Size queries (no device work; hindexer_workspace_bytes asks the HIP runtime for the device's occupancy figures, so the
+ * device the corpus lives on must be current); return 0 on invalid arguments.  lambda <= 0 selects the default sample size. */
 size_t hindexer_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int64_t lambda);
 size_t mol_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int k);
 

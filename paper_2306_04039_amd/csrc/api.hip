@@ -111,22 +111,24 @@ extern "C" int64_t hindexer_default_lambda(const mol_corpus_t *c, int Kp) {
 extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp, int64_t lambda) {
   if (!c || B < 1 || B > 1024 || Kp < 1 || Kp > c->N || c->d1 == 0) return 0;
   HindexerPlan p0, p1;
-  hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_EXACT, &p0);
-  hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_PAPER, &p1);
+  if (hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_EXACT, &p0) != MOL_OK) return 0;
+  if (hindexer_plan(c, B, Kp, lambda, MOL_HINDEXER_PAPER, &p1) != MOL_OK) return 0;
   return p0.total > p1.total ? p0.total : p1.total;
 }
 
-static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, size_t *off_scores) {
+static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, size_t *off_scores, size_t *off_topk) {
   size_t off = align_up((size_t)B * c->H * 4, 256);
   if (off_scores) *off_scores = off;
   off = align_up(off + (size_t)B * row * 4, 256);
+  if (off_topk) *off_topk = off;
+  off += final_topk_workspace_bytes(B);
   return off;
 }
 
 extern "C" size_t mol_workspace_bytes(const mol_corpus_t *c, int B, int Kp, int k) {
   if (!c || B < 1 || B > 1024 || k < 0) return 0;
   const int64_t row = Kp > 0 ? Kp : c->N;
-  return mol_ws_layout(c, B, row, nullptr);
+  return mol_ws_layout(c, B, row, nullptr, nullptr);
 }
 
 static mol_status_t check_ws(const void *ws, size_t have, size_t need) {
@@ -147,8 +149,9 @@ extern "C" mol_status_t hindexer_topk(const mol_corpus_t *c, const void *q1, int
     return mol_fail(MOL_EINVAL, "unknown mode %d", mode);
   if (sample_idx && lambda < 1) return mol_fail(MOL_EINVAL, "an explicit sample needs lambda >= 1");
   HindexerPlan p;
-  hindexer_plan(c, B, Kp, lambda, mode & ~MOL_HINDEXER_FORCE_REDO, &p);
-  mol_status_t rc = check_ws(workspace, workspace_bytes, p.total);
+  mol_status_t rc = hindexer_plan(c, B, Kp, lambda, mode & ~MOL_HINDEXER_FORCE_REDO, &p);
+  if (rc != MOL_OK) return rc;
+  rc = check_ws(workspace, workspace_bytes, p.total);
   if (rc != MOL_OK) return rc;
   return hindexer_run(c, q1, B, Kp, sample_idx, seed, mode, p, cand_idx, cand_score, cand_count,
                       static_cast<char *>(workspace), static_cast<hipStream_t>(stream));
@@ -186,8 +189,8 @@ extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, c
   if (!out_idx || !out_score) return mol_fail(MOL_EINVAL, "out_idx / out_score is NULL");
   if (k < 1 || k > 1024) return mol_fail(MOL_EINVAL, "k=%d must be in [1, 1024]", k);
   const int64_t row = cand_idx ? Kp : c->N;
-  size_t off_scores = 0;
-  const size_t need = mol_ws_layout(c, B, row, &off_scores);
+  size_t off_scores = 0, off_topk = 0;
+  const size_t need = mol_ws_layout(c, B, row, &off_scores, &off_topk);
   rc = check_ws(workspace, workspace_bytes, need);
   if (rc != MOL_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -197,5 +200,5 @@ extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, c
   if (rc != MOL_OK) return rc;
   rc = launch_mol_score(c, user_embs, U, B, cand_idx, row, scores, st);
   if (rc != MOL_OK) return rc;
-  return launch_final_topk(scores, cand_idx, B, row, k, out_idx, out_score, st);
+  return launch_final_topk(scores, cand_idx, B, row, k, out_idx, out_score, static_cast<char *>(workspace) + off_topk, st);
 }

@@ -99,9 +99,12 @@ struct HindexerPlan {
   bool sampling;       // false: every item passes (threshold -inf)
   int64_t lambda;      // sample size actually used
   int64_t rank;        // threshold rank inside the sample (1-based from the largest)
-  int64_t cap;         // survivor capacity per (query, shard) list
+  int64_t grid;        // workgroups of the list-writing scans
+  int64_t L;           // survivor lists per query (8 per workgroup)
+  int64_t cap;         // capacity of one survivor list
   // workspace offsets (bytes)
-  size_t off_sample, off_skeys, off_thr, off_count, off_flags, off_surv, off_hist, off_state, total;
+  size_t off_sample, off_skeys, off_thr, off_count, off_flags, off_sstat, off_surv, off_mhist, off_mcnt, off_tie,
+      off_hist, off_state, total;
 };
 mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, int mode, HindexerPlan *p);
 mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
@@ -115,5 +118,6 @@ mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B,
 mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
                               const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st);
 // select.hip
+size_t final_topk_workspace_bytes(int B);
 mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
-                               int32_t *out_idx, float *out_score, hipStream_t st);
+                               int32_t *out_idx, float *out_score, char *ws, hipStream_t st);

@@ -1,0 +1,180 @@
+// Multi-workgroup radix selection under the total order (key descending, index ascending).
+//
+// The lists handled here (sampled stage-1 scores, stage-1 survivors, MoL scores of the candidates) hold 1e5..1e6
+// entries per query: too much for one workgroup to walk several times at the latency the path needs, so every pass is
+// a grid of (slices x queries) workgroups.  Three histogram passes over fixed digits of the 32-bit key
+// (bits 31..21, 20..10, 9..0) find the exact K-th key; an emit pass writes everything above it, and the few items tied
+// at the K-th key are parked in a small buffer from which a finishing workgroup takes the lowest indices.
+// No per-query state is carried between the kernels except the three histograms: every workgroup re-derives the
+// digits found so far from them (a 2048-bin scan, microseconds), which saves a launch per pass.
+#pragma once
+#include "common.hpp"
+
+#define MSEL_THREADS 256
+#define MSEL_BINS 2048
+#define MSEL_PASSES 3
+#define MSEL_TIE_CAP 2048
+
+__device__ __forceinline__ int msel_lo(int p) { return p == 0 ? 21 : (p == 1 ? 10 : 0); }
+__device__ __forceinline__ int msel_bins(int p) { return p == 2 ? 1024 : 2048; }
+
+struct MselShared {
+  uint32_t hist[MSEL_BINS];
+  uint32_t part[MSEL_THREADS];
+  uint32_t res[4];
+};
+
+// What the three histograms say about the K-th element of one query.
+struct MselCut {
+  uint32_t total;   // number of elements in the list
+  uint32_t K;       // effective rank: min(requested, total)
+  uint32_t prefix;  // key bits fixed by the passes resolved so far
+  uint32_t krem;    // rank inside the set that matches prefix
+  uint32_t cnt;     // size of the digit bucket chosen by the last resolved pass
+};
+
+// Workgroup-cooperative: the digit of pass-histogram g (nb bins) that holds rank krem (1-based from the largest digit).
+// Returns through sh.res: {digit, rank inside the digit, bucket size, total}.  Requires 1 <= krem <= total for a
+// meaningful digit; total is always right.
+__device__ inline void msel_find(const uint32_t *g, int nb, uint32_t krem, MselShared &sh) {
+  const int t = threadIdx.x;
+  const int per = nb / MSEL_THREADS;
+  const int top = nb - 1 - t * per;  // this thread covers digits top, top-1, ..., top-per+1
+  uint32_t s = 0;
+  for (int j = 0; j < per; ++j) s += g[top - j];
+  sh.part[t] = s;
+  if (t == 0) {
+    sh.res[0] = 0;
+    sh.res[1] = 0;
+    sh.res[2] = 0;
+  }
+  __syncthreads();
+  // inclusive prefix over threads (thread 0 holds the largest digits)
+  for (int o = 1; o < MSEL_THREADS; o <<= 1) {
+    const uint32_t add = (t >= o) ? sh.part[t - o] : 0u;
+    __syncthreads();
+    sh.part[t] += add;
+    __syncthreads();
+  }
+  const uint32_t incl = sh.part[t];
+  uint32_t above = incl - s;
+  if (t == MSEL_THREADS - 1) sh.res[3] = incl;
+  if (above < krem && krem <= incl) {
+    int d = top;
+    uint32_t c = g[d];
+    while (above + c < krem) {
+      above += c;
+      c = g[--d];
+    }
+    sh.res[0] = (uint32_t)d;
+    sh.res[1] = krem - above;
+    sh.res[2] = c;
+  }
+  __syncthreads();
+}
+
+// Re-derives the cut after `resolved` passes (0..3) from the per-pass histograms of query b.
+// hist layout: [MSEL_PASSES][B][MSEL_BINS].
+__device__ inline MselCut msel_cut(const uint32_t *hist, int B, int b, uint32_t K_req, int resolved, MselShared &sh) {
+  MselCut c;
+  c.total = 0;
+  c.K = 0;
+  c.prefix = 0;
+  c.krem = 0;
+  c.cnt = 0;
+  for (int p = 0; p < resolved; ++p) {
+    const uint32_t *g = hist + ((size_t)p * B + b) * MSEL_BINS;
+    if (p == 0) {
+      msel_find(g, msel_bins(0), 0xffffffffu, sh);  // only the total is used
+      c.total = sh.res[3];
+      c.K = K_req < c.total ? K_req : c.total;
+      c.krem = c.K;
+      __syncthreads();
+      if (c.K == 0) return c;
+    }
+    msel_find(g, msel_bins(p), c.krem, sh);
+    c.prefix |= sh.res[0] << msel_lo(p);
+    c.krem = sh.res[1];
+    c.cnt = sh.res[2];
+    __syncthreads();
+  }
+  return c;
+}
+
+// Histogram pass p over the elements `each` hands out (each(f) calls f(key, idx) for this workgroup's slice).
+// The caller provides the prefix fixed by the earlier passes.  Flushes non-empty bins to the global histogram.
+template <class Each>
+__device__ inline void msel_hist_pass(Each each, int p, uint32_t prefix, uint32_t *ghist, MselShared &sh) {
+  const int nb = msel_bins(p);
+  for (int i = threadIdx.x; i < nb; i += MSEL_THREADS) sh.hist[i] = 0;
+  __syncthreads();
+  const int lo = msel_lo(p);
+  const int hi_shift = lo + (p == 2 ? 10 : 11);
+  const uint32_t mask = (uint32_t)nb - 1u;
+  each([&](uint32_t key, uint32_t) {
+    const bool match = (p == 0) || ((key >> hi_shift) == (prefix >> hi_shift));
+    if (match) atomicAdd(&sh.hist[(key >> lo) & mask], 1u);
+  });
+  __syncthreads();
+  for (int i = threadIdx.x; i < nb; i += MSEL_THREADS) {
+    const uint32_t v = sh.hist[i];
+    if (v) atomicAdd(&ghist[i], v);
+  }
+}
+
+// Appends (key, idx) to an output list with one atomic per wavefront.  `take` may differ per lane; all 64 lanes
+// of the wavefront must call.
+__device__ __forceinline__ uint32_t msel_wave_slot(bool take, uint32_t *counter) {
+  const uint64_t m = __ballot(take);
+  if (m == 0) return 0;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  base = __shfl(base, leader);
+  return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+// Walks slice `blk` of `nblk` of p[0..n) with U loads in flight per thread.  f(i, value, valid) is called the same
+// number of times by every thread of the workgroup (valid = false past the end), so f may use wavefront collectives.
+template <int U, class T, class F>
+__device__ __forceinline__ void msel_slice_for_each(const T *p, int64_t n, int blk, int nblk, F f) {
+  const int64_t step = (int64_t)U * MSEL_THREADS;
+  int64_t chunk = (n + nblk - 1) / nblk;
+  chunk = (chunk + step - 1) / step * step;
+  const int64_t lo = (int64_t)blk * chunk;
+  int64_t hi = lo + chunk;
+  if (hi > n) hi = n;
+  for (int64_t base = lo; base < hi; base += step) {
+    T v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = base + (int64_t)u * MSEL_THREADS + threadIdx.x;
+      if (i < hi) v[u] = p[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = base + (int64_t)u * MSEL_THREADS + threadIdx.x;
+      f(i, v[u], i < hi);
+    }
+  }
+}
+
+// Finishing helper: of the nt ties parked in `ties` (all with the same key), the `need` lowest indices are appended to
+// the output through `put(slot_offset, idx)`; slot offsets run from 0 to need-1 in ascending index order.
+// One workgroup; nt <= MSEL_TIE_CAP.  sh.hist is used as scratch for the indices.
+template <class Put>
+__device__ inline void msel_take_lowest_ties(const uint32_t *ties, uint32_t nt, uint32_t need, MselShared &sh, Put put) {
+  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) sh.hist[i] = ties[i];
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
+    const uint32_t me = sh.hist[i];
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < nt; ++j) rank += (sh.hist[j] < me || (sh.hist[j] == me && j < i)) ? 1u : 0u;
+    if (rank < need) put(rank, me);
+  }
+  __syncthreads();
+}
+
+__global__ void k_zero_u32(uint32_t *p, size_t n);
+#define MCNT_STRIDE 64  // uint32 per query in the counter block: [0] emitted, [1] ties parked, [2] "too many ties" flag

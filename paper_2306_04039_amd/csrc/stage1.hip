@@ -7,9 +7,17 @@
 // the query fragments in registers for the whole kernel, accumulates in fp32 on MFMA and compares the 32x32
 // score tile against the per-query thresholds in registers.  Only survivors are written (index + score key),
 // so no N-length score vector ever reaches HBM.
+//
+// Survivor lists.  In the 32x32 score tile a lane always holds scores of ONE query (column = lane % 32), so every
+// (wavefront, lane) pair appends the survivors it finds to a list of its own and counts them in a register: no
+// atomics, nothing to wait for (with a shared per-query counter the scan spent 10 % of its time waiting for
+// returning atomics).  A query therefore owns L = 2 * (number of wavefronts) short lists; tile t goes to wavefront
+// t mod W, so each list is a deterministic set whatever the timing.
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.hpp"
+#include "msel.hpp"
 #include "select.hpp"
 
 namespace {
@@ -32,13 +40,6 @@ struct ExactState {
 };
 #define EXACT_BINS 256
 
-// Survivors of one query are appended to SHARDS independent lists, the list chosen by the tile number
-// (item index / 32) mod SHARDS.  Appending costs one returning atomic per survivor; atomics on one cache line
-// serialise in L2, so the counters are spread over B*SHARDS lines.  Which list an item lands in depends only on its
-// index, so each list is a deterministic set.
-#define SHARDS 16
-#define COUNT_STRIDE 64  // uint32 per counter slot (256 bytes)
-
 struct ScanArgs {
   const char *X;         // item table, row-major, ROWB bytes per row
   int64_t n_rows;        // rows to score (N, or lambda for the gathered sample)
@@ -48,9 +49,10 @@ struct ScanArgs {
   int B;                 // total number of queries
   int qbase;             // first query handled by this launch
   const float *thr;      // FILTER: per-query threshold (strict >)
-  uint32_t *count;       // FILTER: survivor counters, one per (query, shard), each on its own 256-byte line
-  uint2 *surv;           // FILTER: [B][SHARDS][cap_s] (key, idx)
-  int64_t cap_s;         // capacity of one shard
+  uint32_t *cnt;         // FILTER*: [B][L] survivors found per list (may exceed cap: overflow)
+  uint2 *surv;           // FILTER*: [B][L][cap] (key, idx)
+  int64_t L;             // lists per query = 2 * wavefronts of the launch
+  int64_t cap;           // capacity of one list
   uint32_t *skeys;       // KEYS: [B][skeys_stride] score keys
   int64_t skeys_stride;
   const ExactState *state;  // exact redo: per-query state
@@ -67,13 +69,14 @@ template <bool F32, int NQG, int EPI, bool GATHER, int DEPTH>
 __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   constexpr int NCH = F32 ? 8 : 4;
   constexpr int ROWB = F32 ? 256 : 128;
+  constexpr bool REDO = EPI >= EPI_HIST_KEY;
+  constexpr bool HIST = EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX;
+  constexpr bool LISTS = EPI == EPI_FILTER || EPI == EPI_FILTER_EXACT;
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   const int64_t ntiles = (a.n_rows + 31) >> 5;
-  constexpr bool REDO = EPI >= EPI_HIST_KEY;
-  constexpr bool HIST = EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX;
   extern __shared__ uint32_t lds_hist[];  // HIST: [32*NQG][EXACT_BINS]
   if constexpr (REDO) {
     if (*a.gate == 0) return;
@@ -86,6 +89,8 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   uint4 q[NQG][NCH];
   float thr[NQG];
   uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
+  uint32_t cnt[NQG];
+  uint2 *lst[NQG];
 #pragma unroll
   for (int g = 0; g < NQG; ++g) {
     const int b = a.qbase + 32 * g + r;
@@ -94,6 +99,11 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
       q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
     thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
     st_active[g] = 0;
+    cnt[g] = 0;
+    lst[g] = nullptr;
+    if constexpr (LISTS) {
+      if (b < a.B) lst[g] = a.surv + ((size_t)b * a.L + wave * 2 + h) * a.cap;
+    }
     if constexpr (REDO) {
       if (b < a.B) {
         const ExactState s = a.state[b];
@@ -166,10 +176,8 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
             for (int j = 0; j < 16; ++j) {
               const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
               if (((mask >> j) & 1u) && n < a.n_rows) {
-                const int sh = (int)(tile & (SHARDS - 1));
-                const uint32_t slot = atomicAdd(&a.count[(size_t)(b * SHARDS + sh) * COUNT_STRIDE], 1u);
-                if ((int64_t)slot < a.cap_s)
-                  a.surv[((size_t)b * SHARDS + sh) * a.cap_s + slot] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
+                if ((int64_t)cnt[g] < a.cap) lst[g][cnt[g]] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
+                ++cnt[g];
               }
             }
           }
@@ -180,9 +188,8 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
               const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
               const uint32_t k = f32_to_key(acc[g][j]);
               if ((k > st_tkey[g] || (k == st_tkey[g] && (uint32_t)n <= st_ilim[g])) && n < a.n_rows) {
-                const int sh = (int)(tile & (SHARDS - 1));
-                const uint32_t slot = atomicAdd(&a.count[(size_t)(b * SHARDS + sh) * COUNT_STRIDE], 1u);
-                if ((int64_t)slot < a.cap_s) a.surv[((size_t)b * SHARDS + sh) * a.cap_s + slot] = make_uint2(k, (uint32_t)n);
+                if ((int64_t)cnt[g] < a.cap) lst[g][cnt[g]] = make_uint2(k, (uint32_t)n);
+                ++cnt[g];
               }
             }
           }
@@ -213,6 +220,13 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
       }
     }
   }
+  if constexpr (LISTS) {
+#pragma unroll
+    for (int g = 0; g < NQG; ++g) {
+      const int b = a.qbase + 32 * g + r;
+      if (b < a.B && (EPI == EPI_FILTER || st_active[g] == 3u)) a.cnt[(size_t)b * a.L + wave * 2 + h] = cnt[g];
+    }
+  }
   if constexpr (HIST) {
     __syncthreads();
     for (int i = threadIdx.x; i < 32 * NQG * EXACT_BINS; i += 256) {
@@ -228,9 +242,9 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
 //   stage 1..4   : digit of the key found from the histogram of the scan just done; after the fourth the K'-th key is
 //                  known and either every tie is taken or the index passes start.
 //   stage 5..8   : the same on ~idx among the ties; after the fourth the index limit is known.
-//   stage 9      : queries with a known threshold get their survivor counters cleared for the final filter scan.
+//   stage 9      : queries with a known threshold are marked for the final filter scan.
 __global__ __launch_bounds__(EXACT_BINS) void k_exact_step(int stage, ExactState *state, uint32_t *hist, uint32_t *gate,
-                                                           uint32_t *flags, uint32_t *count, uint32_t Kp) {
+                                                           uint32_t *flags, uint32_t Kp) {
   __shared__ uint32_t suf[EXACT_BINS];
   if (gate[0] == 0) return;
   const int b = blockIdx.x;
@@ -251,10 +265,7 @@ __global__ __launch_bounds__(EXACT_BINS) void k_exact_step(int stage, ExactState
     return;
   }
   if (stage == 9) {
-    if (st->active == 3u) {
-      if (t < SHARDS) count[(size_t)(b * SHARDS + t) * COUNT_STRIDE] = 0;
-      if (t == 0) flags[b] = 2u;
-    }
+    if (t == 0 && st->active == 3u) flags[b] = 2u;
     return;
   }
   const uint32_t want = stage <= 4 ? 1u : 2u;
@@ -311,71 +322,222 @@ __global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64
   out[i] = (int32_t)(((z >> 32) * N) >> 32);
 }
 
-// Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement); resets the counters.
-__global__ __launch_bounds__(SELECT_THREADS) void k_sample_threshold(const uint32_t *skeys, int64_t stride,
-                                                                     int64_t lambda, uint32_t rank, float *thr,
-                                                                     uint32_t *count, uint32_t *flags, uint32_t *gate) {
-  __shared__ SelectShared sh;
-  const int b = blockIdx.x;
-  const uint32_t *keys = skeys + (size_t)b * stride;
-  auto each = [&](auto f) {  // rows are 16-byte aligned (stride is a multiple of 32 keys)
+// Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement), by multi-workgroup radix
+// selection over the B x lambda score keys.  k_thr_hist is launched once per digit pass; k_thr_finish writes the
+// threshold and resets the flags and the redo gate.
+__global__ __launch_bounds__(MSEL_THREADS) void k_thr_hist(const uint32_t *skeys, int64_t stride, int64_t lambda,
+                                                           uint32_t rank, uint32_t *mhist, int B, int pass) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
+  uint32_t prefix = 0;
+  if (pass > 0) prefix = msel_cut(mhist, B, b, rank, pass, sh).prefix;
+  const uint32_t *keys = skeys + (size_t)b * stride;  // rows are 16-byte aligned (stride is a multiple of 32 keys)
+  auto each = [&](auto f) {
     const int64_t n4 = lambda >> 2;
-    block_for_each<4>(reinterpret_cast<const uint4 *>(keys), n4, [&](int64_t i, uint4 v) {
-      f(v.x, (uint32_t)(4 * i));
-      f(v.y, (uint32_t)(4 * i + 1));
-      f(v.z, (uint32_t)(4 * i + 2));
-      f(v.w, (uint32_t)(4 * i + 3));
+    msel_slice_for_each<4>(reinterpret_cast<const uint4 *>(keys), n4, blk, G, [&](int64_t, uint4 v, bool valid) {
+      if (valid) {
+        f(v.x, 0u);
+        f(v.y, 0u);
+        f(v.z, 0u);
+        f(v.w, 0u);
+      }
     });
-    for (int64_t i = 4 * n4 + threadIdx.x; i < lambda; i += SELECT_THREADS) f(keys[i], (uint32_t)i);
+    if (blk == 0)
+      for (int64_t i = 4 * n4 + threadIdx.x; i < lambda; i += MSEL_THREADS) f(keys[i], 0u);
   };
-  block_select_kth<false>(each, rank, sh);
+  msel_hist_pass(each, pass, prefix, mhist + ((size_t)pass * B + b) * MSEL_BINS, sh);
+}
+
+__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, float *thr,
+                                                             uint32_t *flags, uint32_t *gate) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.x;
+  const MselCut c = msel_cut(mhist, B, b, rank, MSEL_PASSES, sh);
   if (threadIdx.x == 0) {
-    thr[b] = key_to_f32(sh.kth_key);
+    thr[b] = c.K ? key_to_f32(c.prefix) : -INFINITY;
     flags[b] = 0;
     if (b == 0) gate[0] = gate[1] = 0;
   }
-  if (threadIdx.x < SHARDS) count[(size_t)(b * SHARDS + threadIdx.x) * COUNT_STRIDE] = 0;
 }
 
-__global__ void k_init_all_pass(float *thr, uint32_t *count, uint32_t *flags, uint32_t *gate, int B) {
+__global__ void k_init_all_pass(float *thr, uint32_t *flags, uint32_t *gate, int B) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) gate[0] = gate[1] = 0;
   if (i < B) {
     thr[i] = -INFINITY;
     flags[i] = 0;
   }
-  if (i < B * SHARDS) count[(size_t)i * COUNT_STRIDE] = 0;
 }
 
-// Survivors -> at most K' candidates (Section 4.1.2).  flags[b] is set to 1 when the survivor lists cannot give
-// the answer (a list overflowed, or fewer than K' survived in exact mode); such a query is redone by the exact path.
-__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, int64_t cap_s,
-                                                                     const uint32_t *count, uint32_t *flags, uint32_t *gate,
-                                                                     int Kp, int mode, bool force_redo, bool only_flagged,
+// ---- survivors -> at most K' candidates (Section 4.1.2) ----------------------------------------------------------
+// sstat[b] = {survivors of query b, 1 if its lists cannot give the answer}: a list overflowed, or (exact mode) fewer
+// than K' survived, or the caller asked for the redo.  Such a query is left to the exact redo.
+__global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_t L, int64_t cap, int Kp, int mode,
+                                                     bool force, const uint32_t *flags, bool only_flagged,
+                                                     uint2 *sstat) {
+  __shared__ uint32_t s_tot[4], s_ovf[4];
+  const int b = blockIdx.x;
+  if (only_flagged && flags[b] != 2u) return;
+  uint32_t tot = 0, ovf = 0;
+  for (int64_t i = threadIdx.x; i < L; i += 256) {
+    const uint32_t c = cnt[(size_t)b * L + i];
+    tot += c;
+    ovf |= ((int64_t)c > cap) ? 1u : 0u;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    tot += __shfl_xor((int)tot, o);
+    ovf |= (uint32_t)__shfl_xor((int)ovf, o);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    s_tot[threadIdx.x >> 6] = tot;
+    s_ovf[threadIdx.x >> 6] = ovf;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    tot = s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3];
+    ovf = s_ovf[0] | s_ovf[1] | s_ovf[2] | s_ovf[3];
+    const bool bad = ovf || force || (mode == MOL_HINDEXER_EXACT && tot < (uint32_t)Kp);
+    sstat[b] = make_uint2(tot, bad ? 1u : 0u);
+  }
+}
+
+// Walks lists [lo, hi) of query b, one list per wavefront at a time, lanes across the entries.  f(entry, valid) is
+// called the same number of times by all 64 lanes of a wavefront (so it may use wavefront collectives).
+template <class F>
+__device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int b,
+                                                  int64_t lo, int64_t hi, int nwaves_in_block, F f) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  for (int64_t l = lo + wv; l < hi; l += nwaves_in_block) {
+    uint32_t n = cnt[(size_t)b * L + l];
+    if ((int64_t)n > cap) n = (uint32_t)cap;
+    const uint2 *p = surv + ((size_t)b * L + l) * cap;
+    for (uint32_t e0 = 0; e0 < n; e0 += 64) {
+      const uint32_t e = e0 + lane;
+      const bool valid = e < n;
+      uint2 v = make_uint2(0u, 0u);
+      if (valid) v = p[e];
+      f(v, valid);
+    }
+  }
+}
+
+__global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, const uint32_t *cnt, int64_t L,
+                                                            int64_t cap, const uint2 *sstat, int Kp, uint32_t *mhist,
+                                                            int B, int pass) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
+  const uint2 stt = sstat[b];
+  if (stt.y || stt.x <= (uint32_t)Kp) return;
+  uint32_t prefix = 0;
+  if (pass > 0) prefix = msel_cut(mhist, B, b, (uint32_t)Kp, pass, sh).prefix;
+  const int64_t per = (L + G - 1) / G;
+  const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
+  auto each = [&](auto f) {
+    for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+      if (valid) f(e.x, e.y);
+    });
+  };
+  msel_hist_pass(each, pass, prefix, mhist + ((size_t)pass * B + b) * MSEL_BINS, sh);
+}
+
+__global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, const uint32_t *cnt, int64_t L,
+                                                            int64_t cap, const uint2 *sstat, int Kp,
+                                                            const uint32_t *mhist, int B, uint32_t *mcnt,
+                                                            uint32_t *tiebuf, int32_t *cand_idx, float *cand_score) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
+  const uint2 stt = sstat[b];
+  if (stt.y) return;
+  const bool take_all = stt.x <= (uint32_t)Kp;
+  uint32_t kth = 0;
+  bool all_ties = true;
+  if (!take_all) {
+    const MselCut c = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
+    kth = c.prefix;
+    all_ties = (c.krem == c.cnt);
+  }
+  int32_t *oi = cand_idx + (size_t)b * Kp;
+  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
+  uint32_t *mc = mcnt + (size_t)b * MCNT_STRIDE;
+  const int64_t per = (L + G - 1) / G;
+  const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
+  for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+    const bool at = valid && !take_all && e.x == kth;
+    const bool take = valid && (take_all || e.x > kth || (at && all_ties));
+    const bool tie = at && !all_ties;
+    const uint32_t slot = msel_wave_slot(take, mc);
+    if (take && slot < (uint32_t)Kp) {
+      oi[slot] = (int32_t)e.y;
+      if (os) os[slot] = key_to_f32(e.x);
+    }
+    if (__ballot(tie)) {
+      const uint32_t ts = msel_wave_slot(tie, mc + 1);
+      if (tie && ts < MSEL_TIE_CAP) tiebuf[(size_t)b * MSEL_TIE_CAP + ts] = e.y;
+    }
+  });
+}
+
+__global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat, int Kp, const uint32_t *mhist, int B,
+                                                              uint32_t *mcnt, const uint32_t *tiebuf, uint32_t *flags,
+                                                              uint32_t *gate, int32_t *cand_idx, float *cand_score,
+                                                              int32_t *cand_count) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const uint2 stt = sstat[b];
+  int32_t *oi = cand_idx + (size_t)b * Kp;
+  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
+  uint32_t nout = 0;
+  if (stt.y) {
+    if (tid == 0) {
+      flags[b] = 1u;  // redone by the exact path
+      gate[0] = 1u;
+      cand_count[b] = -1;
+    }
+  } else if (stt.x <= (uint32_t)Kp) {
+    nout = stt.x;
+    if (tid == 0) cand_count[b] = (int32_t)nout;
+  } else {
+    const MselCut c = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
+    nout = (uint32_t)Kp;
+    if (c.krem != c.cnt) {  // only the krem lowest indices of the cnt items tied at the K'-th key are taken
+      if (c.cnt > MSEL_TIE_CAP) {
+        if (tid == 0) mcnt[(size_t)b * MCNT_STRIDE + 2] = 1u;  // left to the single-workgroup selection
+        return;
+      }
+      const uint32_t base = (uint32_t)Kp - c.krem;
+      const float sc = key_to_f32(c.prefix);
+      msel_take_lowest_ties(tiebuf + (size_t)b * MSEL_TIE_CAP, c.cnt, c.krem, sh, [&](uint32_t rank, uint32_t idx) {
+        oi[base + rank] = (int32_t)idx;
+        if (os) os[base + rank] = sc;
+      });
+    }
+    if (tid == 0) cand_count[b] = Kp;
+  }
+  for (int64_t i = nout + tid; i < Kp; i += MSEL_THREADS) {
+    oi[i] = -1;
+    if (os) os[i] = -INFINITY;
+  }
+}
+
+// Single-workgroup form of the same selection.  It runs for queries the multi-workgroup kernels hand over (more than
+// MSEL_TIE_CAP items tied at the K'-th key: `enable`), and after the exact redo (`only_flagged`).
+__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, const uint32_t *cnt, int64_t L,
+                                                                     int64_t cap, const uint2 *sstat, uint32_t *flags,
+                                                                     int Kp, bool only_flagged, const uint32_t *enable,
                                                                      int32_t *cand_idx, float *cand_score,
                                                                      int32_t *cand_count) {
   __shared__ SelectShared sh;
-  __shared__ uint32_t cnt_s[SHARDS];
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
   if (only_flagged && flags[b] != 2u) return;  // 2 = survivor lists rebuilt by the exact path
-  if (tid < SHARDS) cnt_s[tid] = count[(size_t)(b * SHARDS + tid) * COUNT_STRIDE];
-  __syncthreads();
-  uint64_t total = 0;
-  bool overflow = false;
-  for (int i = 0; i < SHARDS; ++i) {
-    total += cnt_s[i];
-    overflow = overflow || (int64_t)cnt_s[i] > cap_s;
-  }
-  const uint2 *list = surv + (size_t)b * SHARDS * cap_s;
+  if (enable && enable[(size_t)b * MCNT_STRIDE] == 0u) return;
+  const uint2 stt = sstat[b];
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
-  const bool underflow = (mode == MOL_HINDEXER_EXACT) && total < (uint64_t)Kp;
-  if (overflow || underflow || (force_redo && !only_flagged)) {
+  if (stt.y) {  // only after the redo: the exact K' items did not fit the lists (see molret.h)
     if (tid == 0) {
-      flags[b] = only_flagged ? 3u : 1u;  // 3 = the exact K' items did not fit the lists (see molret.h)
+      flags[b] = 3u;
       cand_count[b] = -1;
-      if (!only_flagged) gate[0] = 1;
     }
     for (int i = tid; i < Kp; i += SELECT_THREADS) {
       oi[i] = -1;
@@ -384,11 +546,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
     return;
   }
   auto each = [&](auto f) {
-    for (int s = 0; s < SHARDS; ++s) {
-      block_for_each<4>(list + (size_t)s * cap_s, (int64_t)cnt_s[s], [&](int64_t, uint2 e) { f(e.x, e.y); });
-    }
+    for_each_survivor(surv, cnt, L, cap, b, 0, L, SELECT_THREADS / 64, [&](uint2 e, bool valid) {
+      if (valid) f(e.x, e.y);
+    });
   };
-  const bool take_all = total <= (uint64_t)Kp;
+  const bool take_all = stt.x <= (uint32_t)Kp;
   if (!take_all) block_select_kth<true>(each, (uint32_t)Kp, sh);
   if (tid == 0) sh.out_count = 0;
   __syncthreads();
@@ -402,7 +564,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
     }
   });
   __syncthreads();
-  const uint32_t nout = take_all ? (uint32_t)total : (uint32_t)Kp;
+  const uint32_t nout = take_all ? stt.x : (uint32_t)Kp;
   for (int64_t i = nout + tid; i < Kp; i += SELECT_THREADS) {
     oi[i] = -1;
     if (os) os[i] = -INFINITY;
@@ -413,46 +575,93 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
   }
 }
 
+// ---- launch helpers ----------------------------------------------------------------------------------------------
 template <bool F32, int EPI, bool GATHER>
-mol_status_t launch_scan(const ScanArgs &a0, int B, hipStream_t st) {
-  static int sm_count = 0;
-  if (!sm_count) {
+void (*scan_kernel(int nqg))(ScanArgs) {
+  constexpr int DEPTH = 2;
+  return nqg == 4 ? k_stage1_scan<F32, 4, EPI, GATHER, DEPTH>
+                  : (nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH> : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>);
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (!cus) {
     int dev = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      cus = 0;
   }
-  constexpr int DEPTH = F32 ? 2 : 4;
+  return cus;
+}
+
+// Workgroups (of 4 wavefronts) a scan over `ntiles` tiles is launched with: resident blocks, at most one tile each.
+// fixed_grid > 0 forces the grid (the survivor lists are laid out for a given number of wavefronts).
+template <bool F32, int EPI, bool GATHER>
+mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
+  auto kern = scan_kernel<F32, EPI, GATHER>(nqg);
+  const size_t lds = (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0;
+  if (lds > 48 * 1024)
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  int per_sm = 0;
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, lds));
+  if (per_sm < 1) per_sm = 1;
+  if (per_sm > 3) per_sm = 3;
+  const int cus = device_cus();
+  if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
+  int64_t grid = (int64_t)cus * per_sm;
+  const int64_t need = (ntiles + 3) / 4;
+  if (grid > need) grid = need;
+  if (grid < 1) grid = 1;
+  *grid_out = grid;
+  return MOL_OK;
+}
+
+template <bool F32, int EPI, bool GATHER>
+mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStream_t st) {
   const int64_t ntiles = (a0.n_rows + 31) / 32;
   for (int qb = 0; qb < B; qb += 128) {
     ScanArgs a = a0;
     a.qbase = qb;
     const int rem = B - qb;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
-    void (*kern)(ScanArgs) = nqg == 4   ? k_stage1_scan<F32, 4, EPI, GATHER, DEPTH>
-                             : nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH>
-                                        : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>;
-    int per_sm = 0;
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(
-        &per_sm, kern, 256, (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0));
-    if (per_sm < 1) per_sm = 1;
-    if (per_sm > 4) per_sm = 4;
-    int64_t grid = (int64_t)sm_count * per_sm;
-    const int64_t need = (ntiles + 3) / 4;
-    if (grid > need) grid = need;
-    if (grid < 1) grid = 1;
-    size_t lds = 0;
-    if (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) {
-      lds = (size_t)32 * nqg * EXACT_BINS * 4;
-      if (lds > 48 * 1024)
-        HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    }
+    auto kern = scan_kernel<F32, EPI, GATHER>(nqg);
+    int64_t grid = 0;
+    mol_status_t rc = scan_grid<F32, EPI, GATHER>(nqg, ntiles, &grid);
+    if (rc != MOL_OK) return rc;
+    if (fixed_grid > 0) grid = fixed_grid;
+    const size_t lds = (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     HIP_TRY(hipGetLastError());
   }
   return MOL_OK;
 }
 
+// The grid every list-writing scan of a call uses: the smallest over the kernel variants the call will launch, so
+// that all of them can be resident and the list layout (L = 8 * grid lists per query) is the same for all.
+mol_status_t list_scan_grid(bool f32, int B, int64_t N, int64_t *grid_out) {
+  const int64_t ntiles = (N + 31) / 32;
+  int64_t best = -1;
+  for (int qb = 0; qb < B; qb += 128) {
+    const int rem = B - qb;
+    const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
+    int64_t g1 = 0, g2 = 0;
+    mol_status_t rc = f32 ? scan_grid<true, EPI_FILTER, false>(nqg, ntiles, &g1)
+                          : scan_grid<false, EPI_FILTER, false>(nqg, ntiles, &g1);
+    if (rc != MOL_OK) return rc;
+    rc = f32 ? scan_grid<true, EPI_FILTER_EXACT, false>(nqg, ntiles, &g2)
+             : scan_grid<false, EPI_FILTER_EXACT, false>(nqg, ntiles, &g2);
+    if (rc != MOL_OK) return rc;
+    const int64_t g = g1 < g2 ? g1 : g2;
+    if (best < 0 || g < best) best = g;
+  }
+  *grid_out = best;
+  return MOL_OK;
+}
+
 }  // namespace
+
+__global__ void k_zero_u32(uint32_t *p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
 
 // ------------------------------------------------------------------------------------------------ host
 mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, int mode, HindexerPlan *p) {
@@ -468,18 +677,24 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   if (mode == MOL_HINDEXER_EXACT) rank = r_paper + (int64_t)ceil(5.0 * sqrt((double)r_paper)) + 8;
   if (rank > lambda) rank = lambda;
   p->rank = rank;
-  // rows that can land in one shard: tiles t with t % SHARDS == s, 32 rows each
-  const int64_t shard_rows = ((N + 31) / 32 + SHARDS - 1) / SHARDS * 32;
+
+  mol_status_t rc = list_scan_grid(c->stage1_dtype == MOL_F32, B, N, &p->grid);
+  if (rc != MOL_OK) return rc;
+  p->L = p->grid * 8;  // 4 wavefronts per workgroup, 2 lists (lane halves) per wavefront
+  // rows one list can see: the tiles of its wavefront, 16 rows of each
+  const int64_t ntiles = (N + 31) / 32;
+  const int64_t list_rows = (ntiles + p->grid * 4 - 1) / (p->grid * 4) * 16;
   if (p->sampling) {
     const double expect = (double)N * (double)rank / (double)lambda;
-    double cap = expect * (1.0 + 6.0 / sqrt((double)rank)) + 1024;
-    if (cap < (double)Kp + 1024) cap = (double)Kp + 1024;
-    const double per = cap / SHARDS;
-    int64_t cap_s = (int64_t)(per + 6.0 * sqrt(per)) + 64;
-    if (cap_s > shard_rows) cap_s = shard_rows;
-    p->cap = cap_s;
+    double tot = expect * (1.0 + 6.0 / sqrt((double)rank)) + 1024;
+    if (tot < (double)Kp + 1024) tot = (double)Kp + 1024;
+    const double per = tot / (double)p->L;
+    int64_t cap = (int64_t)(per + 8.0 * sqrt(per) + 8.0);
+    cap = (cap + 1) & ~(int64_t)1;
+    if (cap > list_rows) cap = list_rows;
+    p->cap = cap;
   } else {
-    p->cap = shard_rows;
+    p->cap = list_rows;
   }
   const int64_t lam_pad = (p->lambda + 31) / 32 * 32;
   size_t off = 0;
@@ -490,11 +705,19 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->off_thr = off;
   off = align_up(off + (size_t)B * 4, 256);
   p->off_count = off;
-  off = align_up(off + (size_t)B * SHARDS * COUNT_STRIDE * 4, 256);
+  off = align_up(off + (size_t)B * p->L * 4, 256);
   p->off_flags = off;
   off = align_up(off + (size_t)B * 4, 256);
+  p->off_sstat = off;
+  off = align_up(off + (size_t)B * 8, 256);
   p->off_surv = off;
-  off = align_up(off + (size_t)B * SHARDS * p->cap * 8, 256);
+  off = align_up(off + (size_t)B * p->L * p->cap * 8, 256);
+  p->off_mhist = off;  // two sets of radix-select histograms (sampled threshold, survivors), then counters
+  off = align_up(off + (size_t)2 * MSEL_PASSES * B * MSEL_BINS * 4, 256);
+  p->off_mcnt = off;
+  off = align_up(off + (size_t)B * MCNT_STRIDE * 4, 256);
+  p->off_tie = off;
+  off = align_up(off + (size_t)B * MSEL_TIE_CAP * 4, 256);
   p->off_hist = off;
   off = align_up(off + (size_t)B * EXACT_BINS * 4, 256);
   p->off_state = off;
@@ -508,8 +731,9 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
                           int32_t *cand_count, char *ws, hipStream_t st) {
   const bool f32 = (c->stage1_dtype == MOL_F32);
   float *thr = reinterpret_cast<float *>(ws + p.off_thr);
-  uint32_t *count = reinterpret_cast<uint32_t *>(ws + p.off_count);
+  uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + p.off_count);
   uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
+  uint2 *sstat = reinterpret_cast<uint2 *>(ws + p.off_sstat);
   uint2 *surv = reinterpret_cast<uint2 *>(ws + p.off_surv);
   uint32_t *hist = reinterpret_cast<uint32_t *>(ws + p.off_hist);
   uint32_t *gate = reinterpret_cast<uint32_t *>(ws + p.off_state);
@@ -517,14 +741,25 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   const bool force_redo = (mode & MOL_HINDEXER_FORCE_REDO) != 0;
   mode &= ~MOL_HINDEXER_FORCE_REDO;
 
+  uint32_t *mhist = reinterpret_cast<uint32_t *>(ws + p.off_mhist);
+  uint32_t *mhist2 = mhist + (size_t)MSEL_PASSES * B * MSEL_BINS;
+  uint32_t *mcnt = reinterpret_cast<uint32_t *>(ws + p.off_mcnt);
+  uint32_t *tiebuf = reinterpret_cast<uint32_t *>(ws + p.off_tie);
+  {  // histograms and counters of both selections start at zero (they are contiguous in the workspace)
+    const size_t nz = (p.off_tie - p.off_mhist) / 4;
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((nz + 1023) / 1024)), dim3(256), 0, st, mhist, nz);
+    HIP_TRY(hipGetLastError());
+  }
+
   ScanArgs a = {};
   a.X = static_cast<const char *>(c->stage1);
   a.Q = static_cast<const char *>(q1);
   a.B = B;
   a.thr = thr;
-  a.count = count;
+  a.cnt = cnt;
   a.surv = surv;
-  a.cap_s = p.cap;
+  a.L = p.L;
+  a.cap = p.cap;
 
   if (p.sampling) {
     int32_t *samp = reinterpret_cast<int32_t *>(ws + p.off_sample);
@@ -546,15 +781,21 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     mol_status_t rc;
     {
       ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
-      rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, st) : launch_scan<false, EPI_KEYS, true>(s, B, st);
+      rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, 0, st) : launch_scan<false, EPI_KEYS, true>(s, B, 0, st);
     }
     if (rc != MOL_OK) return rc;
     ProfScope ps(MOL_PROF_THRESHOLD, st);
-    hipLaunchKernelGGL(k_sample_threshold, dim3(B), dim3(SELECT_THREADS), 0, st, skeys, lam_pad, p.lambda,
-                       (uint32_t)p.rank, thr, count, flags, gate);
+    int G = 512 / B;
+    G = G < 1 ? 1 : (G > 32 ? 32 : G);
+    for (int pass = 0; pass < MSEL_PASSES; ++pass) {
+      hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
+                         mhist, B, pass);
+      HIP_TRY(hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank, thr, flags, gate);
     HIP_TRY(hipGetLastError());
   } else {
-    hipLaunchKernelGGL(k_init_all_pass, dim3((B * SHARDS + 255) / 256), dim3(256), 0, st, thr, count, flags, gate, B);
+    hipLaunchKernelGGL(k_init_all_pass, dim3((B + 255) / 256), dim3(256), 0, st, thr, flags, gate, B);
     HIP_TRY(hipGetLastError());
   }
 
@@ -562,21 +803,38 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   mol_status_t rc;
   {
     ProfScope ps(MOL_PROF_SCAN_FILTER, st);
-    rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, st) : launch_scan<false, EPI_FILTER, false>(a, B, st);
+    rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, p.grid, st) : launch_scan<false, EPI_FILTER, false>(a, B, p.grid, st);
   }
   if (rc != MOL_OK) return rc;
 
   ProfScope ps(MOL_PROF_SELECT, st);
-  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, gate, Kp,
-                     mode, force_redo, false, cand_idx, cand_score, cand_count);
-  HIP_TRY(hipGetLastError());
+  {
+    hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, force_redo, flags, false,
+                       sstat);
+    HIP_TRY(hipGetLastError());
+    int G = 1024 / B;
+    G = G < 1 ? 1 : (G > 32 ? 32 : G);
+    for (int pass = 0; pass < MSEL_PASSES; ++pass) {
+      hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
+                         pass);
+      HIP_TRY(hipGetLastError());
+    }
+    hipLaunchKernelGGL(k_surv_emit, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
+                       mcnt, tiebuf, cand_idx, cand_score);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, B, mcnt, tiebuf, flags, gate,
+                       cand_idx, cand_score, cand_count);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, flags, Kp,
+                       false, mcnt + 2, cand_idx, cand_score, cand_count);
+    HIP_TRY(hipGetLastError());
+  }
 
   // exact redo of flagged queries; every kernel below returns at once when none is flagged
   a.state = state;
   a.hist = hist;
   auto step = [&](int stage) -> mol_status_t {
-    hipLaunchKernelGGL(k_exact_step, dim3(B), dim3(EXACT_BINS), 0, st, stage, state, hist, gate, flags, count,
-                       (uint32_t)Kp);
+    hipLaunchKernelGGL(k_exact_step, dim3(B), dim3(EXACT_BINS), 0, st, stage, state, hist, gate, flags, (uint32_t)Kp);
     HIP_TRY(hipGetLastError());
     return MOL_OK;
   };
@@ -585,18 +843,21 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     a.shift = 24 - 8 * (pass & 3);
     a.gate = gate + (pass < 4 ? 0 : 1);
     if (pass < 4)
-      rc = f32 ? launch_scan<true, EPI_HIST_KEY, false>(a, B, st) : launch_scan<false, EPI_HIST_KEY, false>(a, B, st);
+      rc = f32 ? launch_scan<true, EPI_HIST_KEY, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_KEY, false>(a, B, 0, st);
     else
-      rc = f32 ? launch_scan<true, EPI_HIST_IDX, false>(a, B, st) : launch_scan<false, EPI_HIST_IDX, false>(a, B, st);
+      rc = f32 ? launch_scan<true, EPI_HIST_IDX, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_IDX, false>(a, B, 0, st);
     if (rc == MOL_OK) rc = step(pass + 1);
   }
   if (rc == MOL_OK) rc = step(9);
   if (rc != MOL_OK) return rc;
   a.gate = gate;
-  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, st) : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, st);
+  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, p.grid, st)
+           : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, p.grid, st);
   if (rc != MOL_OK) return rc;
-  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, p.cap, count, flags, gate, Kp,
-                     mode, false, true, cand_idx, cand_score, cand_count);
+  hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, false, flags, true, sstat);
+  HIP_TRY(hipGetLastError());
+  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, flags, Kp,
+                     true, nullptr, cand_idx, cand_score, cand_count);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
