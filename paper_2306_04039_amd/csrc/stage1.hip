@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
   uint32_t cnt[NQG];
   uint2 *lst[NQG];
+  const uint32_t cap32 = (uint32_t)a.cap;
 #pragma unroll
   for (int g = 0; g < NQG; ++g) {
     const int b = a.qbase + 32 * g + r;
@@ -164,6 +165,12 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
 
       // acc[g][j]: item row 8*(j/4) + 4*h + j%4 of the tile, query qbase + 32*g + r
       const int64_t row0 = tile * 32 + 4 * h;
+      uint32_t vmask = 0xffffu;  // rows of this lane that exist (only the last tile can be partial)
+      if (tile == ntiles - 1) {
+        vmask = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) vmask |= (row0 + 8 * (j >> 2) + (j & 3) < a.n_rows) ? (1u << j) : 0u;
+      }
 #pragma unroll
       for (int g = 0; g < NQG; ++g) {
         const int b = a.qbase + 32 * g + r;
@@ -171,12 +178,13 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
           uint32_t mask = 0;
 #pragma unroll
           for (int j = 0; j < 16; ++j) mask |= (acc[g][j] > thr[g]) ? (1u << j) : 0u;
+          mask &= vmask;
           if (mask) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-              const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
-              if (((mask >> j) & 1u) && n < a.n_rows) {
-                if ((int64_t)cnt[g] < a.cap) lst[g][cnt[g]] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)n);
+              if ((mask >> j) & 1u) {
+                if (cnt[g] < cap32)
+                  lst[g][cnt[g]] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
                 ++cnt[g];
               }
             }
@@ -401,22 +409,40 @@ __global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_
   }
 }
 
-// Walks lists [lo, hi) of query b, one list per wavefront at a time, lanes across the entries.  f(entry, valid) is
-// called the same number of times by all 64 lanes of a wavefront (so it may use wavefront collectives).
+// Walks lists [lo, hi) of query b.  A wavefront takes 64 lists at a time: the lanes fetch the 64 counts with one load,
+// then the lists are read four at a time (independent loads in flight), lanes across the entries of a list.
+// f(entry, valid) is called the same number of times by all 64 lanes of a wavefront (wavefront collectives are safe).
 template <class F>
 __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int b,
                                                   int64_t lo, int64_t hi, int nwaves_in_block, F f) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  for (int64_t l = lo + wv; l < hi; l += nwaves_in_block) {
-    uint32_t n = cnt[(size_t)b * L + l];
-    if ((int64_t)n > cap) n = (uint32_t)cap;
-    const uint2 *p = surv + ((size_t)b * L + l) * cap;
-    for (uint32_t e0 = 0; e0 < n; e0 += 64) {
-      const uint32_t e = e0 + lane;
-      const bool valid = e < n;
-      uint2 v = make_uint2(0u, 0u);
-      if (valid) v = p[e];
-      f(v, valid);
+  const uint32_t cap32 = (uint32_t)cap;
+  for (int64_t l0 = lo + (int64_t)wv * 64; l0 < hi; l0 += (int64_t)nwaves_in_block * 64) {
+    uint32_t mine = 0;
+    if (l0 + lane < hi) mine = cnt[(size_t)b * L + l0 + lane];
+    if (mine > cap32) mine = cap32;
+    const int nl = (int)((hi - l0) < 64 ? (hi - l0) : 64);
+    const uint2 *base = surv + ((size_t)b * L + l0) * cap;
+    for (int i0 = 0; i0 < nl; i0 += 4) {
+      uint32_t n[4];
+      uint2 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        n[u] = (i0 + u < nl) ? (uint32_t)__shfl((int)mine, i0 + u) : 0u;
+        v[u] = make_uint2(0u, 0u);
+        if ((uint32_t)lane < n[u]) v[u] = base[(size_t)(i0 + u) * cap + lane];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (n[u]) f(v[u], (uint32_t)lane < n[u]);
+        for (uint32_t e0 = 64; e0 < n[u]; e0 += 64) {  // lists longer than a wavefront (rare)
+          const uint32_t e = e0 + lane;
+          const bool valid = e < n[u];
+          uint2 w = make_uint2(0u, 0u);
+          if (valid) w = base[(size_t)(i0 + u) * cap + e];
+          f(w, valid);
+        }
+      }
     }
   }
 }

@@ -1,0 +1,66 @@
+"""Full-size parity: the 100M-item workload in the launch configuration bench.py times, checked on sampled outputs
+the oracle can compute one by one (the corpus does not fit the host, so rows are fetched from the device as needed)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import retrieval_oracle as orc
+from parity_util import assert_scores_close, assert_sorted_desc, assert_topk_set, bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+S1_TOL = 2e-6
+
+
+def test_c4_100m_two_stage_sampled_parity():
+    import paper_2306_04039_amd as m
+    free, total = torch.cuda.mem_get_info()
+    if total < 200 * 2**30:
+        pytest.skip("needs the 288 GB device")
+    wl = synth.CONFIGS["C4"]
+    cen = synth.make_centres(wl, DEV)
+    items = synth.make_items(wl, cen)
+    q = synth.make_queries(wl, cen)
+    gw = synth.make_gate_weights(wl, DEV)
+    corpus = m.mol_corpus_pack(items["x1"], items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                               logit_scale=wl.logit_scale, act=wl.act, borrow=True)
+    B, Kp, k = wl.B, wl.Kp, wl.k
+    lam = m.hindexer_default_lambda(corpus, Kp)
+    ws1 = torch.empty(m.hindexer_workspace_bytes(corpus, B, Kp, lam), dtype=torch.uint8, device=DEV)
+    ws2 = torch.empty(m.mol_workspace_bytes(corpus, B, Kp, k), dtype=torch.uint8, device=DEV)
+    ci, cs, cc = m.hindexer_topk(corpus, q["q1"], Kp, lam=lam, seed=1003, workspace=ws1)
+    idx, sc = m.mol_topk(corpus, q["F"], q["gu"], ci, k, workspace=ws2)
+    torch.cuda.synchronize()
+    assert int(cc.min()) == Kp and int(cc.max()) == Kp
+
+    q1b, Fb, gub = bits(q["q1"]), bits(q["F"]), bits(q["gu"])
+    g = torch.Generator(device=DEV).manual_seed(11)
+    probe = torch.randint(0, wl.N, (3_000_000,), generator=g, device=DEV)            # rows checked for omissions
+    probe_x = bits(items["x1"][probe])
+    probe_np = probe.cpu().numpy()
+    for b in (0, 13, 31):
+        cand = ci[b].long()
+        assert int(cand.min()) >= 0 and cand.unique().numel() == Kp, "candidates must be K' distinct items"
+        # stage 1: every candidate's score, recomputed in fp64 from the stored bits
+        s_cand = orc.stage1_scores(q1b[b:b + 1], bits(items["x1"][cand]))[0]
+        np.testing.assert_allclose(cs[b].cpu().numpy(), s_cand, rtol=0, atol=S1_TOL)
+        boundary = s_cand.min()
+        # ... and no probed item outside the candidate set beats the boundary by more than the tolerance
+        s_probe = orc.stage1_scores(q1b[b:b + 1], probe_x)[0]
+        inside = np.isin(probe_np, cand.cpu().numpy())
+        assert np.all(s_probe[~inside] <= boundary + S1_TOL), "an item above the K'-th score was left out"
+        assert inside.sum() >= 1000                      # the probe does hit the candidate region (Kp/N * 3e6 = 3000)
+        assert np.all(s_probe[inside] >= boundary - S1_TOL)
+        # stage 2: MoL scores of all K' candidates from the oracle, then its top-k against the GPU's
+        rows = cand.cpu().numpy()
+        model = orc.MolModel(bits(items["G"][cand]), bits(items["gx"][cand]), bits(gw.W1), bits(gw.b1), bits(gw.W2),
+                             bits(gw.b2), wl.logit_scale, wl.act)
+        phi = orc.mol_scores_for(model, orc.as_f64(Fb[b]), orc.as_f64(gub[b]), np.arange(Kp))
+        lookup = dict(zip(rows.tolist(), phi.tolist()))
+        kth = np.sort(phi)[::-1][k - 1]
+        got_idx, got_sc = idx[b].cpu().numpy(), sc[b].cpu().numpy()
+        assert_topk_set(got_idx, lookup, k, 2e-3 * abs(kth) + 1e-4, f"query {b}")
+        assert_scores_close(got_sc, [lookup[i] for i in got_idx.tolist()], wl.logit_scale, f"query {b}")
+        assert_sorted_desc(got_sc, got_idx, f"query {b}")
+    corpus.free()
