@@ -36,7 +36,6 @@ struct MolArgs {
   int B;
   int act;
   float logit_scale;
-  int query_fastest;     // tile order: 1 = consecutive tiles are different queries of the same item block
 };
 
 template <int K_U, int K_X, int D_P, int H>
@@ -60,7 +59,13 @@ __device__ __forceinline__ float act_fn(float x, int act) {
   return act == MOL_ACT_RELU ? fmaxf(x, 0.f) : x / (1.f + __expf(-x));
 }
 
-template <int K_U, int K_X, int D_P, int H>
+// EXH = false: tiles of 32 candidates of one query (cand list or not), every tile gathers its own rows.
+// EXH = true : exhaustive scoring (every item for every query).  A wavefront takes a block of 32 consecutive items,
+//              loads their rows and cached gate halves into registers ONCE and walks a chunk of queries over them, so
+//              the item tensors are read once per query chunk instead of once per query (the per-query form moves
+//              B x the corpus through L2 and is bound by that, not by the matrix cores).
+#define MOL_QCHUNK 256
+template <int K_U, int K_X, int D_P, int H, bool EXH>
 __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
   constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
@@ -91,21 +96,34 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 
   int cur_b = -1;
   uint4 Ff[SA];
-  for (int64_t tile = wave; tile < ntiles; tile += nwaves) {
+  constexpr int PD = RT < 8 ? RT : 8;
+  uint4 A[PD][SA];
+  uint2 xi[MT][4];
+  int idx = -1, idxc = 0;
+  bool ok = false;
+  const int64_t n_qch = EXH ? (a.B + MOL_QCHUNK - 1) / MOL_QCHUNK : 1;
+  const int64_t ntasks = EXH ? tpq * n_qch : ntiles;
+  for (int64_t task = wave; task < ntasks; task += nwaves) {
+   const int b_lo = EXH ? (int)(task % n_qch) * MOL_QCHUNK : 0;
+   const int b_hi = EXH ? (b_lo + MOL_QCHUNK < a.B ? b_lo + MOL_QCHUNK : a.B) : 1;
+   for (int bq = b_lo; bq < b_hi; ++bq) {
     int b;
     int64_t c0;
-    if (a.query_fastest) {
-      b = (int)(tile % a.B);
-      c0 = (tile / a.B) << 5;
+    if (EXH) {
+      b = bq;
+      c0 = (task / n_qch) << 5;
     } else {
-      b = (int)(tile / tpq);
-      c0 = (tile % tpq) << 5;
+      b = (int)(task / tpq);
+      c0 = (task % tpq) << 5;
     }
+    const bool new_items = !EXH || bq == b_lo;
     const int64_t cpos = c0 + c;
-    int idx = -1;
-    if (cpos < a.Kp) idx = a.cand ? a.cand[(size_t)b * a.Kp + cpos] : (int)cpos;
-    const bool ok = idx >= 0 && idx < a.N;
-    const int idxc = ok ? idx : 0;
+    if (new_items) {
+      idx = -1;
+      if (cpos < a.Kp) idx = a.cand ? a.cand[(size_t)b * a.Kp + cpos] : (int)cpos;
+      ok = idx >= 0 && idx < a.N;
+      idxc = ok ? idx : 0;
+    }
 
     if (b != cur_b) {
       cur_b = b;
@@ -116,8 +134,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     }
 
     // item half of layer 1 for this lane's candidate: hidden units 32*mt + 8*q + 4*h + {0..3}
-    uint2 xi[MT][4];
-    {
+    if (new_items) {
       const char *xp = a.xi + ((size_t)idxc * H + 4 * h) * 2;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
@@ -126,8 +143,6 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     }
 
     // ---- A: component logits -> LDS tile --------------------------------------------------------------
-    constexpr int PD = RT < 8 ? RT : 8;
-    uint4 A[PD][SA];
     auto load_rows = [&](uint4(&dst)[SA], int rt) {
       const int ci = rt * CPR + r16 / K_X;
       const int nidx = __shfl(idxc, ci);
@@ -135,8 +150,10 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 #pragma unroll
       for (int s = 0; s < SA; ++s) dst[s] = ld16(rowp + 64 * s);
     };
+    if (new_items || RT > PD) {
 #pragma unroll
-    for (int i = 0; i < PD; ++i) load_rows(A[i], i);
+      for (int i = 0; i < PD; ++i) load_rows(A[i], i);
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -255,6 +272,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     // the next tile overwrites the LDS logit tile: all lanes must be done reading it
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
+   }
   }
 }
 
@@ -269,10 +287,10 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
   U[i] = acc;
 }
 
-template <int K_U, int K_X, int D_P, int H>
+template <int K_U, int K_X, int D_P, int H, bool EXH>
 mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
-  auto kern = k_mol_score<K_U, K_X, D_P, H>;
+  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH>;
   static bool configured = false;
   static int per_sm = 1, sm_count = 0;
   if (!configured) {
@@ -285,7 +303,7 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
     if (per_sm < 1) per_sm = 1;
     configured = true;
   }
-  const int64_t ntiles = ((a.Kp + 31) / 32) * a.B;
+  const int64_t ntiles = EXH ? ((a.Kp + 31) / 32) * ((a.B + MOL_QCHUNK - 1) / MOL_QCHUNK) : ((a.Kp + 31) / 32) * a.B;
   int64_t grid = (int64_t)sm_count * per_sm;
   const int64_t need = (ntiles + 3) / 4;
   if (grid > need) grid = need;
@@ -343,9 +361,9 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.B = B;
   a.act = c->act;
   a.logit_scale = c->logit_scale;
-  a.query_fastest = cand_idx ? 0 : 1;
 #define X(KU, KX, DP, HH) \
-  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_shape<KU, KX, DP, HH>(a, st);
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH)                                   \
+    return cand_idx ? launch_shape<KU, KX, DP, HH, false>(a, st) : launch_shape<KU, KX, DP, HH, true>(a, st);
   MOL_SHAPES(X)
 #undef X
   return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", c->k_u, c->k_x, c->d_p, c->H);

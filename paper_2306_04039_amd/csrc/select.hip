@@ -99,10 +99,12 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_fin_finish(int k, const uint32
       });
   }
   __syncthreads();
-  // bitonic sort of TOPK_MAX slots by (key desc, idx asc)
-  for (int size = 2; size <= TOPK_MAX; size <<= 1) {
+  // bitonic sort of the first `width` slots (the power of two covering k) by (key desc, idx asc)
+  int width = 64;
+  while (width < k) width <<= 1;
+  for (int size = 2; size <= width; size <<= 1) {
     for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      for (int i = tid; i < TOPK_MAX; i += MSEL_THREADS) {
+      for (int i = tid; i < width; i += MSEL_THREADS) {
         const int j = i ^ stride;
         if (j > i) {
           const uint32_t ki = skey[i], kj = skey[j], ii = sidx[i], ij = sidx[j];

@@ -487,11 +487,34 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   uint32_t *mc = mcnt + (size_t)b * MCNT_STRIDE;
   const int64_t per = (L + G - 1) / G;
   const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
+  // Two walks over this workgroup's lists: the first counts what each wavefront will emit, one atomic reserves the
+  // workgroup's output range, the second writes (a returning atomic per wavefront step would serialise on latency).
+  __shared__ uint32_t wave_tot[MSEL_THREADS / 64];
+  __shared__ uint32_t block_base;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  uint32_t mine = 0;
+  for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+    const bool at = valid && !take_all && e.x == kth;
+    const bool take = valid && (take_all || e.x > kth || (at && all_ties));
+    mine += (uint32_t)__popcll(__ballot(take));
+  });
+  if (lane == 0) wave_tot[wv] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t tot = 0;
+    for (int i = 0; i < MSEL_THREADS / 64; ++i) tot += wave_tot[i];
+    block_base = tot ? atomicAdd(mc, tot) : 0u;
+  }
+  __syncthreads();
+  uint32_t off = block_base;
+  for (int i = 0; i < wv; ++i) off += wave_tot[i];
   for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
     const bool at = valid && !take_all && e.x == kth;
     const bool take = valid && (take_all || e.x > kth || (at && all_ties));
     const bool tie = at && !all_ties;
-    const uint32_t slot = msel_wave_slot(take, mc);
+    const uint64_t m = __ballot(take);
+    const uint32_t slot = off + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+    off += (uint32_t)__popcll(m);
     if (take && slot < (uint32_t)Kp) {
       oi[slot] = (int32_t)e.y;
       if (os) os[slot] = key_to_f32(e.x);
