@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
         const uint4 af = ld16(w1x + ((size_t)(32 * mt + c) * DG + 16 * s + 8 * h) * 2);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bfrag[s]), acc, 0, 0, 0);
       }
+      mfma_settle(acc);
       if (ok) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -160,7 +161,7 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   c->act = cfg->act;
   c->logit_scale = cfg->logit_scale;
   c->flags = cfg->flags;
-  hipGetDevice(&c->device);
+  (void)hipGetDevice(&c->device);
 
   const int P = c->P, H = c->H;
   const int MT = H / 32, S1 = P / 16, PT = (P + 31) / 32, S2 = H / 16;

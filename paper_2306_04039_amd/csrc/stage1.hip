@@ -10,9 +10,9 @@
 //
 // Survivor lists.  In the 32x32 score tile a lane always holds scores of ONE query (column = lane % 32), so every
 // (wavefront, lane) pair appends the survivors it finds to a list of its own and counts them in a register: no
-// atomics, nothing to wait for (with a shared per-query counter the scan spent 10 % of its time waiting for
-// returning atomics).  A query therefore owns L = 2 * (number of wavefronts) short lists; tile t goes to wavefront
-// t mod W, so each list is a deterministic set whatever the timing.
+// atomics in the scan.  A query therefore owns L = 2 * (number of wavefronts) short lists; which wavefront gets a tile
+// is fixed by the tile number, so each list is a deterministic set whatever the timing.  The lists one wavefront
+// writes are adjacent in memory ([list][query][slot]).
 #include <math.h>
 #include <stdlib.h>
 
@@ -28,15 +28,17 @@ enum { EPI_FILTER = 0, EPI_KEYS = 1, EPI_HIST_KEY = 2, EPI_HIST_IDX = 3, EPI_FIL
 // select over recomputed scores.  Four scans histogram the 8-bit digits of the score key (most significant first)
 // and give the exact K'-th key; if only some of the items tied at that key may be taken, four more scans do the same
 // on the item index among the ties (lowest indices win).  A last scan then keeps exactly the K' items
-// {key > tkey} U {key == tkey, idx <= idx_limit}.  Every kernel of the chain returns at once when no query is
-// flagged, which is the normal case.
+// {key > tkey} U {key == tkey, idx <= idx_limit} and writes them straight to the output (one counter per query hands
+// out the slots: the K' items may sit in consecutive rows, e.g. a run of duplicates, so per-wavefront lists of bounded
+// size cannot hold them).  Every kernel of the chain returns at once when no query is flagged, the normal case.
 struct ExactState {
   uint32_t active;     // 0 not redone, 1 key passes, 2 index passes, 3 threshold known
   uint32_t prefix;     // digits found so far (of the key, then of ~idx)
   uint32_t krem;       // rank still to resolve
   uint32_t tkey;       // exact K'-th key
   uint32_t idx_limit;  // ties at tkey are taken while idx <= idx_limit
-  uint32_t pad[3];
+  uint32_t emitted;    // output slots handed out by the last scan
+  uint32_t pad[2];
 };
 #define EXACT_BINS 256
 
@@ -50,12 +52,15 @@ struct ScanArgs {
   int qbase;             // first query handled by this launch
   const float *thr;      // FILTER: per-query threshold (strict >)
   uint32_t *cnt;         // FILTER*: [B][L] survivors found per list (may exceed cap: overflow)
-  uint2 *surv;           // FILTER*: [B][L][cap] (key, idx)
+  uint2 *surv;           // FILTER*: [L][B][cap] (key, idx): the lists one wavefront writes are adjacent in memory
   int64_t L;             // lists per query = 2 * wavefronts of the launch
   int64_t cap;           // capacity of one list
   uint32_t *skeys;       // KEYS: [B][skeys_stride] score keys
   int64_t skeys_stride;
-  const ExactState *state;  // exact redo: per-query state
+  ExactState *state;        // exact redo: per-query state
+  int32_t *out_idx;         // FILTER_EXACT: [B][Kp] candidates, written directly
+  float *out_score;         // FILTER_EXACT: [B][Kp] or NULL
+  int Kp;
   uint32_t *hist;           // exact redo: [B][EXACT_BINS] digit histogram
   const uint32_t *gate;     // exact redo: the kernel returns at once when *gate == 0
   int shift;                // exact redo: bit position of the digit
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   constexpr int ROWB = F32 ? 256 : 128;
   constexpr bool REDO = EPI >= EPI_HIST_KEY;
   constexpr bool HIST = EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX;
-  constexpr bool LISTS = EPI == EPI_FILTER || EPI == EPI_FILTER_EXACT;
+  constexpr bool LISTS = EPI == EPI_FILTER;
   const int lane = threadIdx.x & 63;
   const int r = lane & 31, h = lane >> 5;
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -103,7 +108,7 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
     cnt[g] = 0;
     lst[g] = nullptr;
     if constexpr (LISTS) {
-      if (b < a.B) lst[g] = a.surv + ((size_t)b * a.L + wave * 2 + h) * a.cap;
+      if (b < a.B) lst[g] = a.surv + ((size_t)(wave * 2 + h) * a.B + b) * a.cap;
     }
     if constexpr (REDO) {
       if (b < a.B) {
@@ -129,15 +134,21 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   };
 
   uint4 buf[DEPTH][NCH];
+  // A wavefront reads TILE_RUN consecutive tiles (16 KB), then jumps by the whole grid: the grid as a whole sweeps the
+  // table front to back while each wavefront's loads stay within a DRAM page for a few steps.
+  constexpr int64_t TILE_RUN = 4;
+  const int64_t n_it = (ntiles + nwaves * TILE_RUN - 1) / (nwaves * TILE_RUN) * TILE_RUN;  // tiles per wavefront
+  auto tile_of = [&](int64_t it) -> int64_t { return ((it / TILE_RUN) * nwaves + wave) * TILE_RUN + it % TILE_RUN; };
 #pragma unroll
   for (int i = 0; i < DEPTH; ++i)
-    if (wave + i * nwaves < ntiles) load_tile(buf[i], wave + i * nwaves);
+    if (i < n_it && tile_of(i) < ntiles) load_tile(buf[i], tile_of(i));
 
-  for (int64_t tile0 = wave; tile0 < ntiles; tile0 += DEPTH * nwaves) {
+  for (int64_t it0 = 0; it0 < n_it; it0 += DEPTH) {
 #pragma unroll
     for (int i = 0; i < DEPTH; ++i) {
-      const int64_t tile = tile0 + i * nwaves;
-      if (tile >= ntiles) break;
+      if (it0 + i >= n_it) break;
+      const int64_t tile = tile_of(it0 + i);
+      if (tile >= ntiles) break;  // tile_of grows with its argument: nothing valid follows
       f32x16 acc[NQG];
 #pragma unroll
       for (int g = 0; g < NQG; ++g)
@@ -160,8 +171,11 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
           }
         }
       }
-      const int64_t tnext = tile + DEPTH * nwaves;
-      if (tnext < ntiles) load_tile(buf[i], tnext);
+      if (it0 + i + DEPTH < n_it) {
+        const int64_t tnext = tile_of(it0 + i + DEPTH);
+        if (tnext < ntiles) load_tile(buf[i], tnext);
+      }
+      mfma_settle();
 
       // acc[g][j]: item row 8*(j/4) + 4*h + j%4 of the tile, query qbase + 32*g + r
       const int64_t row0 = tile * 32 + 4 * h;
@@ -196,8 +210,11 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
               const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
               const uint32_t k = f32_to_key(acc[g][j]);
               if ((k > st_tkey[g] || (k == st_tkey[g] && (uint32_t)n <= st_ilim[g])) && n < a.n_rows) {
-                if ((int64_t)cnt[g] < a.cap) lst[g][cnt[g]] = make_uint2(k, (uint32_t)n);
-                ++cnt[g];
+                const uint32_t slot = atomicAdd(&a.state[b].emitted, 1u);
+                if (slot < (uint32_t)a.Kp) {  // exactly K' items qualify; the check only guards the buffer
+                  a.out_idx[(size_t)b * a.Kp + slot] = (int32_t)n;
+                  if (a.out_score) a.out_score[(size_t)b * a.Kp + slot] = key_to_f32(k);
+                }
               }
             }
           }
@@ -232,7 +249,7 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
 #pragma unroll
     for (int g = 0; g < NQG; ++g) {
       const int b = a.qbase + 32 * g + r;
-      if (b < a.B && (EPI == EPI_FILTER || st_active[g] == 3u)) a.cnt[(size_t)b * a.L + wave * 2 + h] = cnt[g];
+      if (b < a.B) a.cnt[(size_t)b * a.L + wave * 2 + h] = cnt[g];
     }
   }
   if constexpr (HIST) {
@@ -381,11 +398,9 @@ __global__ void k_init_all_pass(float *thr, uint32_t *flags, uint32_t *gate, int
 // sstat[b] = {survivors of query b, 1 if its lists cannot give the answer}: a list overflowed, or (exact mode) fewer
 // than K' survived, or the caller asked for the redo.  Such a query is left to the exact redo.
 __global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_t L, int64_t cap, int Kp, int mode,
-                                                     bool force, const uint32_t *flags, bool only_flagged,
-                                                     uint2 *sstat) {
+                                                     bool force, uint2 *sstat) {
   __shared__ uint32_t s_tot[4], s_ovf[4];
   const int b = blockIdx.x;
-  if (only_flagged && flags[b] != 2u) return;
   uint32_t tot = 0, ovf = 0;
   for (int64_t i = threadIdx.x; i < L; i += 256) {
     const uint32_t c = cnt[(size_t)b * L + i];
@@ -413,7 +428,7 @@ __global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_
 // then the lists are read four at a time (independent loads in flight), lanes across the entries of a list.
 // f(entry, valid) is called the same number of times by all 64 lanes of a wavefront (wavefront collectives are safe).
 template <class F>
-__device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int b,
+__device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int B, int b,
                                                   int64_t lo, int64_t hi, int nwaves_in_block, F f) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t cap32 = (uint32_t)cap;
@@ -422,7 +437,8 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
     if (l0 + lane < hi) mine = cnt[(size_t)b * L + l0 + lane];
     if (mine > cap32) mine = cap32;
     const int nl = (int)((hi - l0) < 64 ? (hi - l0) : 64);
-    const uint2 *base = surv + ((size_t)b * L + l0) * cap;
+    const uint2 *base = surv + ((size_t)l0 * B + b) * cap;  // list l of query b starts at (l * B + b) * cap
+    const size_t lstride = (size_t)B * cap;
     for (int i0 = 0; i0 < nl; i0 += 4) {
       uint32_t n[4];
       uint2 v[4];
@@ -430,7 +446,7 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
       for (int u = 0; u < 4; ++u) {
         n[u] = (i0 + u < nl) ? (uint32_t)__shfl((int)mine, i0 + u) : 0u;
         v[u] = make_uint2(0u, 0u);
-        if ((uint32_t)lane < n[u]) v[u] = base[(size_t)(i0 + u) * cap + lane];
+        if ((uint32_t)lane < n[u]) v[u] = base[(size_t)(i0 + u) * lstride + lane];
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -439,7 +455,7 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
           const uint32_t e = e0 + lane;
           const bool valid = e < n[u];
           uint2 w = make_uint2(0u, 0u);
-          if (valid) w = base[(size_t)(i0 + u) * cap + e];
+          if (valid) w = base[(size_t)(i0 + u) * lstride + e];
           f(w, valid);
         }
       }
@@ -459,7 +475,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, c
   const int64_t per = (L + G - 1) / G;
   const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
   auto each = [&](auto f) {
-    for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+    for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
       if (valid) f(e.x, e.y);
     });
   };
@@ -493,7 +509,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   __shared__ uint32_t block_base;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   uint32_t mine = 0;
-  for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+  for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
     const bool at = valid && !take_all && e.x == kth;
     const bool take = valid && (take_all || e.x > kth || (at && all_ties));
     mine += (uint32_t)__popcll(__ballot(take));
@@ -508,7 +524,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   __syncthreads();
   uint32_t off = block_base;
   for (int i = 0; i < wv; ++i) off += wave_tot[i];
-  for_each_survivor(surv, cnt, L, cap, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+  for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
     const bool at = valid && !take_all && e.x == kth;
     const bool take = valid && (take_all || e.x > kth || (at && all_ties));
     const bool tie = at && !all_ties;
@@ -569,33 +585,21 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat
 }
 
 // Single-workgroup form of the same selection.  It runs for queries the multi-workgroup kernels hand over (more than
-// MSEL_TIE_CAP items tied at the K'-th key: `enable`), and after the exact redo (`only_flagged`).
+// MSEL_TIE_CAP items tied at the K'-th key: `enable`).
 __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, const uint32_t *cnt, int64_t L,
-                                                                     int64_t cap, const uint2 *sstat, uint32_t *flags,
-                                                                     int Kp, bool only_flagged, const uint32_t *enable,
+                                                                     int64_t cap, const uint2 *sstat, int Kp,
+                                                                     const uint32_t *enable,
                                                                      int32_t *cand_idx, float *cand_score,
                                                                      int32_t *cand_count) {
   __shared__ SelectShared sh;
-  const int b = blockIdx.x;
+  const int b = blockIdx.x, B = gridDim.x;
   const int tid = threadIdx.x;
-  if (only_flagged && flags[b] != 2u) return;  // 2 = survivor lists rebuilt by the exact path
-  if (enable && enable[(size_t)b * MCNT_STRIDE] == 0u) return;
+  if (enable[(size_t)b * MCNT_STRIDE] == 0u) return;
   const uint2 stt = sstat[b];
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
-  if (stt.y) {  // only after the redo: the exact K' items did not fit the lists (see molret.h)
-    if (tid == 0) {
-      flags[b] = 3u;
-      cand_count[b] = -1;
-    }
-    for (int i = tid; i < Kp; i += SELECT_THREADS) {
-      oi[i] = -1;
-      if (os) os[i] = -INFINITY;
-    }
-    return;
-  }
   auto each = [&](auto f) {
-    for_each_survivor(surv, cnt, L, cap, b, 0, L, SELECT_THREADS / 64, [&](uint2 e, bool valid) {
+    for_each_survivor(surv, cnt, L, cap, B, b, 0, L, SELECT_THREADS / 64, [&](uint2 e, bool valid) {
       if (valid) f(e.x, e.y);
     });
   };
@@ -618,9 +622,28 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
     oi[i] = -1;
     if (os) os[i] = -INFINITY;
   }
-  if (tid == 0) {
-    cand_count[b] = (int32_t)nout;
-    if (only_flagged) flags[b] = 0;
+  if (tid == 0) cand_count[b] = (int32_t)nout;
+}
+
+// After the last scan of the exact redo: a redone query holds exactly K' candidates.  Anything else (a query whose
+// threshold was never resolved, a count that is not K') is reported as cand_count = -1 with an empty row.
+__global__ __launch_bounds__(256) void k_exact_finish(const ExactState *state, const uint32_t *gate, uint32_t *flags,
+                                                      int Kp, int32_t *cand_idx, float *cand_score,
+                                                      int32_t *cand_count) {
+  if (gate[0] == 0) return;
+  const int b = blockIdx.x;
+  if (flags[b] == 0u) return;  // not redone
+  const bool ok = flags[b] == 2u && state[b].emitted == (uint32_t)Kp;
+  if (!ok) {
+    for (int i = threadIdx.x; i < Kp; i += 256) {
+      cand_idx[(size_t)b * Kp + i] = -1;
+      if (cand_score) cand_score[(size_t)b * Kp + i] = -INFINITY;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    cand_count[b] = ok ? Kp : -1;
+    flags[b] = ok ? 0u : 3u;
   }
 }
 
@@ -653,11 +676,11 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   int per_sm = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, lds));
   if (per_sm < 1) per_sm = 1;
-  if (per_sm > 3) per_sm = 3;
+  if (per_sm > 2) per_sm = 2;  // measured: two resident workgroups per CU stream fastest with the run-of-4 tile order
   const int cus = device_cus();
   if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
   int64_t grid = (int64_t)cus * per_sm;
-  const int64_t need = (ntiles + 3) / 4;
+  const int64_t need = (ntiles + 15) / 16;  // at least one run of 4 tiles for each of the 4 wavefronts
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
   *grid_out = grid;
@@ -684,22 +707,18 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStrea
   return MOL_OK;
 }
 
-// The grid every list-writing scan of a call uses: the smallest over the kernel variants the call will launch, so
-// that all of them can be resident and the list layout (L = 8 * grid lists per query) is the same for all.
+// The grid of the list-writing scan of a call: the smallest over the query-group variants the call will launch, so
+// that the list layout (L = 8 * grid lists per query) is the same for all of them.
 mol_status_t list_scan_grid(bool f32, int B, int64_t N, int64_t *grid_out) {
   const int64_t ntiles = (N + 31) / 32;
   int64_t best = -1;
   for (int qb = 0; qb < B; qb += 128) {
     const int rem = B - qb;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
-    int64_t g1 = 0, g2 = 0;
-    mol_status_t rc = f32 ? scan_grid<true, EPI_FILTER, false>(nqg, ntiles, &g1)
-                          : scan_grid<false, EPI_FILTER, false>(nqg, ntiles, &g1);
+    int64_t g = 0;
+    mol_status_t rc = f32 ? scan_grid<true, EPI_FILTER, false>(nqg, ntiles, &g)
+                          : scan_grid<false, EPI_FILTER, false>(nqg, ntiles, &g);
     if (rc != MOL_OK) return rc;
-    rc = f32 ? scan_grid<true, EPI_FILTER_EXACT, false>(nqg, ntiles, &g2)
-             : scan_grid<false, EPI_FILTER_EXACT, false>(nqg, ntiles, &g2);
-    if (rc != MOL_OK) return rc;
-    const int64_t g = g1 < g2 ? g1 : g2;
     if (best < 0 || g < best) best = g;
   }
   *grid_out = best;
@@ -732,7 +751,7 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->L = p->grid * 8;  // 4 wavefronts per workgroup, 2 lists (lane halves) per wavefront
   // rows one list can see: the tiles of its wavefront, 16 rows of each
   const int64_t ntiles = (N + 31) / 32;
-  const int64_t list_rows = (ntiles + p->grid * 4 - 1) / (p->grid * 4) * 16;
+  const int64_t list_rows = (ntiles + p->grid * 16 - 1) / (p->grid * 16) * 4 * 16;  // runs of 4 tiles per wavefront
   if (p->sampling) {
     const double expect = (double)N * (double)rank / (double)lambda;
     double tot = expect * (1.0 + 6.0 / sqrt((double)rank)) + 1024;
@@ -858,8 +877,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
 
   ProfScope ps(MOL_PROF_SELECT, st);
   {
-    hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, force_redo, flags, false,
-                       sstat);
+    hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, force_redo, sstat);
     HIP_TRY(hipGetLastError());
     int G = 1024 / B;
     G = G < 1 ? 1 : (G > 32 ? 32 : G);
@@ -874,8 +892,8 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, B, mcnt, tiebuf, flags, gate,
                        cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, flags, Kp,
-                       false, mcnt + 2, cand_idx, cand_score, cand_count);
+    hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp,
+                       mcnt + 2, cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
   }
 
@@ -900,13 +918,12 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   if (rc == MOL_OK) rc = step(9);
   if (rc != MOL_OK) return rc;
   a.gate = gate;
-  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, p.grid, st)
-           : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, p.grid, st);
+  a.out_idx = cand_idx;
+  a.out_score = cand_score;
+  a.Kp = Kp;
+  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, 0, st) : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, 0, st);
   if (rc != MOL_OK) return rc;
-  hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, false, flags, true, sstat);
-  HIP_TRY(hipGetLastError());
-  hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, flags, Kp,
-                     true, nullptr, cand_idx, cand_score, cand_count);
+  hipLaunchKernelGGL(k_exact_finish, dim3(B), dim3(256), 0, st, state, gate, flags, Kp, cand_idx, cand_score, cand_count);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
