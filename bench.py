@@ -20,6 +20,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes one launch of the corpus scan moves on the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this script (KiB per dispatch), each scaled by what the same counter reads for a 1 GiB device copy (--calibrate-copy):
+# FETCH_SIZE counts half the bytes (x2.000), WRITE_SIZE all of them (x1.000).  Re-measure when the scan kernel changes.
+SCAN_TRAFFIC_KIB = {"C4-100M": {"fetch": 6250074.1, "fetch_scale": 2.0, "write": 116014.1, "write_scale": 1.0}}
+
 # context only: the paper's serving latency for MoL + h-indexer on its (unnamed) production GPU, Section 5.3
 PAPER_CONTEXT = {"median_latency_ms_incl_batching_wait": 30.0, "hardware": "unnamed production GPU", "source": "Section 5.3"}
 
@@ -176,6 +181,11 @@ def main():
     gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + wl.H * 2 + 4 + 4)
     mol_flops = B * Kp * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
 
+    traffic = None
+    t = SCAN_TRAFFIC_KIB.get(wl.name)
+    if t and not args.n_items and args.mode == 0:
+        traffic = (t["fetch"] * t["fetch_scale"] + t["write"] * t["write_scale"]) * 1024.0
+
     result = {
         "metric": "queries/s + p50 batch latency, 100M-item h-indexer+MoL top-100, 1 GPU",
         "value": B / (ms_per_step * 1e-3),
@@ -194,7 +204,8 @@ def main():
         "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, K'={Kp}, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}, "
                                f"h-indexer mode {args.mode}, lambda={lam}"},
         "roofline": {"kernel": "k_stage1_scan (corpus scan + threshold filter)", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated)",
+                     "algorithmic_bytes": scan_bytes,
                      "avg_launch_ms": scan_ms / max(1, scan_n), "launches": scan_n},
         "kernels_ms_per_step": {name: v[0] / args.steps for name, v in prof.items() if v[1]},
         "mol_stage": {"gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,

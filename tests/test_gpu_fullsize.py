@@ -63,4 +63,10 @@ def test_c4_100m_two_stage_sampled_parity():
         assert_topk_set(got_idx, lookup, k, 2e-3 * abs(kth) + 1e-4, f"query {b}")
         assert_scores_close(got_sc, [lookup[i] for i in got_idx.tolist()], wl.logit_scale, f"query {b}")
         assert_sorted_desc(got_sc, got_idx, f"query {b}")
+    # the exact radix redo (every query forced through it) must reproduce the same K' sets: both paths return the exact
+    # top-K' under the same fp32 scores and the same tie rule, and the sampled path was checked against the oracle above
+    ci2, cs2, cc2 = m.hindexer_topk(corpus, q["q1"], Kp, lam=lam, seed=1003, mode=m.HINDEXER_EXACT | 0x100, workspace=ws1)
+    torch.cuda.synchronize()
+    assert int(cc2.min()) == Kp and int(cc2.max()) == Kp
+    assert torch.equal(ci.sort(dim=1).values, ci2.sort(dim=1).values)
     corpus.free()
