@@ -58,8 +58,9 @@ enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
  *   in  = [ cl (P = k_u*k_x component logits, index p = ku*k_x + kx) | user gate feature (d_gu) | item gate feature (d_gx) ]
  *   pi  = softmax_P( W2 * act(W1 * in + b1) + b2 ),    phi = sum_p pi_p * cl_p         (Eq. 3, Eq. 6)
  *   cl_p = logit_scale * <user_emb[ku], item_emb[kx]>                                   (Eq. 9; logit_scale = 1/tau)
- * Supported shapes: d1 = 64; d_p in {32, 64, 128}; k_x in {1, 2, 4, 8, 16}; k_u <= 16; P a multiple of 16
- * and at most 128; H a multiple of 32, at most 256; d_gu, d_gx multiples of 16, at most 256.
+ * Supported shapes: d1 = 64 (or 0); d_gu a multiple of 16, at most 256; d_gx in {16, 32, 64, 96, 128, 256}; (k_u, k_x, d_p, H) one of the combinations
+ * the scoring kernel is instantiated for: (4,4,32,32), (4,4,64,64), (8,4,64,128), (8,8,64,128), (2,8,32,64),
+ * (16,1,32,32), (8,2,128,96).  Anything else makes mol_corpus_pack return MOL_EUNSUPPORTED.
  */
 typedef struct {
   int64_t N;            /* corpus size */
@@ -113,7 +114,9 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive, then the exact
  *                                     top-K' of the survivors; a query whose survivors number fewer than K' or overflow the
  *                                     workspace is redone on the device with an exact multi-pass radix threshold.  The
- *                                     result is the exact stage-1 top-K' under fp32 scores.
+ *                                     result is the exact stage-1 top-K' under fp32 scores.  cand_count[b] = -1 (row
+ *                                     all -1) reports a query that could not be completed; it does not occur for
+ *                                     finite scores.
  *   cand_idx    : out int32 [B, Kp]; a set, in no particular order; unused slots are -1.
  *   cand_score  : out f32 [B, Kp] stage-1 scores aligned with cand_idx (unused slots -inf), or NULL.
  *   cand_count  : out int32 [B] number of valid slots.
