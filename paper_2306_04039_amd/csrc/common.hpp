@@ -53,25 +53,12 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) {
 // Matrix-core results need a fixed number of idle issue slots before an ordinary vector instruction may read them; the
 // hardware does not interlock this and the compiler inserts the slots itself, but it has been seen to miss the shortest
 // path when a branch diamond (a conditional prefetch) sits between the last MFMA and the first read: accumulators were
-// then read before the last MFMA had landed.  These helpers put the full wait (20 slots, enough for a 16-pass MFMA) on
-// every path.  mfma_settle() fences the instruction scheduler; mfma_settle(acc) instead ties the wait to the
-// accumulators by data dependence (they then live in ordinary vector registers) and leaves other work free to move.
+// then read before the last MFMA had landed.  Called after such a diamond and before the first read, this puts the full
+// wait (20 slots, enough for a 16-pass MFMA) on every path; the scheduling barriers keep MFMAs above and reads below.
 __device__ __forceinline__ void mfma_settle() {
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
-}
-template <typename V>
-__device__ __forceinline__ void mfma_settle(V &acc) {
-  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc));
-}
-template <typename V, int N>
-__device__ __forceinline__ void mfma_settle(V (&acc)[N]) {
-#pragma unroll
-  for (int g = 0; g < N; ++g) asm volatile("" : "+v"(acc[g]));
-  asm volatile("s_nop 15\n\ts_nop 3");
-#pragma unroll
-  for (int g = 0; g < N; ++g) asm volatile("" : "+v"(acc[g]));
 }
 
 // 16-byte global load through a plain pointer.

@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
       for (int s = 0; s < SA; ++s)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[rt % PD][s]), as_bf16x8(Ff[s]), acc, 0, 0, 0);
       if (rt + PD < RT) load_rows(A[rt % PD], rt + PD);
-      mfma_settle(acc);
+      mfma_settle();
       // acc[j]: row 4*g + j of the tile = (candidate rt*CPR + (4g+j)/K_X, kx (4g+j)%K_X); column ku = r16
       if (r16 < K_U) {
         if constexpr (K_X % 4 == 0) {
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
         acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc1[mt], 0, 0, 0);
       }
     }
-    mfma_settle(acc1);
+    mfma_settle();
 
     // ---- C: activation, then layer 2 (transposed): acc2[pt][j] = z[p = 32pt + 8(j/4) + 4h + j%4][c] -----
     f32x16 acc2[PT];
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
         }
       }
     }
-    mfma_settle(acc2);
+    mfma_settle();
 
     // ---- D: softmax over components and the weighted sum --------------------------------------------------
     float m = -INFINITY;

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
         const uint4 af = ld16(w1x + ((size_t)(32 * mt + c) * DG + 16 * s + 8 * h) * 2);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bfrag[s]), acc, 0, 0, 0);
       }
-      mfma_settle(acc);
+      mfma_settle();
       if (ok) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {

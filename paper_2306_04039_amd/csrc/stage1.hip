@@ -20,7 +20,22 @@
 #include "msel.hpp"
 #include "select.hpp"
 
+// Tuning constants of the corpus scan (measured on MI355X at N = 1e8, B = 32).
+#ifndef MOL_SCAN_DEPTH
+#define MOL_SCAN_DEPTH 2     // tiles in flight per wavefront (register ring)
+#endif
+#ifndef MOL_SCAN_TILE_RUN
+#define MOL_SCAN_TILE_RUN 4  // consecutive 32-row tiles a wavefront reads before it strides by the whole grid
+#endif
+#ifndef MOL_SCAN_PER_CU
+#define MOL_SCAN_PER_CU 2    // resident workgroups per compute unit
+#endif
+
 namespace {
+
+// Survivor records a lane stages in LDS before it writes them out (per query group); the rings of a workgroup take
+// 4 wavefronts * 64 lanes * NQG * entries * 8 bytes.
+constexpr uint32_t scan_ring_entries(int nqg) { return nqg == 4 ? 8u : 16u; }
 
 enum { EPI_FILTER = 0, EPI_KEYS = 1, EPI_HIST_KEY = 2, EPI_HIST_IDX = 3, EPI_FILTER_EXACT = 4 };
 
@@ -82,7 +97,11 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int64_t nwaves = (int64_t)gridDim.x * 4;
   const int64_t ntiles = (a.n_rows + 31) >> 5;
-  extern __shared__ uint32_t lds_hist[];  // HIST: [32*NQG][EXACT_BINS]
+  extern __shared__ uint32_t lds_hist[];  // HIST: [32*NQG][EXACT_BINS];  FILTER: survivor rings, see below
+  // FILTER: a lane stages its survivors in a private LDS ring of RING entries and copies the ring to its list in HBM
+  // when it is full, so that the lists are written in whole 64/128-byte pieces.  (Appending each 8-byte record straight
+  // to HBM cost a quarter of the scan's time: 4.6 M scattered partial-line writes at N = 1e8, K' = 1e5.)
+  constexpr uint32_t RING = scan_ring_entries(NQG);
   if constexpr (REDO) {
     if (*a.gate == 0) return;
   }
@@ -97,9 +116,11 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
   uint32_t cnt[NQG];
   uint2 *lst[NQG];
   const uint32_t cap32 = (uint32_t)a.cap;
+  uint2 *ring[NQG];
 #pragma unroll
   for (int g = 0; g < NQG; ++g) {
     const int b = a.qbase + 32 * g + r;
+    ring[g] = reinterpret_cast<uint2 *>(lds_hist) + ((size_t)((threadIdx.x >> 6) * NQG + g) * 64 + lane) * RING;
 #pragma unroll
     for (int ci = 0; ci < NCH; ++ci)
       q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
@@ -133,10 +154,19 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
     for (int ci = 0; ci < NCH; ++ci) dst[ci] = ld16(p + ci * 32);
   };
 
+  // copies the first n (even up to RING) staged records of query group g to the lane's list; cnt[g] already counts them
+  auto flush_ring = [&](int g, uint32_t n) {
+    if (lst[g] == nullptr || cnt[g] > cap32) return;  // a list that overflowed is redone anyway
+    uint2 *dst = lst[g] + (cnt[g] - n);
+    for (uint32_t e = 0; e + 2 <= n; e += 2)
+      *reinterpret_cast<uint4 *>(dst + e) = *reinterpret_cast<const uint4 *>(ring[g] + e);
+    if (n & 1u) dst[n - 1] = ring[g][n - 1];
+  };
+
   uint4 buf[DEPTH][NCH];
-  // A wavefront reads TILE_RUN consecutive tiles (16 KB), then jumps by the whole grid: the grid as a whole sweeps the
+  // A wavefront reads TILE_RUN consecutive tiles (4 KB each at bf16), then jumps by the whole grid: the grid as a whole sweeps the
   // table front to back while each wavefront's loads stay within a DRAM page for a few steps.
-  constexpr int64_t TILE_RUN = 4;
+  constexpr int64_t TILE_RUN = MOL_SCAN_TILE_RUN;
   const int64_t n_it = (ntiles + nwaves * TILE_RUN - 1) / (nwaves * TILE_RUN) * TILE_RUN;  // tiles per wavefront
   auto tile_of = [&](int64_t it) -> int64_t { return ((it / TILE_RUN) * nwaves + wave) * TILE_RUN + it % TILE_RUN; };
 #pragma unroll
@@ -189,19 +219,21 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
       for (int g = 0; g < NQG; ++g) {
         const int b = a.qbase + 32 * g + r;
         if constexpr (EPI == EPI_FILTER) {
-          uint32_t mask = 0;
+          // about 1.5 of the 1024 scores of a tile pass: one compare per accumulator, and the (rare) append is a
+          // branch the wavefront skips when no lane takes it
+          auto append = [&](int j) {
+            ring[g][cnt[g] & (RING - 1)] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
+            ++cnt[g];
+            if ((cnt[g] & (RING - 1)) == 0) flush_ring(g, RING);
+          };
+          if (tile != ntiles - 1) {
 #pragma unroll
-          for (int j = 0; j < 16; ++j) mask |= (acc[g][j] > thr[g]) ? (1u << j) : 0u;
-          mask &= vmask;
-          if (mask) {
+            for (int j = 0; j < 16; ++j)
+              if (acc[g][j] > thr[g]) [[unlikely]] append(j);
+          } else {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-              if ((mask >> j) & 1u) {
-                if (cnt[g] < cap32)
-                  lst[g][cnt[g]] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
-                ++cnt[g];
-              }
-            }
+            for (int j = 0; j < 16; ++j)
+              if (acc[g][j] > thr[g] && ((vmask >> j) & 1u)) append(j);
           }
         } else if constexpr (EPI == EPI_FILTER_EXACT) {
           if (st_active[g] == 3u) {
@@ -249,6 +281,8 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
 #pragma unroll
     for (int g = 0; g < NQG; ++g) {
       const int b = a.qbase + 32 * g + r;
+      const uint32_t rest = cnt[g] & (RING - 1);
+      if (rest) flush_ring(g, rest);
       if (b < a.B) a.cnt[(size_t)b * a.L + wave * 2 + h] = cnt[g];
     }
   }
@@ -650,9 +684,16 @@ __global__ __launch_bounds__(256) void k_exact_finish(const ExactState *state, c
 // ---- launch helpers ----------------------------------------------------------------------------------------------
 template <bool F32, int EPI, bool GATHER>
 void (*scan_kernel(int nqg))(ScanArgs) {
-  constexpr int DEPTH = 2;
+  constexpr int DEPTH = MOL_SCAN_DEPTH;
   return nqg == 4 ? k_stage1_scan<F32, 4, EPI, GATHER, DEPTH>
                   : (nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH> : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>);
+}
+
+// dynamic LDS of one scan workgroup
+size_t scan_lds_bytes(int epi, int nqg) {
+  if (epi == EPI_HIST_KEY || epi == EPI_HIST_IDX) return (size_t)32 * nqg * EXACT_BINS * 4;
+  if (epi == EPI_FILTER) return (size_t)4 * 64 * nqg * scan_ring_entries(nqg) * 8;
+  return 0;
 }
 
 int device_cus() {
@@ -670,17 +711,17 @@ int device_cus() {
 template <bool F32, int EPI, bool GATHER>
 mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   auto kern = scan_kernel<F32, EPI, GATHER>(nqg);
-  const size_t lds = (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0;
+  const size_t lds = scan_lds_bytes(EPI, nqg);
   if (lds > 48 * 1024)
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   int per_sm = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, lds));
   if (per_sm < 1) per_sm = 1;
-  if (per_sm > 2) per_sm = 2;  // measured: two resident workgroups per CU stream fastest with the run-of-4 tile order
+  if (per_sm > MOL_SCAN_PER_CU) per_sm = MOL_SCAN_PER_CU;
   const int cus = device_cus();
   if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
   int64_t grid = (int64_t)cus * per_sm;
-  const int64_t need = (ntiles + 15) / 16;  // at least one run of 4 tiles for each of the 4 wavefronts
+  const int64_t need = (ntiles + 4 * MOL_SCAN_TILE_RUN - 1) / (4 * MOL_SCAN_TILE_RUN);  // at least one run of tiles for each of the 4 wavefronts
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
   *grid_out = grid;
@@ -700,7 +741,7 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStrea
     mol_status_t rc = scan_grid<F32, EPI, GATHER>(nqg, ntiles, &grid);
     if (rc != MOL_OK) return rc;
     if (fixed_grid > 0) grid = fixed_grid;
-    const size_t lds = (EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX) ? (size_t)32 * nqg * EXACT_BINS * 4 : 0;
+    const size_t lds = scan_lds_bytes(EPI, nqg);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     HIP_TRY(hipGetLastError());
   }
@@ -751,14 +792,15 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->L = p->grid * 8;  // 4 wavefronts per workgroup, 2 lists (lane halves) per wavefront
   // rows one list can see: the tiles of its wavefront, 16 rows of each
   const int64_t ntiles = (N + 31) / 32;
-  const int64_t list_rows = (ntiles + p->grid * 16 - 1) / (p->grid * 16) * 4 * 16;  // runs of 4 tiles per wavefront
+  const int64_t run_tiles = p->grid * 4 * MOL_SCAN_TILE_RUN;  // tiles one sweep of the grid covers
+  const int64_t list_rows = (ntiles + run_tiles - 1) / run_tiles * MOL_SCAN_TILE_RUN * 16;  // rows that can land in one list
   if (p->sampling) {
     const double expect = (double)N * (double)rank / (double)lambda;
     double tot = expect * (1.0 + 6.0 / sqrt((double)rank)) + 1024;
     if (tot < (double)Kp + 1024) tot = (double)Kp + 1024;
     const double per = tot / (double)p->L;
     int64_t cap = (int64_t)(per + 8.0 * sqrt(per) + 8.0);
-    cap = (cap + 1) & ~(int64_t)1;
+    cap = (cap + 15) & ~(int64_t)15;  // whole rings: a full ring either fits a list or overflows it
     if (cap > list_rows) cap = list_rows;
     p->cap = cap;
   } else {
