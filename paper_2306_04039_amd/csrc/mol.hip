@@ -65,6 +65,12 @@ __device__ __forceinline__ float act_fn(float x, int act) {
 //              the item tensors are read once per query chunk instead of once per query (the per-query form moves
 //              B x the corpus through L2 and is bound by that, not by the matrix cores).
 #define MOL_QCHUNK 256
+#ifndef MOL_PF_ROWS
+#define MOL_PF_ROWS 4  // row-tile loads of the next tile started before the gating stages (registers stay live there)
+#endif
+#ifndef MOL_PF_XI
+#define MOL_PF_XI 0    // also start the next tile's cached item-gate loads early
+#endif
 template <int K_U, int K_X, int D_P, int H, bool EXH>
 __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
@@ -103,6 +109,17 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   bool ok = false;
   const int64_t n_qch = EXH ? (a.B + MOL_QCHUNK - 1) / MOL_QCHUNK : 1;
   const int64_t ntasks = EXH ? tpq * n_qch : ntiles;
+  // !EXH: the gathers of a tile are started while the previous tile is still in its gating stages (the row registers
+  // are free after stage A, the item-gate registers after stage C), so a wavefront always has loads in flight.
+  // idx_n / idxc_n: this lane's candidate of the next tile; primed: the current tile's gathers were started early.
+  auto task_cand = [&](int64_t t) -> int {
+    const int tb = (int)(t / tpq);
+    const int64_t tc = ((t % tpq) << 5) + c;
+    return tc < a.Kp ? (a.cand ? a.cand[(size_t)tb * a.Kp + tc] : (int)tc) : -1;
+  };
+  int idx_n = -1, idxc_n = 0;
+  bool primed = false;
+  if (!EXH && wave < ntasks) idx_n = task_cand(wave);
   for (int64_t task = wave; task < ntasks; task += nwaves) {
    const int b_lo = EXH ? (int)(task % n_qch) * MOL_QCHUNK : 0;
    const int b_hi = EXH ? (b_lo + MOL_QCHUNK < a.B ? b_lo + MOL_QCHUNK : a.B) : 1;
@@ -118,9 +135,15 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     }
     const bool new_items = !EXH || bq == b_lo;
     const int64_t cpos = c0 + c;
+    const bool have_next = !EXH && task + nwaves < ntasks;
     if (new_items) {
-      idx = -1;
-      if (cpos < a.Kp) idx = a.cand ? a.cand[(size_t)b * a.Kp + cpos] : (int)cpos;
+      if (EXH) {
+        idx = -1;
+        if (cpos < a.Kp) idx = a.cand ? a.cand[(size_t)b * a.Kp + cpos] : (int)cpos;
+      } else {
+        idx = idx_n;
+        idx_n = have_next ? task_cand(task + nwaves) : -1;
+      }
       ok = idx >= 0 && idx < a.N;
       idxc = ok ? idx : 0;
     }
@@ -134,25 +157,28 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     }
 
     // item half of layer 1 for this lane's candidate: hidden units 32*mt + 8*q + 4*h + {0..3}
-    if (new_items) {
-      const char *xp = a.xi + ((size_t)idxc * H + 4 * h) * 2;
+    auto load_xi = [&](int item) {
+      const char *xp = a.xi + ((size_t)item * H + 4 * h) * 2;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int q = 0; q < 4; ++q) xi[mt][q] = *reinterpret_cast<const uint2 *>(xp + (32 * mt + 8 * q) * 2);
-    }
+    };
+    if (new_items && !(primed && MOL_PF_XI)) load_xi(idxc);
 
     // ---- A: component logits -> LDS tile --------------------------------------------------------------
-    auto load_rows = [&](uint4(&dst)[SA], int rt) {
+    auto load_rows = [&](uint4(&dst)[SA], int rt, int item = -1) {
       const int ci = rt * CPR + r16 / K_X;
-      const int nidx = __shfl(idxc, ci);
+      const int nidx = __shfl(item < 0 ? idxc : item, ci);
       const char *rowp = a.embs + (((size_t)nidx * K_X + (r16 % K_X)) * D_P + 8 * g) * 2;
 #pragma unroll
       for (int s = 0; s < SA; ++s) dst[s] = ld16(rowp + 64 * s);
     };
-    if (new_items || RT > PD) {
+    constexpr int PFR = MOL_PF_ROWS < PD ? MOL_PF_ROWS : PD;
+    if (EXH ? (new_items || RT > PD) : true) {
 #pragma unroll
-      for (int i = 0; i < PD; ++i) load_rows(A[i], i);
+      for (int i = 0; i < PD; ++i)
+        if (EXH || i >= PFR || !primed) load_rows(A[i], i);
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -161,7 +187,6 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
       for (int s = 0; s < SA; ++s)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[rt % PD][s]), as_bf16x8(Ff[s]), acc, 0, 0, 0);
       if (rt + PD < RT) load_rows(A[rt % PD], rt + PD);
-      mfma_settle();
       // acc[j]: row 4*g + j of the tile = (candidate rt*CPR + (4g+j)/K_X, kx (4g+j)%K_X); column ku = r16
       if (r16 < K_U) {
         if constexpr (K_X % 4 == 0) {
@@ -174,6 +199,11 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
             cl[(rt * CPR + (4 * g + j) / K_X) * CLS + r16 * K_X + (4 * g + j) % K_X] = acc[j] * a.logit_scale;
         }
       }
+    }
+    if (have_next) {  // the row registers are free: start the next tile's first rows
+      idxc_n = (idx_n >= 0 && idx_n < a.N) ? idx_n : 0;
+#pragma unroll
+      for (int i = 0; i < PFR; ++i) load_rows(A[i], i, idxc_n);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -201,7 +231,6 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
         acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc1[mt], 0, 0, 0);
       }
     }
-    mfma_settle();
 
     // ---- C: activation, then layer 2 (transposed): acc2[pt][j] = z[p = 32pt + 8(j/4) + 4h + j%4][c] -----
     f32x16 acc2[PT];
@@ -237,7 +266,9 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
         }
       }
     }
-    mfma_settle();
+
+    if (have_next && MOL_PF_XI) load_xi(idxc_n);  // the item-gate registers are free: the next tile's cached gate halves
+    primed = have_next;
 
     // ---- D: softmax over components and the weighted sum --------------------------------------------------
     float m = -INFINITY;
