@@ -116,19 +116,19 @@ extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp,
   return p0.total > p1.total ? p0.total : p1.total;
 }
 
-static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, size_t *off_scores, size_t *off_topk) {
+static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, int k, size_t *off_scores, size_t *off_topk) {
   size_t off = align_up((size_t)B * c->H * 4, 256);
   if (off_scores) *off_scores = off;
   off = align_up(off + (size_t)B * row * 4, 256);
   if (off_topk) *off_topk = off;
-  off += final_topk_workspace_bytes(B);
+  off += final_topk_workspace_bytes(B, row, k);
   return off;
 }
 
 extern "C" size_t mol_workspace_bytes(const mol_corpus_t *c, int B, int Kp, int k) {
   if (!c || B < 1 || B > 1024 || k < 0) return 0;
   const int64_t row = Kp > 0 ? Kp : c->N;
-  return mol_ws_layout(c, B, row, nullptr, nullptr);
+  return mol_ws_layout(c, B, row, k, nullptr, nullptr);
 }
 
 static mol_status_t check_ws(const void *ws, size_t have, size_t need) {
@@ -190,7 +190,7 @@ extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, c
   if (k < 1 || k > 1024) return mol_fail(MOL_EINVAL, "k=%d must be in [1, 1024]", k);
   const int64_t row = cand_idx ? Kp : c->N;
   size_t off_scores = 0, off_topk = 0;
-  const size_t need = mol_ws_layout(c, B, row, &off_scores, &off_topk);
+  const size_t need = mol_ws_layout(c, B, row, k, &off_scores, &off_topk);
   rc = check_ws(workspace, workspace_bytes, need);
   if (rc != MOL_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);

@@ -129,6 +129,6 @@ mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B,
 mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
                               const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st);
 // select.hip
-size_t final_topk_workspace_bytes(int B);
+size_t final_topk_workspace_bytes(int B, int64_t Kp, int k);
 mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
                                int32_t *out_idx, float *out_score, char *ws, hipStream_t st);
