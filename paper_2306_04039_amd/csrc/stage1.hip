@@ -75,11 +75,81 @@ struct ScanArgs {
   ExactState *state;        // exact redo: per-query state
   int32_t *out_idx;         // FILTER_EXACT: [B][Kp] candidates, written directly
   float *out_score;         // FILTER_EXACT: [B][Kp] or NULL
+  int32_t *out_count;       // FILTER_EXACT: [B]
+  uint32_t *flags;          // FILTER_EXACT: [B] per-query status (1 = being redone -> 0 done / 3 failed)
   int Kp;
+  uint32_t *gate_rw;        // exact redo: the two gate words and, at [2], the workgroup ticket of the redo scans
+  int stage;                // exact redo: step to run when a histogram scan has finished (1..8)
   uint32_t *hist;           // exact redo: [B][EXACT_BINS] digit histogram
   const uint32_t *gate;     // exact redo: the kernel returns at once when *gate == 0
   int shift;                // exact redo: bit position of the digit
 };
+
+// One step of the exact redo, run for query b by the 256 threads of the last workgroup of a histogram scan to finish:
+//   stage 1..4 : digit of the key found from the histogram of the scan just done; after the fourth the K'-th key is
+//                known and either every tie is taken or the index passes start (gate[1] = 1).
+//   stage 5..8 : the same on ~idx among the ties; after the fourth the index limit is known.
+// The histogram row is read past the L1 cache (other workgroups added to it with device-scope atomics) and zeroed for
+// the next scan.
+__device__ inline void exact_step(int stage, ExactState *st, uint32_t *hb, uint32_t *gate, uint32_t *suf) {
+  const int t = threadIdx.x;
+  __syncthreads();  // suf and *st may still be in use by the previous query's step
+  const uint32_t want = stage <= 4 ? 1u : 2u;
+  const uint32_t active = st->active;
+  const uint32_t mine = __hip_atomic_load(&hb[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  hb[t] = 0;  // ready for the next scan
+  if (active != want) return;
+  // inclusive suffix sums: suf[t] = sum of bins >= t
+  suf[t] = mine;
+  __syncthreads();
+  for (int o = 1; o < EXACT_BINS; o <<= 1) {
+    const uint32_t add = (t + o < EXACT_BINS) ? suf[t + o] : 0u;
+    __syncthreads();
+    suf[t] += add;
+    __syncthreads();
+  }
+  const uint32_t krem = st->krem, prefix = st->prefix;
+  const uint32_t above = suf[t] - mine;  // elements in larger digits
+  __syncthreads();
+  if (above < krem && krem <= above + mine) {  // exactly one thread
+    const int shift = 24 - 8 * ((stage - 1) & 3);
+    const uint32_t np = prefix | ((uint32_t)t << shift);
+    const uint32_t nk = krem - above;
+    if (stage == 4) {
+      st->tkey = np;
+      if (nk == mine) {  // all items tied at the K'-th key fit
+        st->active = 3;
+        st->idx_limit = 0xffffffffu;
+      } else {
+        st->active = 2;
+        st->prefix = 0;
+        st->krem = nk;
+        gate[1] = 1;
+      }
+    } else if (stage == 8) {
+      st->idx_limit = ~np;
+      st->active = 3;
+    } else {
+      st->prefix = np;
+      st->krem = nk;
+    }
+  }
+}
+
+// True in every thread of the last workgroup of the grid to get here (all writes of the others are then visible);
+// the counter is left at zero for the next launch.
+__device__ inline bool last_workgroup(uint32_t *ticket) {
+  __shared__ uint32_t s_last;
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = atomicAdd(ticket, 1u);
+    s_last = (t == gridDim.x - 1) ? 1u : 0u;
+    if (s_last) *ticket = 0;
+  }
+  __syncthreads();
+  return s_last != 0;
+}
 
 // F32 = false: bf16 rows of 64 (128 B), 4 x 16-byte chunks per lane, one 32x32x16 MFMA per chunk.
 // F32 = true : fp32 rows of 64 (256 B), 8 x 16-byte chunks per lane, four 32x32x2 MFMAs per chunk.
@@ -293,79 +363,33 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
       const int b = a.qbase + i / EXACT_BINS;
       if (v && b < a.B) atomicAdd(&a.hist[(size_t)b * EXACT_BINS + (i & (EXACT_BINS - 1))], v);
     }
-  }
-}
-
-// One step of the exact redo between two scans (one workgroup of EXACT_BINS threads per query).
-//   stage 0      : flagged queries start the key passes (rank K').
-//   stage 1..4   : digit of the key found from the histogram of the scan just done; after the fourth the K'-th key is
-//                  known and either every tie is taken or the index passes start.
-//   stage 5..8   : the same on ~idx among the ties; after the fourth the index limit is known.
-//   stage 9      : queries with a known threshold are marked for the final filter scan.
-__global__ __launch_bounds__(EXACT_BINS) void k_exact_step(int stage, ExactState *state, uint32_t *hist, uint32_t *gate,
-                                                           uint32_t *flags, uint32_t Kp) {
-  __shared__ uint32_t suf[EXACT_BINS];
-  if (gate[0] == 0) return;
-  const int b = blockIdx.x;
-  const int t = threadIdx.x;
-  ExactState *st = state + b;
-  uint32_t *hb = hist + (size_t)b * EXACT_BINS;
-  if (stage == 0) {
-    if (t == 0) {
-      ExactState s = {};
-      if (flags[b] == 1u) {
-        s.active = 1;
-        s.krem = Kp;
-        s.idx_limit = 0xffffffffu;
-      }
-      *st = s;
+    // the last workgroup to finish turns the histograms into the next digit of every query of this launch
+    if (last_workgroup(a.gate_rw + 2)) {
+      uint32_t *suf = lds_hist;  // the LDS histogram is flushed: reuse its first EXACT_BINS words
+      for (int b = a.qbase; b < a.B && b < a.qbase + 32 * NQG; ++b)
+        exact_step(a.stage, a.state + b, a.hist + (size_t)b * EXACT_BINS, a.gate_rw, suf);
     }
-    hb[t] = 0;
-    return;
   }
-  if (stage == 9) {
-    if (t == 0 && st->active == 3u) flags[b] = 2u;
-    return;
-  }
-  const uint32_t want = stage <= 4 ? 1u : 2u;
-  const uint32_t active = st->active;
-  const uint32_t mine = hb[t];
-  __syncthreads();
-  hb[t] = 0;  // ready for the next scan
-  if (active != want) return;
-  // inclusive suffix sums: suf[t] = sum of bins >= t
-  suf[t] = mine;
-  __syncthreads();
-  for (int o = 1; o < EXACT_BINS; o <<= 1) {
-    const uint32_t add = (t + o < EXACT_BINS) ? suf[t + o] : 0u;
-    __syncthreads();
-    suf[t] += add;
-    __syncthreads();
-  }
-  const uint32_t krem = st->krem, prefix = st->prefix;
-  const uint32_t above = suf[t] - mine;  // elements in larger digits
-  __syncthreads();
-  if (above < krem && krem <= above + mine) {  // exactly one thread
-    const int shift = 24 - 8 * ((stage - 1) & 3);
-    const uint32_t np = prefix | ((uint32_t)t << shift);
-    const uint32_t nk = krem - above;
-    if (stage == 4) {
-      st->tkey = np;
-      if (nk == mine) {  // all items tied at the K'-th key fit
-        st->active = 3;
-        st->idx_limit = 0xffffffffu;
-      } else {
-        st->active = 2;
-        st->prefix = 0;
-        st->krem = nk;
-        gate[1] = 1;
+  if constexpr (EPI == EPI_FILTER_EXACT) {
+    // the last workgroup closes the redo: a redone query holds exactly K' candidates; anything else (a threshold that
+    // was never resolved, a count that is not K') is reported as cand_count = -1 with an empty row
+    if (last_workgroup(a.gate_rw + 2)) {
+      for (int b = a.qbase; b < a.B && b < a.qbase + 32 * NQG; ++b) {
+        if (a.flags[b] == 0u) continue;  // not redone
+        const uint32_t emitted = __hip_atomic_load(&a.state[b].emitted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool ok = a.state[b].active == 3u && emitted == (uint32_t)a.Kp;
+        if (!ok) {
+          for (int i = threadIdx.x; i < a.Kp; i += 256) {
+            a.out_idx[(size_t)b * a.Kp + i] = -1;
+            if (a.out_score) a.out_score[(size_t)b * a.Kp + i] = -INFINITY;
+          }
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          a.out_count[b] = ok ? a.Kp : -1;
+          a.flags[b] = ok ? 0u : 3u;
+        }
       }
-    } else if (stage == 8) {
-      st->idx_limit = ~np;
-      st->active = 3;
-    } else {
-      st->prefix = np;
-      st->krem = nk;
     }
   }
 }
@@ -415,13 +439,13 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhi
   if (threadIdx.x == 0) {
     thr[b] = c.K ? key_to_f32(c.prefix) : -INFINITY;
     flags[b] = 0;
-    if (b == 0) gate[0] = gate[1] = 0;
+    if (b == 0) gate[0] = gate[1] = gate[2] = 0;
   }
 }
 
 __global__ void k_init_all_pass(float *thr, uint32_t *flags, uint32_t *gate, int B) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) gate[0] = gate[1] = 0;
+  if (i == 0) gate[0] = gate[1] = gate[2] = 0;
   if (i < B) {
     thr[i] = -INFINITY;
     flags[i] = 0;
@@ -578,11 +602,23 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
 
 __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat, int Kp, const uint32_t *mhist, int B,
                                                               uint32_t *mcnt, const uint32_t *tiebuf, uint32_t *flags,
-                                                              uint32_t *gate, int32_t *cand_idx, float *cand_score,
+                                                              uint32_t *gate, ExactState *state, uint32_t *ehist,
+                                                              int32_t *cand_idx, float *cand_score,
                                                               int32_t *cand_count) {
   __shared__ MselShared sh;
   const int b = blockIdx.x, tid = threadIdx.x;
   const uint2 stt = sstat[b];
+  // state of the exact redo: a flagged query starts the key passes at rank K'
+  if (tid == 0) {
+    ExactState s = {};
+    if (stt.y) {
+      s.active = 1;
+      s.krem = (uint32_t)Kp;
+      s.idx_limit = 0xffffffffu;
+    }
+    state[b] = s;
+  }
+  for (int i = tid; i < EXACT_BINS; i += MSEL_THREADS) ehist[(size_t)b * EXACT_BINS + i] = 0;
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
   uint32_t nout = 0;
@@ -657,28 +693,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
     if (os) os[i] = -INFINITY;
   }
   if (tid == 0) cand_count[b] = (int32_t)nout;
-}
-
-// After the last scan of the exact redo: a redone query holds exactly K' candidates.  Anything else (a query whose
-// threshold was never resolved, a count that is not K') is reported as cand_count = -1 with an empty row.
-__global__ __launch_bounds__(256) void k_exact_finish(const ExactState *state, const uint32_t *gate, uint32_t *flags,
-                                                      int Kp, int32_t *cand_idx, float *cand_score,
-                                                      int32_t *cand_count) {
-  if (gate[0] == 0) return;
-  const int b = blockIdx.x;
-  if (flags[b] == 0u) return;  // not redone
-  const bool ok = flags[b] == 2u && state[b].emitted == (uint32_t)Kp;
-  if (!ok) {
-    for (int i = threadIdx.x; i < Kp; i += 256) {
-      cand_idx[(size_t)b * Kp + i] = -1;
-      if (cand_score) cand_score[(size_t)b * Kp + i] = -INFINITY;
-    }
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    cand_count[b] = ok ? Kp : -1;
-    flags[b] = ok ? 0u : 3u;
-  }
 }
 
 // ---- launch helpers ----------------------------------------------------------------------------------------------
@@ -831,7 +845,7 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->off_hist = off;
   off = align_up(off + (size_t)B * EXACT_BINS * 4, 256);
   p->off_state = off;
-  off = align_up(off + (size_t)B * sizeof(ExactState) + 256, 256);  // + the two gate words
+  off = align_up(off + (size_t)B * sizeof(ExactState) + 256, 256);  // + the gate words and the ticket
   p->total = off;
   return MOL_OK;
 }
@@ -932,40 +946,35 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
                        mcnt, tiebuf, cand_idx, cand_score);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, B, mcnt, tiebuf, flags, gate,
-                       cand_idx, cand_score, cand_count);
+                       state, hist, cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp,
                        mcnt + 2, cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
   }
 
-  // exact redo of flagged queries; every kernel below returns at once when none is flagged
+  // exact redo of flagged queries: 8 histogram scans and the emitting scan; each returns at once when no query is
+  // flagged (k_surv_finish has set up the per-query state; the last workgroup of every scan advances it)
   a.state = state;
   a.hist = hist;
-  auto step = [&](int stage) -> mol_status_t {
-    hipLaunchKernelGGL(k_exact_step, dim3(B), dim3(EXACT_BINS), 0, st, stage, state, hist, gate, flags, (uint32_t)Kp);
-    HIP_TRY(hipGetLastError());
-    return MOL_OK;
-  };
-  rc = step(0);
-  for (int pass = 0; pass < 8 && rc == MOL_OK; ++pass) {
+  a.gate_rw = gate;
+  a.flags = flags;
+  a.out_idx = cand_idx;
+  a.out_score = cand_score;
+  a.out_count = cand_count;
+  a.Kp = Kp;
+  for (int pass = 0; pass < 8; ++pass) {
     a.shift = 24 - 8 * (pass & 3);
     a.gate = gate + (pass < 4 ? 0 : 1);
+    a.stage = pass + 1;
     if (pass < 4)
       rc = f32 ? launch_scan<true, EPI_HIST_KEY, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_KEY, false>(a, B, 0, st);
     else
       rc = f32 ? launch_scan<true, EPI_HIST_IDX, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_IDX, false>(a, B, 0, st);
-    if (rc == MOL_OK) rc = step(pass + 1);
+    if (rc != MOL_OK) return rc;
   }
-  if (rc == MOL_OK) rc = step(9);
-  if (rc != MOL_OK) return rc;
   a.gate = gate;
-  a.out_idx = cand_idx;
-  a.out_score = cand_score;
-  a.Kp = Kp;
   rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, 0, st) : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, 0, st);
   if (rc != MOL_OK) return rc;
-  hipLaunchKernelGGL(k_exact_finish, dim3(B), dim3(256), 0, st, state, gate, flags, Kp, cand_idx, cand_score, cand_count);
-  HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
