@@ -156,8 +156,10 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    # timed region: only the dominant kernel (the corpus scan) is bracketed by HIP events inside the library (each
+    # bracket idles the device for about 10 us); the per-kernel breakdown comes from a second, untimed set of steps
     m.profile_read()
-    m.profile_enable(True)
+    m.profile_enable(True, slots=["scan_filter"])
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -168,13 +170,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     m.profile_enable(False)
-    prof = m.profile_read()
+    prof_scan = m.profile_read()
     lat = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
     ms_per_step = wall * 1e3 / args.steps
+    m.profile_enable(True)
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    m.profile_enable(False)
+    prof = m.profile_read()
     counts = out1[2].cpu()
     assert int(counts.min()) >= 0, "h-indexer reported a failed query"
 
-    scan_ms, scan_n = prof["scan_filter"]
+    scan_ms, scan_n = prof_scan["scan_filter"]
     scan_bytes = wl.N * wl.d1 * (4 if wl.stage1_dtype == "f32" else 2)
     achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
     mol_ms, mol_n = prof["mol_score"]
@@ -208,6 +216,7 @@ def main():
                      "algorithmic_bytes": scan_bytes,
                      "avg_launch_ms": scan_ms / max(1, scan_n), "launches": scan_n},
         "kernels_ms_per_step": {name: v[0] / args.steps for name, v in prof.items() if v[1]},
+        "kernels_note": "from a second, untimed set of steps with every kernel group bracketed by events",
         "mol_stage": {"gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,
                       "gather_frac_of_hbm_peak": (gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 / HBM_PEAK_GBS) if mol_n else 0.0,
                       "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0},

@@ -58,7 +58,7 @@ enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
  *   in  = [ cl (P = k_u*k_x component logits, index p = ku*k_x + kx) | user gate feature (d_gu) | item gate feature (d_gx) ]
  *   pi  = softmax_P( W2 * act(W1 * in + b1) + b2 ),    phi = sum_p pi_p * cl_p         (Eq. 3, Eq. 6)
  *   cl_p = logit_scale * <user_emb[ku], item_emb[kx]>                                   (Eq. 9; logit_scale = 1/tau)
- * Supported shapes: d1 = 64 (or 0); d_gu a multiple of 16, at most 256; d_gx in {16, 32, 64, 96, 128, 256}; (k_u, k_x, d_p, H) one of the combinations
+ * Supported shapes: d1 = 64 (or 0); 1 <= d_gu <= 1024; d_gx in {16, 32, 64, 96, 128, 256}; (k_u, k_x, d_p, H) one of the combinations
  * the scoring kernel is instantiated for: (4,4,32,32), (4,4,64,64), (8,4,64,128), (8,8,64,128), (2,8,32,64),
  * (16,1,32,32), (8,2,128,96).  Anything else makes mol_corpus_pack return MOL_EUNSUPPORTED.
  */
@@ -150,9 +150,11 @@ mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const v
                       size_t workspace_bytes, void *stream);
 
 /*
- * Optional per-kernel timing, for benchmarks.  While enabled, every kernel launch of the calls above is bracketed by
- * HIP events on the caller's stream (a few microseconds of overhead per launch).  mol_profile_read synchronises on
- * the recorded events, adds up the elapsed time per slot since the last read and clears the record.
+ * Optional per-kernel timing, for benchmarks.  While enabled, the kernel launches of the calls above are bracketed by
+ * HIP events on the caller's stream (each bracket costs about 10 microseconds of idle device time).  mol_profile_read
+ * synchronises on the recorded events, adds up the elapsed time per slot since the last read and clears the record.
+ *   on : 0 = off, 1 = every slot, otherwise 2 * m where bit s of m enables slot s (e.g. 2 << MOL_PROF_SCAN_FILTER
+ *        times the corpus scan only).
  *   slot_ms, slot_launches : host arrays of MOL_PROF_SLOTS entries (either may be NULL).
  */
 enum {

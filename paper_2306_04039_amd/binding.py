@@ -259,8 +259,15 @@ def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, c
     return out
 
 
-def profile_enable(on: bool) -> None:
-    _check(load_library().mol_profile_enable(1 if on else 0))
+def profile_enable(on, slots=None) -> None:
+    """on = False/True: no / every slot; slots = iterable of PROF_SLOTS names: only those."""
+    if slots is not None:
+        mask = 0
+        for name in slots:
+            mask |= 1 << PROF_SLOTS.index(name)
+        _check(load_library().mol_profile_enable(2 * mask))
+    else:
+        _check(load_library().mol_profile_enable(1 if on else 0))
 
 
 def profile_read() -> dict:

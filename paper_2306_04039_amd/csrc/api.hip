@@ -25,7 +25,7 @@ struct ProfRec {
   hipEvent_t a, b;
 };
 struct Prof {
-  bool on = false;
+  uint32_t mask = 0;  // bit s: slot s is timed
   std::mutex mu;
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> pool;
@@ -44,7 +44,7 @@ struct Prof {
 }  // namespace
 
 void mol_prof_begin(int slot, hipStream_t st) {
-  if (!g_prof.on) return;
+  if (!((g_prof.mask >> slot) & 1u)) return;
   std::lock_guard<std::mutex> lk(g_prof.mu);
   hipEvent_t e = g_prof.get();
   if (e) (void)hipEventRecord(e, st);
@@ -52,7 +52,7 @@ void mol_prof_begin(int slot, hipStream_t st) {
 }
 
 void mol_prof_end(int slot, hipStream_t st) {
-  if (!g_prof.on) return;
+  if (!((g_prof.mask >> slot) & 1u)) return;
   std::lock_guard<std::mutex> lk(g_prof.mu);
   hipEvent_t a = g_prof.open_ev[slot];
   g_prof.open_ev[slot] = nullptr;
@@ -68,7 +68,7 @@ void mol_prof_end(int slot, hipStream_t st) {
 
 extern "C" mol_status_t mol_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof.mu);
-  g_prof.on = on != 0;
+  g_prof.mask = on == 1 ? 0xffffffffu : (on <= 0 ? 0u : (uint32_t)on >> 1);
   return MOL_OK;
 }
 

@@ -311,13 +311,29 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 }
 
 // U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
+// One thread per output, 8 bf16 of each operand per load when the rows allow it.
 __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, int B, int H, int d_gu) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * H) return;
   const int b = i / H, hh = i % H;
+  const uint4 *wr = reinterpret_cast<const uint4 *>(w1u + (size_t)hh * d_gu);
+  const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)b * d_gu);
   float acc = 0.f;
-  for (int j = 0; j < d_gu; ++j)
-    acc = fmaf(bf16_bits_to_f32(w1u[(size_t)hh * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+  if (d_gu % 8 != 0) {  // rows are not 16-byte aligned: element by element
+    for (int j = 0; j < d_gu; ++j)
+      acc = fmaf(bf16_bits_to_f32(w1u[(size_t)hh * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+    U[i] = acc;
+    return;
+  }
+  for (int j = 0; j < d_gu / 8; ++j) {
+    const uint4 w = wr[j], g = gr[j];
+    const uint32_t wv[4] = {w.x, w.y, w.z, w.w}, gv[4] = {g.x, g.y, g.z, g.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc = fmaf(bf16_bits_to_f32(wv[e] & 0xffffu), bf16_bits_to_f32(gv[e] & 0xffffu), acc);
+      acc = fmaf(bf16_bits_to_f32(wv[e] >> 16), bf16_bits_to_f32(gv[e] >> 16), acc);
+    }
+  }
   U[i] = acc;
 }
 

@@ -42,21 +42,24 @@ __device__ inline void msel_find(const uint32_t *g, int nb, uint32_t krem, MselS
   const int top = nb - 1 - t * per;  // this thread covers digits top, top-1, ..., top-per+1
   uint32_t s = 0;
   for (int j = 0; j < per; ++j) s += g[top - j];
-  sh.part[t] = s;
   if (t == 0) {
     sh.res[0] = 0;
     sh.res[1] = 0;
     sh.res[2] = 0;
   }
-  __syncthreads();
-  // inclusive prefix over threads (thread 0 holds the largest digits)
-  for (int o = 1; o < MSEL_THREADS; o <<= 1) {
-    const uint32_t add = (t >= o) ? sh.part[t - o] : 0u;
-    __syncthreads();
-    sh.part[t] += add;
-    __syncthreads();
+  // inclusive prefix over threads (thread 0 holds the largest digits): inside each wavefront with lane shuffles, then
+  // the wavefront totals through LDS
+  uint32_t incl_w = s;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl_w, o);
+    if ((t & 63) >= o) incl_w += up;
   }
-  const uint32_t incl = sh.part[t];
+  if ((t & 63) == 63) sh.part[t >> 6] = incl_w;
+  __syncthreads();
+  uint32_t before = 0;
+  for (int w = 0; w < (t >> 6); ++w) before += sh.part[w];
+  const uint32_t incl = incl_w + before;
   uint32_t above = incl - s;
   if (t == MSEL_THREADS - 1) sh.res[3] = incl;
   if (above < krem && krem <= incl) {
