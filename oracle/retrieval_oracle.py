@@ -29,7 +29,8 @@ Algorithm 2 with the whole corpus as the sample, P = 1 reduces to the scaled dot
 to one and phi lies between the smallest and largest component logit, a uniform gate gives the mean
 logit in closed form, a user-only gate reproduces Eq. 5 through a different evaluation order, one-hot
 gates expose the component index order, softmax shift invariance, a loop-by-loop re-derivation,
-K' = N two-stage equals exhaustive MoL, corpus permutation and batch-split invariance.
+K' = N two-stage equals exhaustive MoL, corpus permutation and batch-split invariance; INT8 quantisation against
+exact rational round-half-even on dyadic scales and hand-worked cases, INT8 scores against Python integers.
 The recall level of the approximate (sampled) mode is "parity unpinned": the paper's recall figure
 carries no numbers.
 """
@@ -53,11 +54,11 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 
 
 def as_f64(a: np.ndarray) -> np.ndarray:
-    """uint16 => bf16 bit patterns; float32/float64 => widened."""
+    """uint16 => bf16 bit patterns; float32/float64 => widened; int8 => the integers (quantised stage-1 vectors)."""
     a = np.asarray(a)
     if a.dtype == np.uint16:
         return bf16_bits_to_f64(a)
-    if a.dtype in (np.float32, np.float64):
+    if a.dtype in (np.float32, np.float64, np.int8):
         return a.astype(np.float64)
     raise TypeError(f"unsupported input dtype {a.dtype}")
 
@@ -87,8 +88,19 @@ def nth_largest(values: np.ndarray, r: int) -> float:
 
 
 # --------------------------------------------------------------------------- stage 1
+def quantize_int8(x: np.ndarray, scale: float) -> np.ndarray:
+    """INT8 stage-1 vectors (Section 4.1.1).  The paper gives no scheme; the reading taken is the plain symmetric one
+    with one scale per tensor: q = clamp(round_half_even(x * scale), -127, 127).  The product decides an integer, so it
+    is taken in the precision the kernel uses: both factors in fp32, one fp32 rounding, then the rounding to integer."""
+    xf = as_f64(x).astype(np.float32)                     # bf16 / fp32 inputs: exact
+    t = (xf * np.float32(scale)).astype(np.float32)       # fp32 * fp32 -> fp32, rounded once
+    return np.clip(np.rint(t), -127.0, 127.0).astype(np.int8)   # rint: halves to even
+
+
 def stage1_scores(Q1: np.ndarray, X1: np.ndarray) -> np.ndarray:
-    """s[b, n] = <Q1[b], X1[n]> in fp64 (Algorithm 2, dotProduct; Section 4.1.1)."""
+    """s[b, n] = <Q1[b], X1[n]> in fp64 (Algorithm 2, dotProduct; Section 4.1.1).  For int8 inputs the result is the
+    exact integer dot product (every product and every partial sum is an integer below 2^53), which is what the
+    selection consumes: no scale is applied to it (Section 4.1.1)."""
     return as_f64(Q1) @ as_f64(X1).T
 
 

@@ -409,3 +409,54 @@ def test_batch_split_invariance():
     for b in range(3):
         h1 = orc.hindexer(Q1[b:b + 1], X1, 30, S)[0]
         assert h1[0].tolist() == hw[b][0].tolist() and h1[2] == hw[b][2]
+
+
+# --------------------------------------------------------------------------- INT8 stage 1 (Section 4.1.1)
+def test_quantize_int8_hand_worked_cases():
+    """scale = 2 makes every product exact, so the expected codes follow from round-half-even and the clamp alone."""
+    x = np.array([0.0, 0.25, 0.75, 1.25, 1.75, -0.25, -0.75, -1.25, 100.0, -100.0, 63.5, -63.5, 63.75], dtype=np.float32)
+    want = np.array([0, 0, 2, 2, 4, 0, -2, -2, 127, -127, 127, -127, 127], dtype=np.int8)
+    assert np.array_equal(orc.quantize_int8(x, 2.0), want)
+    # the usual scale for unit-range data
+    y = np.array([1.0, -1.0, 0.5, -0.5, 0.25], dtype=np.float32)
+    assert np.array_equal(orc.quantize_int8(y, 127.0), np.array([127, -127, 64, -64, 32], dtype=np.int8))
+
+
+def test_quantize_int8_matches_exact_rational_rounding_on_dyadic_scales():
+    from fractions import Fraction
+    rng = np.random.default_rng(5)
+    x32 = rng.normal(size=400).astype(np.float32)
+    bits = (x32.view(np.uint32) >> 16).astype(np.uint16)              # truncate to bf16 bit patterns
+    for scale in (0.5, 8.0, 64.0):
+        got = orc.quantize_int8(bits, scale)
+        xs = orc.bf16_bits_to_f64(bits)
+        want = [max(-127, min(127, round(Fraction(float(v)) * Fraction(scale)))) for v in xs]   # Fraction.round: half even
+        assert got.tolist() == want
+        assert np.array_equal(got, orc.quantize_int8(xs.astype(np.float32), scale))               # bf16 bits == fp32 path
+
+
+def test_quantize_int8_is_monotone_and_within_half_a_step():
+    rng = np.random.default_rng(6)
+    x = np.sort(rng.uniform(-1, 1, size=2000).astype(np.float32))
+    q = orc.quantize_int8(x, 127.0).astype(np.int64)
+    assert np.all(np.diff(q) >= 0)
+    assert np.max(np.abs(q - x.astype(np.float64) * 127.0)) <= 0.5 + 1e-4
+    assert q.min() >= -127 and q.max() <= 127
+
+
+def test_int8_stage1_scores_are_the_integer_dot_products():
+    rng = np.random.default_rng(7)
+    Q = rng.integers(-127, 128, size=(3, 64), dtype=np.int8)
+    X = rng.integers(-127, 128, size=(50, 64), dtype=np.int8)
+    X[0] = 127
+    Q[0] = 127                                                          # the extreme: 64 * 127 * 127
+    s = orc.stage1_scores(Q, X)
+    for b in range(3):
+        for n in range(50):
+            assert s[b, n] == sum(int(Q[b, j]) * int(X[n, j]) for j in range(64))
+    assert s[0, 0] == 64 * 127 * 127
+    # integer scores tie often: the K' best are taken by (score desc, index asc)
+    X[10] = X[20]
+    s = orc.stage1_scores(Q, X)
+    ids, sc = orc.exact_topk_stage1(Q, X, 50)[1]
+    assert list(ids).index(10) + 1 == list(ids).index(20)
