@@ -105,6 +105,25 @@ def cpu_baseline(wl, items, q, gw, n_sub, kp_sub):
     }
 
 
+def stage1_recall(x1, q1, cand_idx, Kp, n_queries=4, chunk=10_000_000):
+    """Share of the unquantised stage-1 top-K' (torch matmul on the stored table, first n_queries queries) that the
+    candidate lists contain.  Evaluation of the quantisation only; not part of the timed path."""
+    import torch
+    nq = min(n_queries, q1.shape[0])
+    qt = q1[:nq].float().t().contiguous()
+    scores = torch.empty(nq, x1.shape[0], dtype=torch.float32, device=x1.device)
+    for lo in range(0, x1.shape[0], chunk):
+        scores[:, lo:lo + chunk] = (x1[lo:lo + chunk].float() @ qt).t()
+    hit = 0
+    for b in range(nq):
+        top = torch.topk(scores[b], Kp).indices
+        mark = torch.zeros(x1.shape[0], dtype=torch.bool, device=x1.device)
+        mark[top] = True
+        c = cand_idx[b]
+        hit += int(mark[c[c >= 0].long()].sum())
+    return hit / float(nq * Kp)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -113,6 +132,9 @@ def main():
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4"])
     ap.add_argument("--n-items", type=int, default=0, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--mode", type=int, default=0, help="0 = exact-on-success h-indexer (default), 1 = Algorithm 2 as written")
+    ap.add_argument("--stage1", default="config", choices=["config", "int8"],
+                    help="int8: quantise the stage-1 table and queries (Section 4.1.1) and run the h-indexer on INT8 operands; "
+                         "a different arithmetic from the named workload, reported as such")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run a plain 1 GiB device copy three times (gives profilers' byte counters a kernel of known traffic)")
@@ -133,7 +155,12 @@ def main():
 
     items, q, gw = generate(wl, dev)
     t0 = time.time()
-    corpus = m.mol_corpus_pack(items["x1"], items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+    int8 = args.stage1 == "int8"
+    x1, q1 = items["x1"], q["q1"]
+    if int8:
+        x1 = m.quantize_int8(items["x1"], 127.0 / float(items["x1"].float().abs().max()))
+        q1 = m.quantize_int8(q["q1"], 127.0 / float(q["q1"].float().abs().max()))
+    corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
                                logit_scale=wl.logit_scale, act=wl.act, borrow=True)
     log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
     n_sub = min(wl.N, 2_000_000)
@@ -150,7 +177,7 @@ def main():
     out2 = (torch.empty(B, k, dtype=torch.int32, device=dev), torch.empty(B, k, dtype=torch.float32, device=dev))
 
     def step(i):
-        m.hindexer_topk(corpus, q["q1"], Kp, lam=lam, seed=1000 + i, mode=args.mode, workspace=ws1, out=out1)
+        m.hindexer_topk(corpus, q1, Kp, lam=lam, seed=1000 + i, mode=args.mode, workspace=ws1, out=out1)
         m.mol_topk(corpus, q["F"], q["gu"], out1[0], k, workspace=ws2, out=out2)
 
     for i in range(args.warmup):
@@ -183,7 +210,7 @@ def main():
     assert int(counts.min()) >= 0, "h-indexer reported a failed query"
 
     scan_ms, scan_n = prof_scan["scan_filter"]
-    scan_bytes = wl.N * wl.d1 * (4 if wl.stage1_dtype == "f32" else 2)
+    scan_bytes = wl.N * wl.d1 * (1 if int8 else (4 if wl.stage1_dtype == "f32" else 2))
     achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
     mol_ms, mol_n = prof["mol_score"]
     gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + wl.H * 2 + 4 + 4)
@@ -191,7 +218,7 @@ def main():
 
     traffic = None
     t = SCAN_TRAFFIC_KIB.get(wl.name)
-    if t and not args.n_items and args.mode == 0:
+    if t and not args.n_items and args.mode == 0 and not int8:
         traffic = (t["fetch"] * t["fetch_scale"] + t["write"] * t["write_scale"]) * 1024.0
 
     result = {
@@ -207,10 +234,10 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if wl.stage1_dtype != "f32" else "f32",
+        "dtype": "int8 stage 1 (int32 scores) + bf16 MoL" if int8 else ("bf16" if wl.stage1_dtype != "f32" else "f32"),
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, K'={Kp}, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}, "
-                               f"h-indexer mode {args.mode}, lambda={lam}"},
+                               f"h-indexer mode {args.mode}, lambda={lam}" + (", INT8 stage 1" if int8 else "")},
         "roofline": {"kernel": "k_stage1_scan (corpus scan + threshold filter)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated)",
                      "algorithmic_bytes": scan_bytes,
@@ -222,6 +249,8 @@ def main():
                       "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0},
         "paper_context": PAPER_CONTEXT,
     }
+    if int8:
+        result["int8_stage1_recall_vs_unquantised_topKp"] = stage1_recall(items["x1"], q["q1"], out1[0], Kp)
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

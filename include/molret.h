@@ -40,7 +40,7 @@ typedef enum {
   MOL_EHIP = -5          /* a HIP runtime call failed */
 } mol_status_t;
 
-enum { MOL_F32 = 0, MOL_BF16 = 1 };       /* stage1_dtype */
+enum { MOL_F32 = 0, MOL_BF16 = 1, MOL_INT8 = 2 }; /* stage1_dtype */
 enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
 
 /* pack flags */
@@ -82,12 +82,23 @@ typedef struct {
  * Algorithm 1): keeps the stage-1 table [N, d1] and the item component embeddings [N, k_x, d_p] (already
  * L2-normalised by the caller, Eq. 9), and precomputes the item half of the first gating layer,
  * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H].
- *   stage1_items : [N, d1] of stage1_dtype, or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
+ *   stage1_items : [N, d1] of stage1_dtype (fp32, bf16 or int8), or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
  *   item_embs    : bf16 [N, k_x, d_p].      item_gate : bf16 [N, d_gx]; not referenced after the call returns.
  * Allocates device memory with hipMalloc; synchronises `stream` before returning.  *out is set on MOL_OK only.
  */
 mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *stage1_items, const void *item_embs,
                              const void *item_gate, void *stream, mol_corpus_t **out);
+
+/*
+ * INT8 stage 1 (Section 4.1.1: the stage-1 dot product runs on INT8 operands and its INT32 result goes to the selection
+ * without a de-quantising scale).  A corpus packed with stage1_dtype = MOL_INT8 takes stage1_items as int8 [N, 64] and
+ * hindexer_topk then takes q1 as int8 [B, 64]; scores are exact integers (|s| <= 64*127*127), reported in cand_score as
+ * floats holding those integers.  This helper produces such tensors with one symmetric scale per call:
+ *   dst[i] = clamp(rint(src[i] * scale), -127, 127), the product rounded once to fp32, halves rounded to even.
+ *   src : n elements of src_dtype (MOL_F32 or MOL_BF16), 16-byte aligned.   dst : int8 [n], 8-byte aligned.
+ * A common choice is scale = 127 / max|src|; any positive scale keeps the order of one query's scores up to rounding.
+ */
+mol_status_t mol_quantize_int8(const void *src, int src_dtype, int64_t n, float scale, int8_t *dst, void *stream);
 
 /* Frees what pack allocated (device synchronising).  NULL is accepted. */
 mol_status_t mol_corpus_free(mol_corpus_t *corpus);
@@ -120,7 +131,7 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *   cand_idx    : out int32 [B, Kp]; a set, in no particular order; unused slots are -1.
  *   cand_score  : out f32 [B, Kp] stage-1 scores aligned with cand_idx (unused slots -inf), or NULL.
  *   cand_count  : out int32 [B] number of valid slots.
- * Scores are fp32 accumulations of the stored bf16 / fp32 values.
+ * Scores are fp32 accumulations of the stored bf16 / fp32 values; exact integers for an int8 table.
  */
 mol_status_t hindexer_topk(const mol_corpus_t *corpus, const void *q1, int B, int Kp, const int32_t *sample_idx,
                            int64_t lambda, uint64_t seed, int mode, int32_t *cand_idx, float *cand_score,

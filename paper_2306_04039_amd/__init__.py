@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     mol_workspace_bytes,
     profile_enable,
     profile_read,
+    quantize_int8,
     HINDEXER_EXACT,
     HINDEXER_PAPER,
 )

@@ -20,7 +20,7 @@ _LIB = None
 EXPORTS = (
     "mol_corpus_pack", "mol_corpus_free", "hindexer_workspace_bytes", "mol_workspace_bytes",
     "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
-    "mol_profile_enable", "mol_profile_read",
+    "mol_profile_enable", "mol_profile_read", "mol_quantize_int8",
 )
 
 PROF_SLOTS = ("sample_scores", "threshold", "scan_filter", "select", "user_gate", "mol_score", "final_topk", "spare")
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.mol_profile_enable.restype = i32
     lib.mol_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.mol_profile_read.restype = i32
+    lib.mol_quantize_int8.argtypes = [vp, i32, i64, C.c_float, vp, vp]
+    lib.mol_quantize_int8.restype = i32
     lib.mol_last_error.argtypes = []
     lib.mol_last_error.restype = C.c_char_p
     _LIB = lib
@@ -149,13 +151,13 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     cfg = _Config()
     cfg.N = N
     if stage1_items is not None:
-        if stage1_items.dtype not in (torch.float32, torch.bfloat16):
-            raise ValueError("stage1_items must be float32 or bfloat16")
+        if stage1_items.dtype not in (torch.float32, torch.bfloat16, torch.int8):
+            raise ValueError("stage1_items must be float32, bfloat16 or int8")
         _dev(stage1_items, stage1_items.dtype, "stage1_items")
         if stage1_items.shape[0] != N:
             raise ValueError("stage1_items rows != N")
         cfg.d1 = stage1_items.shape[1]
-        cfg.stage1_dtype = 0 if stage1_items.dtype == torch.float32 else 1
+        cfg.stage1_dtype = {torch.float32: 0, torch.bfloat16: 1, torch.int8: 2}[stage1_items.dtype]
     else:
         cfg.d1 = 0
         cfg.stage1_dtype = 1
@@ -171,6 +173,19 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     keep = (stage1_items, item_embs) if borrow else None
     return Corpus(out.value, N, cfg.d1, None if stage1_items is None else stage1_items.dtype, k_u, k_x, d_p, H, d_gu,
                   keep)
+
+
+def quantize_int8(src: torch.Tensor, scale: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dst = clamp(rint(src * scale), -127, 127) as int8, same shape (Section 4.1.1)."""
+    if src.dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError("src must be float32 or bfloat16")
+    _dev(src, src.dtype, "src")
+    if out is None:
+        out = torch.empty(src.shape, dtype=torch.int8, device=src.device)
+    _dev(out, torch.int8, "out")
+    _check(load_library().mol_quantize_int8(_ptr(src), 0 if src.dtype == torch.float32 else 1, src.numel(), float(scale),
+                                            _ptr(out), _stream()))
+    return out
 
 
 def hindexer_default_lambda(corpus: Corpus, Kp: int) -> int:

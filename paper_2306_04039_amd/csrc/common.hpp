@@ -8,6 +8,8 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
 
 #define WAVE 64
 
@@ -59,6 +61,11 @@ __device__ __forceinline__ void mfma_settle() {
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
   __builtin_amdgcn_sched_barrier(0);
+}
+
+__device__ __forceinline__ i32x4 as_i32x4(uint4 v) {
+  i32x4 r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+  return r;
 }
 
 // 16-byte global load through a plain pointer.

@@ -134,7 +134,8 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   if (cfg->N < 1 || cfg->N >= (int64_t)1 << 31) return mol_fail(MOL_EINVAL, "N=%lld must be in [1, 2^31)", (long long)cfg->N);
   if (cfg->d1 != 0 && cfg->d1 != 64) return mol_fail(MOL_EUNSUPPORTED, "d1=%d: the stage-1 kernels are built for d1 = 64", cfg->d1);
   if (cfg->d1 != 0 && !stage1_items) return mol_fail(MOL_EINVAL, "stage1_items is NULL but d1 != 0");
-  if (cfg->stage1_dtype != MOL_F32 && cfg->stage1_dtype != MOL_BF16) return mol_fail(MOL_EINVAL, "bad stage1_dtype");
+  if (cfg->stage1_dtype != MOL_F32 && cfg->stage1_dtype != MOL_BF16 && cfg->stage1_dtype != MOL_INT8)
+    return mol_fail(MOL_EINVAL, "bad stage1_dtype");
   if (cfg->act != MOL_ACT_RELU && cfg->act != MOL_ACT_SILU) return mol_fail(MOL_EINVAL, "bad act");
   if (!mol_shape_supported(cfg->k_u, cfg->k_x, cfg->d_p, cfg->H))
     return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", cfg->k_u, cfg->k_x,
@@ -181,7 +182,7 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   ALLOC(c->b2, n5 * 4)
   ALLOC(c->xi, (size_t)c->N * H * 2)
   void *s1copy = nullptr, *embcopy = nullptr;
-  const size_t s1_bytes = (size_t)c->N * c->d1 * (c->stage1_dtype == MOL_F32 ? 4 : 2);
+  const size_t s1_bytes = (size_t)c->N * c->d1 * (c->stage1_dtype == MOL_F32 ? 4 : (c->stage1_dtype == MOL_BF16 ? 2 : 1));
   const size_t emb_bytes = (size_t)c->N * c->k_x * c->d_p * 2;
   if (c->d1 && !(cfg->flags & MOL_PACK_BORROW_STAGE1)) { ALLOC(s1copy, s1_bytes) }
   if (!(cfg->flags & MOL_PACK_BORROW_EMBS)) { ALLOC(embcopy, emb_bytes) }
@@ -220,6 +221,69 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     return rc;
   }
   *out = c;
+  return MOL_OK;
+}
+
+// Symmetric INT8 quantisation of stage-1 vectors (Section 4.1.1): q = clamp(rint(x * scale), -127, 127); the product is
+// taken in fp32 (one rounding), rint rounds halves to even.  8 elements per thread.
+template <bool SRC_BF16>
+__global__ void k_quantize_int8(const void *src, int64_t n, float scale, int8_t *dst) {
+  const int64_t i0 = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (i0 >= n) return;
+  float v[8];
+  const int m = (n - i0) < 8 ? (int)(n - i0) : 8;
+  if (m == 8) {
+    if (SRC_BF16) {
+      const uint4 u = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(src) + i0);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] = bf16_bits_to_f32(w[e] & 0xffffu);
+        v[2 * e + 1] = bf16_bits_to_f32(w[e] >> 16);
+      }
+    } else {
+      const float4 a = *reinterpret_cast<const float4 *>(static_cast<const float *>(src) + i0);
+      const float4 b = *reinterpret_cast<const float4 *>(static_cast<const float *>(src) + i0 + 4);
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+  } else {
+    for (int e = 0; e < m; ++e)
+      v[e] = SRC_BF16 ? bf16_bits_to_f32(static_cast<const uint16_t *>(src)[i0 + e]) : static_cast<const float *>(src)[i0 + e];
+  }
+  uint32_t lo = 0, hi = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (e < m) {
+      float t = rintf(__fmul_rn(v[e], scale));
+      t = fminf(fmaxf(t, -127.f), 127.f);
+      const uint32_t byte = (uint32_t)(int)t & 0xffu;
+      if (e < 4) lo |= byte << (8 * e); else hi |= byte << (8 * (e - 4));
+    }
+  }
+  if (m == 8) {
+    *reinterpret_cast<uint2 *>(dst + i0) = make_uint2(lo, hi);
+  } else {
+    for (int e = 0; e < m; ++e) dst[i0 + e] = (int8_t)((e < 4 ? lo >> (8 * e) : hi >> (8 * (e - 4))) & 0xffu);
+  }
+}
+
+extern "C" mol_status_t mol_quantize_int8(const void *src, int src_dtype, int64_t n, float scale, int8_t *dst,
+                                          void *stream) {
+  if (!src || !dst) return mol_fail(MOL_EINVAL, "mol_quantize_int8: src and dst must not be NULL");
+  if (src_dtype != MOL_F32 && src_dtype != MOL_BF16) return mol_fail(MOL_EINVAL, "mol_quantize_int8: src_dtype must be MOL_F32 or MOL_BF16");
+  if (n < 0 || !(scale > 0.f) || !isfinite(scale)) return mol_fail(MOL_EINVAL, "mol_quantize_int8: n >= 0 and a finite scale > 0 are required");
+  if ((reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(dst) & 7u))
+    return mol_fail(MOL_EINVAL, "mol_quantize_int8: src must be 16-byte and dst 8-byte aligned");
+  if (n == 0) return MOL_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t threads = (n + 7) / 8;
+  const unsigned grid = (unsigned)((threads + 255) / 256);
+  if (src_dtype == MOL_BF16)
+    hipLaunchKernelGGL(k_quantize_int8<true>, dim3(grid), dim3(256), 0, st, src, n, scale, dst);
+  else
+    hipLaunchKernelGGL(k_quantize_int8<false>, dim3(grid), dim3(256), 0, st, src, n, scale, dst);
+  HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
 

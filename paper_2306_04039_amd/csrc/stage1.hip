@@ -151,14 +151,18 @@ __device__ inline bool last_workgroup(uint32_t *ticket) {
   return s_last != 0;
 }
 
-// F32 = false: bf16 rows of 64 (128 B), 4 x 16-byte chunks per lane, one 32x32x16 MFMA per chunk.
-// F32 = true : fp32 rows of 64 (256 B), 8 x 16-byte chunks per lane, four 32x32x2 MFMAs per chunk.
+// DT = MOL_BF16: bf16 rows of 64 (128 B), 4 x 16-byte chunks per lane, one 32x32x16 MFMA per chunk.
+// DT = MOL_F32 : fp32 rows of 64 (256 B), 8 x 16-byte chunks per lane, four 32x32x2 MFMAs per chunk.
+// DT = MOL_INT8: int8 rows of 64 (64 B), 2 x 16-byte chunks per lane, one 32x32x32 integer MFMA per chunk; the int32
+//                sums (|s| <= 64*127*127 < 2^24) are converted to fp32 exactly, so everything after the contraction
+//                -- threshold compare, keys, selection -- is the same code and the same total order (Section 4.1.1:
+//                the integer scores go to the selection as they are, no scale is applied).
 // Lane (r = lane%32, h = lane/32) takes chunks 2*ci + h of row r; the query operand uses the same chunk
 // numbering, so the contraction pairs equal positions whatever order the hardware walks them in.
-template <bool F32, int NQG, int EPI, bool GATHER, int DEPTH>
+template <int DT, int NQG, int EPI, bool GATHER, int DEPTH>
 __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
-  constexpr int NCH = F32 ? 8 : 4;
-  constexpr int ROWB = F32 ? 256 : 128;
+  constexpr int NCH = DT == MOL_F32 ? 8 : (DT == MOL_BF16 ? 4 : 2);
+  constexpr int ROWB = DT == MOL_F32 ? 256 : (DT == MOL_BF16 ? 128 : 64);
   constexpr bool REDO = EPI >= EPI_HIST_KEY;
   constexpr bool HIST = EPI == EPI_HIST_KEY || EPI == EPI_HIST_IDX;
   constexpr bool LISTS = EPI == EPI_FILTER;
@@ -250,15 +254,21 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
       const int64_t tile = tile_of(it0 + i);
       if (tile >= ntiles) break;  // tile_of grows with its argument: nothing valid follows
       f32x16 acc[NQG];
+      i32x16 iacc[NQG];  // DT = MOL_INT8 only
 #pragma unroll
       for (int g = 0; g < NQG; ++g)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[g][j] = 0.f;
+        for (int j = 0; j < 16; ++j) {
+          acc[g][j] = 0.f;
+          iacc[g][j] = 0;
+        }
 #pragma unroll
       for (int ci = 0; ci < NCH; ++ci) {
 #pragma unroll
         for (int g = 0; g < NQG; ++g) {
-          if constexpr (F32) {
+          if constexpr (DT == MOL_INT8) {
+            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(buf[i][ci]), as_i32x4(q[g][ci]), iacc[g], 0, 0, 0);
+          } else if constexpr (DT == MOL_F32) {
             const float av[4] = {__uint_as_float(buf[i][ci].x), __uint_as_float(buf[i][ci].y),
                                  __uint_as_float(buf[i][ci].z), __uint_as_float(buf[i][ci].w)};
             const float qv[4] = {__uint_as_float(q[g][ci].x), __uint_as_float(q[g][ci].y),
@@ -276,6 +286,12 @@ __global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
         if (tnext < ntiles) load_tile(buf[i], tnext);
       }
       mfma_settle();
+      if constexpr (DT == MOL_INT8) {
+#pragma unroll
+        for (int g = 0; g < NQG; ++g)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[g][j] = (float)iacc[g][j];
+      }
 
       // acc[g][j]: item row 8*(j/4) + 4*h + j%4 of the tile, query qbase + 32*g + r
       const int64_t row0 = tile * 32 + 4 * h;
@@ -696,11 +712,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
 }
 
 // ---- launch helpers ----------------------------------------------------------------------------------------------
-template <bool F32, int EPI, bool GATHER>
+template <int DT, int EPI, bool GATHER>
 void (*scan_kernel(int nqg))(ScanArgs) {
   constexpr int DEPTH = MOL_SCAN_DEPTH;
-  return nqg == 4 ? k_stage1_scan<F32, 4, EPI, GATHER, DEPTH>
-                  : (nqg == 2 ? k_stage1_scan<F32, 2, EPI, GATHER, DEPTH> : k_stage1_scan<F32, 1, EPI, GATHER, DEPTH>);
+  return nqg == 4 ? k_stage1_scan<DT, 4, EPI, GATHER, DEPTH>
+                  : (nqg == 2 ? k_stage1_scan<DT, 2, EPI, GATHER, DEPTH> : k_stage1_scan<DT, 1, EPI, GATHER, DEPTH>);
 }
 
 // dynamic LDS of one scan workgroup
@@ -722,9 +738,9 @@ int device_cus() {
 
 // Workgroups (of 4 wavefronts) a scan over `ntiles` tiles is launched with: resident blocks, at most one tile each.
 // fixed_grid > 0 forces the grid (the survivor lists are laid out for a given number of wavefronts).
-template <bool F32, int EPI, bool GATHER>
+template <int DT, int EPI, bool GATHER>
 mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
-  auto kern = scan_kernel<F32, EPI, GATHER>(nqg);
+  auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
   const size_t lds = scan_lds_bytes(EPI, nqg);
   if (lds > 48 * 1024)
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -742,7 +758,7 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   return MOL_OK;
 }
 
-template <bool F32, int EPI, bool GATHER>
+template <int DT, int EPI, bool GATHER>
 mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStream_t st) {
   const int64_t ntiles = (a0.n_rows + 31) / 32;
   for (int qb = 0; qb < B; qb += 128) {
@@ -750,9 +766,9 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStrea
     a.qbase = qb;
     const int rem = B - qb;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
-    auto kern = scan_kernel<F32, EPI, GATHER>(nqg);
+    auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
     int64_t grid = 0;
-    mol_status_t rc = scan_grid<F32, EPI, GATHER>(nqg, ntiles, &grid);
+    mol_status_t rc = scan_grid<DT, EPI, GATHER>(nqg, ntiles, &grid);
     if (rc != MOL_OK) return rc;
     if (fixed_grid > 0) grid = fixed_grid;
     const size_t lds = scan_lds_bytes(EPI, nqg);
@@ -764,15 +780,27 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStrea
 
 // The grid of the list-writing scan of a call: the smallest over the query-group variants the call will launch, so
 // that the list layout (L = 8 * grid lists per query) is the same for all of them.
-mol_status_t list_scan_grid(bool f32, int B, int64_t N, int64_t *grid_out) {
+// launch_scan / scan_grid for a run-time stage-1 dtype
+template <int EPI, bool GATHER>
+mol_status_t launch_scan_dt(int dt, const ScanArgs &a, int B, int64_t fixed_grid, hipStream_t st) {
+  switch (dt) {
+    case MOL_F32: return launch_scan<MOL_F32, EPI, GATHER>(a, B, fixed_grid, st);
+    case MOL_BF16: return launch_scan<MOL_BF16, EPI, GATHER>(a, B, fixed_grid, st);
+    case MOL_INT8: return launch_scan<MOL_INT8, EPI, GATHER>(a, B, fixed_grid, st);
+  }
+  return mol_fail(MOL_EINVAL, "unknown stage-1 dtype %d", dt);
+}
+
+mol_status_t list_scan_grid(int dt, int B, int64_t N, int64_t *grid_out) {
   const int64_t ntiles = (N + 31) / 32;
   int64_t best = -1;
   for (int qb = 0; qb < B; qb += 128) {
     const int rem = B - qb;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
     int64_t g = 0;
-    mol_status_t rc = f32 ? scan_grid<true, EPI_FILTER, false>(nqg, ntiles, &g)
-                          : scan_grid<false, EPI_FILTER, false>(nqg, ntiles, &g);
+    mol_status_t rc = dt == MOL_F32 ? scan_grid<MOL_F32, EPI_FILTER, false>(nqg, ntiles, &g)
+                                    : (dt == MOL_BF16 ? scan_grid<MOL_BF16, EPI_FILTER, false>(nqg, ntiles, &g)
+                                                      : scan_grid<MOL_INT8, EPI_FILTER, false>(nqg, ntiles, &g));
     if (rc != MOL_OK) return rc;
     if (best < 0 || g < best) best = g;
   }
@@ -801,7 +829,7 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   if (rank > lambda) rank = lambda;
   p->rank = rank;
 
-  mol_status_t rc = list_scan_grid(c->stage1_dtype == MOL_F32, B, N, &p->grid);
+  mol_status_t rc = list_scan_grid(c->stage1_dtype, B, N, &p->grid);
   if (rc != MOL_OK) return rc;
   p->L = p->grid * 8;  // 4 wavefronts per workgroup, 2 lists (lane halves) per wavefront
   // rows one list can see: the tiles of its wavefront, 16 rows of each
@@ -853,7 +881,7 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
 mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
                           uint64_t seed, int mode, const HindexerPlan &p, int32_t *cand_idx, float *cand_score,
                           int32_t *cand_count, char *ws, hipStream_t st) {
-  const bool f32 = (c->stage1_dtype == MOL_F32);
+  const int dt = c->stage1_dtype;
   float *thr = reinterpret_cast<float *>(ws + p.off_thr);
   uint32_t *cnt = reinterpret_cast<uint32_t *>(ws + p.off_count);
   uint32_t *flags = reinterpret_cast<uint32_t *>(ws + p.off_flags);
@@ -905,7 +933,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     mol_status_t rc;
     {
       ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
-      rc = f32 ? launch_scan<true, EPI_KEYS, true>(s, B, 0, st) : launch_scan<false, EPI_KEYS, true>(s, B, 0, st);
+      rc = launch_scan_dt<EPI_KEYS, true>(dt, s, B, 0, st);
     }
     if (rc != MOL_OK) return rc;
     ProfScope ps(MOL_PROF_THRESHOLD, st);
@@ -927,7 +955,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   mol_status_t rc;
   {
     ProfScope ps(MOL_PROF_SCAN_FILTER, st);
-    rc = f32 ? launch_scan<true, EPI_FILTER, false>(a, B, p.grid, st) : launch_scan<false, EPI_FILTER, false>(a, B, p.grid, st);
+    rc = launch_scan_dt<EPI_FILTER, false>(dt, a, B, p.grid, st);
   }
   if (rc != MOL_OK) return rc;
 
@@ -968,13 +996,13 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     a.gate = gate + (pass < 4 ? 0 : 1);
     a.stage = pass + 1;
     if (pass < 4)
-      rc = f32 ? launch_scan<true, EPI_HIST_KEY, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_KEY, false>(a, B, 0, st);
+      rc = launch_scan_dt<EPI_HIST_KEY, false>(dt, a, B, 0, st);
     else
-      rc = f32 ? launch_scan<true, EPI_HIST_IDX, false>(a, B, 0, st) : launch_scan<false, EPI_HIST_IDX, false>(a, B, 0, st);
+      rc = launch_scan_dt<EPI_HIST_IDX, false>(dt, a, B, 0, st);
     if (rc != MOL_OK) return rc;
   }
   a.gate = gate;
-  rc = f32 ? launch_scan<true, EPI_FILTER_EXACT, false>(a, B, 0, st) : launch_scan<false, EPI_FILTER_EXACT, false>(a, B, 0, st);
+  rc = launch_scan_dt<EPI_FILTER_EXACT, false>(dt, a, B, 0, st);
   if (rc != MOL_OK) return rc;
   return MOL_OK;
 }
