@@ -28,7 +28,13 @@
 #define MOL_SCAN_TILE_RUN 4  // consecutive 32-row tiles a wavefront reads before it strides by the whole grid
 #endif
 #ifndef MOL_SCAN_PER_CU
-#define MOL_SCAN_PER_CU 2    // resident workgroups per compute unit
+#define MOL_SCAN_PER_CU 2    // resident workgroups per compute unit (bf16 / fp32 table)
+#endif
+#ifndef MOL_SCAN_PER_CU_I8
+#define MOL_SCAN_PER_CU_I8 4 // int8 table (half the bytes per tile): more wavefronts, one tile in flight each
+#endif
+#ifndef MOL_SCAN_DEPTH_I8
+#define MOL_SCAN_DEPTH_I8 1
 #endif
 
 namespace {
@@ -714,7 +720,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2
 // ---- launch helpers ----------------------------------------------------------------------------------------------
 template <int DT, int EPI, bool GATHER>
 void (*scan_kernel(int nqg))(ScanArgs) {
-  constexpr int DEPTH = MOL_SCAN_DEPTH;
+  constexpr int DEPTH = DT == MOL_INT8 ? MOL_SCAN_DEPTH_I8 : MOL_SCAN_DEPTH;
   return nqg == 4 ? k_stage1_scan<DT, 4, EPI, GATHER, DEPTH>
                   : (nqg == 2 ? k_stage1_scan<DT, 2, EPI, GATHER, DEPTH> : k_stage1_scan<DT, 1, EPI, GATHER, DEPTH>);
 }
@@ -747,7 +753,8 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   int per_sm = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, lds));
   if (per_sm < 1) per_sm = 1;
-  if (per_sm > MOL_SCAN_PER_CU) per_sm = MOL_SCAN_PER_CU;
+  constexpr int PER_CU = DT == MOL_INT8 ? MOL_SCAN_PER_CU_I8 : MOL_SCAN_PER_CU;
+  if (per_sm > PER_CU) per_sm = PER_CU;
   const int cus = device_cus();
   if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
   int64_t grid = (int64_t)cus * per_sm;
