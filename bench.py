@@ -23,7 +23,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the corpus scan moves on the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script (KiB per dispatch), each scaled by what the same counter reads for a 1 GiB device copy (--calibrate-copy):
 # FETCH_SIZE counts half the bytes (x2.000), WRITE_SIZE all of them (x1.000).  Re-measure when the scan kernel changes.
-SCAN_TRAFFIC_KIB = {"C4-100M": {"fetch": 6250074.1, "fetch_scale": 2.0, "write": 116014.1, "write_scale": 1.0}}
+SCAN_TRAFFIC_KIB = {("C4-100M", False): {"fetch": 6250189.3, "fetch_scale": 2.0, "write": 31767.9, "write_scale": 1.0},
+                    ("C4-100M", True): {"fetch": 3125102.7, "fetch_scale": 2.0, "write": 33731.6, "write_scale": 1.0}}  # key: (workload, int8 stage 1)
 
 # context only: the paper's serving latency for MoL + h-indexer on its (unnamed) production GPU, Section 5.3
 PAPER_CONTEXT = {"median_latency_ms_incl_batching_wait": 30.0, "hardware": "unnamed production GPU", "source": "Section 5.3"}
@@ -217,8 +218,8 @@ def main():
     mol_flops = B * Kp * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
 
     traffic = None
-    t = SCAN_TRAFFIC_KIB.get(wl.name)
-    if t and not args.n_items and args.mode == 0 and not int8:
+    t = SCAN_TRAFFIC_KIB.get((wl.name, int8))
+    if t and not args.n_items and args.mode == 0:
         traffic = (t["fetch"] * t["fetch_scale"] + t["write"] * t["write_scale"]) * 1024.0
 
     result = {
