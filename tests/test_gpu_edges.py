@@ -1,0 +1,106 @@
+"""GPU edge cases: smallest and largest sizes the boundary accepts, and the two-level final selection with ties and padding."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import retrieval_oracle as orc
+from parity_util import assert_scores_close, assert_sorted_desc, assert_topk_set, bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+S1_TOL = 2e-6
+
+
+def m():
+    import paper_2306_04039_amd as lib
+    return lib
+
+
+def make(wl):
+    cen = synth.make_centres(wl, DEV)
+    return synth.make_items(wl, cen), synth.make_queries(wl, cen), synth.make_gate_weights(wl, DEV)
+
+
+def pack(wl, items, gw):
+    return m().mol_corpus_pack(items["x1"], items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                               logit_scale=wl.logit_scale, act=wl.act)
+
+
+def check_two_stage(wl, items, q, gw, corpus, queries):
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], wl.Kp, seed=3)
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], ci, wl.k)
+    torch.cuda.synchronize()
+    s = orc.stage1_scores(bits(q["q1"]), bits(items["x1"]))
+    model = orc.MolModel(bits(items["G"]), bits(items["gx"]), bits(gw.W1), bits(gw.b1), bits(gw.W2), bits(gw.b2),
+                         wl.logit_scale, wl.act)
+    ci, cc, idx, sc = ci.cpu().numpy(), cc.cpu().numpy(), idx.cpu().numpy(), sc.cpu().numpy()
+    kp_eff = min(wl.Kp, wl.N)
+    assert np.all(cc == kp_eff)
+    for b in queries:
+        assert_topk_set(ci[b, :kp_eff], s[b], kp_eff, S1_TOL, f"stage 1, query {b}")
+        cand = ci[b, :kp_eff].astype(np.int64)
+        phi = orc.mol_scores_for(model, orc.as_f64(bits(q["F"])[b]), orc.as_f64(bits(q["gu"])[b]), cand)
+        lookup = dict(zip(cand.tolist(), phi.tolist()))
+        kk = min(wl.k, kp_eff)
+        kth = np.sort(phi)[::-1][kk - 1]
+        assert_topk_set(idx[b, :kk], lookup, kk, 2e-3 * abs(kth) + 1e-4 * wl.logit_scale, f"stage 2, query {b}")
+        assert_scores_close(sc[b, :kk], [lookup[i] for i in idx[b, :kk].tolist()], wl.logit_scale, f"query {b}")
+        assert_sorted_desc(sc[b, :kk], idx[b, :kk], f"query {b}")
+        assert np.all(idx[b, kk:] == -1) and np.all(np.isneginf(sc[b, kk:]))
+
+
+@pytest.mark.parametrize("N,B,Kp,k", [(1, 1, 1, 1), (17, 2, 17, 5), (31, 3, 1, 1), (33, 1, 20, 20), (64, 4, 64, 100)])
+def test_tiny_corpora(N, B, Kp, k):
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, k=k, n_clusters=min(4, N))
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    check_two_stage(wl, items, q, gw, corpus, range(B))
+    corpus.free()
+
+
+def test_largest_batch():
+    """B = 1024 is the largest batch the boundary takes (eight launches of 128 queries in the scan)."""
+    wl = synth.CONFIGS["C1"].replace(N=6000, B=1024, Kp=64, k=8, n_clusters=16)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    check_two_stage(wl, items, q, gw, corpus, [0, 1, 127, 128, 500, 1023])
+    with pytest.raises(m().MolError) as e:
+        m().hindexer_topk(corpus, torch.cat([q["q1"], q["q1"][:1]]), wl.Kp)
+    assert e.value.status == -1
+    corpus.free()
+
+
+@pytest.mark.parametrize("Kp,k", [(4000, 1024), (40_000, 1024), (20_000, 100), (20_000, 7), (8192, 1)])
+def test_final_selection_levels_with_ties_and_padding(Kp, k):
+    """Single-level (k large against the row) and two-level selection give the k best under (score desc, index asc),
+    with duplicated items (exact ties across slices) and padding scattered through the candidate rows."""
+    wl = synth.CONFIGS["C2"].replace(N=50_000, B=3, n_clusters=8)
+    items, q, gw = make(wl)
+    for key in ("G", "gx"):
+        items[key][25_000:26_000] = items[key][0:1000]           # 1000 exact duplicates, far apart in the row
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(Kp + k)
+    cand = torch.stack([torch.randperm(wl.N, generator=g)[:Kp] for _ in range(3)]).to(torch.int32)
+    cand[0, :1000] = torch.arange(1000, dtype=torch.int32)
+    cand[0, Kp - 1000:] = torch.arange(25_000, 26_000, dtype=torch.int32)
+    cand[1, torch.rand(Kp, generator=g) < 0.3] = -1              # 30 % padding anywhere
+    cand[2, k // 2:] = -1                                        # fewer valid candidates than k
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], cand.to(DEV), k)
+    scores = m().mol_score(corpus, q["F"], q["gu"], cand.to(DEV)).cpu().numpy()
+    idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
+    for b in range(3):
+        ids = cand[b].numpy()
+        valid = ids >= 0
+        ids_v, s_v = ids[valid], scores[b][valid].astype(np.float64)
+        assert np.all(np.isneginf(scores[b][~valid]))
+        # row 0 lists some items twice (the overwritten head and tail can repeat a random pick): keep one copy each
+        ids_u, first = np.unique(ids_v, return_index=True)
+        if b != 0:
+            assert len(ids_u) == len(ids_v)
+        kk = min(k, len(ids_v))
+        want = np.lexsort((ids_v, -s_v))[:kk]
+        assert idx[b, :kk].tolist() == ids_v[want].tolist(), f"row {b}"
+        assert np.array_equal(sc[b, :kk], scores[b][valid][want])
+        assert np.all(idx[b, kk:] == -1) and np.all(np.isneginf(sc[b, kk:]))
+    corpus.free()
