@@ -17,7 +17,9 @@ What it follows (paper sections, in the paper's notation):
   * gating: Eq. 8 / Section 3.2 (a network of item-side, user-side and cross inputs whose output is
     a probability distribution over the k_u*k_x components, Section 3.2 last paragraph), in the
     concrete form of the benchmark workloads: a 2-layer MLP on [component logits || user gate
-    feature || item gate feature] followed by a softmax over the P components.
+    feature || item gate feature] followed by a softmax over the P components; and, as a second
+    form, Algorithm 1's decomposedGating with the choices of Section 3.4 (three 2-layer MLPs,
+    uw * xw + cw, SiLU, softmax).
   * similarity: Eq. 3 / Algorithm 1: phi = sum_p pi_p * cl_p, then the k best.
 
 Readings where the paper is silent (ordering of equal scores, rank rounding, ...) are taken as:
@@ -30,7 +32,9 @@ to one and phi lies between the smallest and largest component logit, a uniform 
 logit in closed form, a user-only gate reproduces Eq. 5 through a different evaluation order, one-hot
 gates expose the component index order, softmax shift invariance, a loop-by-loop re-derivation,
 K' = N two-stage equals exhaustive MoL, corpus permutation and batch-split invariance; INT8 quantisation against
-exact rational round-half-even on dyadic scales and hand-worked cases, INT8 scores against Python integers.
+exact rational round-half-even on dyadic scales and hand-worked cases, INT8 scores against Python integers;
+Algorithm 1's decomposed gate: distribution / convexity, P = 1, all-zero heads give the mean logit, constant heads in
+the two SiLU limits (softmax of the product; uniform), one-hot selection, scalar-loop re-derivation.
 The recall level of the approximate (sampled) mode is "parity unpinned": the paper's recall figure
 carries no numbers.
 """
@@ -194,6 +198,38 @@ def gating_weights(cl: np.ndarray, gu_b: np.ndarray, gx_rows: np.ndarray, W1: np
     return e / e.sum(axis=1, keepdims=True)
 
 
+def _mlp2(x: np.ndarray, Wa: np.ndarray, ba: np.ndarray, Wb: np.ndarray, bb: np.ndarray, act: str) -> np.ndarray:
+    """Two-layer MLP, rows of x: Wb * act(Wa * x + ba) + bb."""
+    return _act(x @ Wa.T + ba, act) @ Wb.T + bb
+
+
+def decomposed_gating(cl: np.ndarray, gu_b: np.ndarray, gx_rows: np.ndarray, user_mlp, item_mlp, cross_mlp,
+                      act: str = "relu") -> np.ndarray:
+    """Algorithm 1, decomposedGating, with the choices Section 3.4 names: userWeightFn, itemWeightFn and crossWeightFn
+    are 2-layer MLPs with k_u*k_x outputs; combineFn(uw, xw, cw) = uw * xw + cw (element-wise) followed by SiLU; then
+    the softmax over the components.  Each *_mlp is (Wa, ba, Wb, bb); `act` is the MLPs' hidden nonlinearity (the paper
+    does not name it)."""
+    uw = _mlp2(gu_b[None, :], *user_mlp, act)          # uWeights      (1, P)
+    xw = _mlp2(gx_rows, *item_mlp, act)                # xWeights      (n, P)   cachable
+    cw = _mlp2(cl, *cross_mlp, act)                    # crossWeights  (n, P)
+    z = _act(uw * xw + cw, "silu")                     # combineFn, then SiLU
+    z = z - z.max(axis=1, keepdims=True)
+    e = np.exp(z)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+class MolModelDecomposed:
+    """Algorithm 1's gate (three 2-layer MLPs, multiplicative combination), decoded to fp64 once."""
+
+    def __init__(self, G, gx, user_mlp, item_mlp, cross_mlp, logit_scale: float = 1.0, act: str = "relu"):
+        self.G = as_f64(G)
+        self.gx = as_f64(gx)
+        dec = lambda m: tuple(as_f64(t) for t in m)
+        self.user_mlp, self.item_mlp, self.cross_mlp = dec(user_mlp), dec(item_mlp), dec(cross_mlp)
+        self.logit_scale = float(logit_scale)
+        self.act = act
+
+
 class MolModel:
     """Weights and item-side tensors, decoded to fp64 once."""
 
@@ -216,7 +252,10 @@ def mol_scores_for(model: MolModel, F_b: np.ndarray, gu_b: np.ndarray, ids: np.n
     for lo in range(0, ids.shape[0], chunk):
         sel = ids[lo: lo + chunk]
         cl = component_logits(F_b, model.G[sel], model.logit_scale)
-        pi = gating_weights(cl, gu_b, model.gx[sel], model.W1, model.b1, model.W2, model.b2, model.act)
+        if isinstance(model, MolModelDecomposed):
+            pi = decomposed_gating(cl, gu_b, model.gx[sel], model.user_mlp, model.item_mlp, model.cross_mlp, model.act)
+        else:
+            pi = gating_weights(cl, gu_b, model.gx[sel], model.W1, model.b1, model.W2, model.b2, model.act)
         out[lo: lo + chunk] = (pi * cl).sum(axis=1)
     return out
 

@@ -460,3 +460,126 @@ def test_int8_stage1_scores_are_the_integer_dot_products():
     s = orc.stage1_scores(Q, X)
     ids, sc = orc.exact_topk_stage1(Q, X, 50)[1]
     assert list(ids).index(10) + 1 == list(ids).index(20)
+
+
+# --------------------------------------------------------------------------- Algorithm 1's decomposed gate
+def small_decomposed(rng, N=30, k_u=2, k_x=3, d=8, H=5, Hu=4, Hx=6, d_gu=4, d_gx=3, scale=1.0, act="relu"):
+    P = k_u * k_x
+    G = rand_bf16_bits(rng, (N, k_x, d), 0.5)
+    gx = rand_bf16_bits(rng, (N, d_gx), 0.5)
+
+    def mlp(d_in, d_h):
+        return (rand_bf16_bits(rng, (d_h, d_in), 0.7), (rng.standard_normal(d_h) * 0.3).astype(np.float32),
+                rand_bf16_bits(rng, (P, d_h), 0.7), (rng.standard_normal(P) * 0.3).astype(np.float32))
+
+    model = orc.MolModelDecomposed(G, gx, mlp(d_gu, Hu), mlp(d_gx, Hx), mlp(P, H), logit_scale=scale, act=act)
+    F = rand_bf16_bits(rng, (3, k_u, d), 0.5)
+    gu = rand_bf16_bits(rng, (3, d_gu), 0.5)
+    return model, F, gu
+
+
+def _with(mlp, Wb=None, bb=None):
+    Wa, ba, Wb0, bb0 = mlp
+    return (Wa, ba, Wb0 if Wb is None else Wb, bb0 if bb is None else bb)
+
+
+def test_decomposed_gate_is_a_distribution_and_single_component_is_the_dot_product():
+    rng = np.random.default_rng(31)
+    model, F, gu = small_decomposed(rng, act="silu", scale=2.0)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    cl = orc.component_logits(Ff[0], model.G, 2.0)
+    pi = orc.decomposed_gating(cl, guf[0], model.gx, model.user_mlp, model.item_mlp, model.cross_mlp, "silu")
+    assert np.allclose(pi.sum(axis=1), 1.0, atol=1e-14) and np.all(pi > 0)
+    phi = orc.mol_scores_for(model, Ff[0], guf[0], np.arange(30))
+    assert np.all(phi <= cl.max(axis=1) + 1e-12) and np.all(phi >= cl.min(axis=1) - 1e-12)
+    one, F1, gu1 = small_decomposed(rng, k_u=1, k_x=1, scale=0.7)
+    s = orc.mol_scores(one, F1, gu1)
+    want = 0.7 * np.einsum("bd,nd->bn", orc.as_f64(F1)[:, 0], one.G[:, 0])
+    assert np.allclose(s, want, atol=1e-14)
+
+
+def test_decomposed_gate_all_zero_heads_give_the_mean_logit():
+    """Second layers zero: uw = xw = cw = 0, SiLU(0) = 0, so the gate is uniform and phi is the mean component logit."""
+    rng = np.random.default_rng(32)
+    model, F, gu = small_decomposed(rng)
+    P = 6
+    Z = lambda m: _with(m, Wb=np.zeros_like(orc.as_f64(m[2])), bb=np.zeros(P))
+    model.user_mlp, model.item_mlp, model.cross_mlp = Z(model.user_mlp), Z(model.item_mlp), Z(model.cross_mlp)
+    s = orc.mol_scores(model, F, gu)
+    Ff = orc.as_f64(F)
+    want = np.einsum("bd,nd->bn", Ff.sum(axis=1), model.G.sum(axis=1)) / P
+    assert np.allclose(s, want, atol=1e-13)
+
+
+def test_decomposed_gate_combination_is_a_product_plus_cross_then_silu():
+    """Constant heads expose combineFn: uw = a, xw = c (vectors over components), cw = t (scalar shift).
+    t -> +large: SiLU is the identity there and the softmax forgets the shift, so pi = softmax(a * c);
+    t -> -large: SiLU goes to 0 for every component, so pi is uniform.  A sum instead of a product, a missing SiLU,
+    or the SiLU applied after the softmax would each break one of the two limits."""
+    rng = np.random.default_rng(33)
+    model, F, gu = small_decomposed(rng, N=12)
+    P = 6
+    a = rng.standard_normal(P)
+    c = rng.standard_normal(P)
+    zeroW = lambda m: np.zeros_like(orc.as_f64(m[2]))
+    model.user_mlp = _with(model.user_mlp, Wb=zeroW(model.user_mlp), bb=a)
+    model.item_mlp = _with(model.item_mlp, Wb=zeroW(model.item_mlp), bb=c)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    cl = orc.component_logits(Ff[1], model.G, 1.0)
+    e = np.exp(a * c - (a * c).max())
+    soft = e / e.sum()
+    for t, want in ((60.0, soft), (-60.0, np.full(P, 1.0 / P))):
+        model.cross_mlp = _with(model.cross_mlp, Wb=zeroW(model.cross_mlp), bb=np.full(P, t))
+        pi = orc.decomposed_gating(cl, guf[1], model.gx, model.user_mlp, model.item_mlp, model.cross_mlp)
+        assert np.allclose(pi, want[None, :], atol=1e-12)
+        phi = orc.mol_scores_for(model, Ff[1], guf[1], np.arange(12))
+        assert np.allclose(phi, cl @ want, atol=1e-12)
+
+
+def test_decomposed_gate_one_hot_selects_the_user_major_component():
+    rng = np.random.default_rng(34)
+    model, F, gu = small_decomposed(rng, N=10, k_u=2, k_x=3)
+    P = 6
+    zeroW = lambda m: np.zeros_like(orc.as_f64(m[2]))
+    Ff = orc.as_f64(F)
+    for p_star in range(P):
+        hot = np.zeros(P)
+        hot[p_star] = 200.0
+        model.user_mlp = _with(model.user_mlp, Wb=zeroW(model.user_mlp), bb=hot)
+        model.item_mlp = _with(model.item_mlp, Wb=zeroW(model.item_mlp), bb=np.ones(P))
+        model.cross_mlp = _with(model.cross_mlp, Wb=zeroW(model.cross_mlp), bb=np.zeros(P))
+        s = orc.mol_scores(model, F, gu)
+        want = np.einsum("bd,nd->bn", Ff[:, p_star // 3], model.G[:, p_star % 3])
+        assert np.allclose(s, want, atol=1e-12)
+
+
+@pytest.mark.parametrize("act", ["relu", "silu"])
+def test_decomposed_gate_loop_by_loop(act):
+    """Scalar loops over Algorithm 1: three MLPs, product plus cross term, SiLU, softmax, weighted sum."""
+    import math
+    rng = np.random.default_rng(35)
+    model, F, gu = small_decomposed(rng, N=5, act=act, scale=1.7)
+    Ff, guf = orc.as_f64(F), orc.as_f64(gu)
+    k_u, d = Ff.shape[1], Ff.shape[2]
+    k_x = model.G.shape[1]
+    P = k_u * k_x
+    hidden = (lambda v: max(v, 0.0)) if act == "relu" else (lambda v: v / (1.0 + math.exp(-v)))
+
+    def mlp(m, x):
+        Wa, ba, Wb, bb = m
+        h = [hidden(ba[i] + sum(Wa[i, j] * x[j] for j in range(len(x)))) for i in range(Wa.shape[0])]
+        return [bb[p] + sum(Wb[p, i] * h[i] for i in range(len(h))) for p in range(Wb.shape[0])]
+
+    got = orc.mol_scores(model, F, gu)
+    for b in range(3):
+        uw = mlp(model.user_mlp, guf[b].tolist())
+        for n in range(5):
+            cl = [1.7 * sum(Ff[b, p // k_x, j] * model.G[n, p % k_x, j] for j in range(d)) for p in range(P)]
+            xw = mlp(model.item_mlp, model.gx[n].tolist())
+            cw = mlp(model.cross_mlp, cl)
+            z = [uw[p] * xw[p] + cw[p] for p in range(P)]
+            z = [v / (1.0 + math.exp(-v)) for v in z]
+            m = max(z)
+            e = [math.exp(v - m) for v in z]
+            phi = sum(ei * ci for ei, ci in zip(e, cl)) / sum(e)
+            assert abs(got[b, n] - phi) < 1e-12
