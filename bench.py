@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--stage1", default="config", choices=["config", "int8"],
                     help="int8: quantise the stage-1 table and queries (Section 4.1.1) and run the h-indexer on INT8 operands; "
                          "a different arithmetic from the named workload, reported as such")
+    ap.add_argument("--gate", default="config", choices=["config", "decomposed"],
+                    help="decomposed: Algorithm 1's gate (user / item / cross MLPs, uw*xw + cw, SiLU) instead of the workload's "
+                         "concatenated MLP; a different model, reported as such")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run a plain 1 GiB device copy three times (gives profilers' byte counters a kernel of known traffic)")
@@ -161,8 +164,15 @@ def main():
     if int8:
         x1 = m.quantize_int8(items["x1"], 127.0 / float(items["x1"].float().abs().max()))
         q1 = m.quantize_int8(q["q1"], 127.0 / float(q["q1"].float().abs().max()))
-    corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
-                               logit_scale=wl.logit_scale, act=wl.act, borrow=True)
+    decomposed = args.gate == "decomposed"
+    if decomposed:
+        import synth
+        user_mlp, item_mlp, cross_mlp = synth.make_decomposed_gate_weights(wl, dev)
+        corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], *cross_mlp, k_u=wl.k_u, logit_scale=wl.logit_scale,
+                                   act=wl.act, borrow=True, user_mlp=user_mlp, item_mlp=item_mlp)
+    else:
+        corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                                   logit_scale=wl.logit_scale, act=wl.act, borrow=True)
     log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
     n_sub = min(wl.N, 2_000_000)
     items["gx_sub"] = items["gx"][:n_sub].clone()
@@ -214,7 +224,7 @@ def main():
     scan_bytes = wl.N * wl.d1 * (1 if int8 else (4 if wl.stage1_dtype == "f32" else 2))
     achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
     mol_ms, mol_n = prof["mol_score"]
-    gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + wl.H * 2 + 4 + 4)
+    gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + (wl.P * 4 if decomposed else wl.H * 2) + 4 + 4)
     mol_flops = B * Kp * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
 
     traffic = None
@@ -238,7 +248,7 @@ def main():
         "dtype": "int8 stage 1 (int32 scores) + bf16 MoL" if int8 else ("bf16" if wl.stage1_dtype != "f32" else "f32"),
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, K'={Kp}, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}, "
-                               f"h-indexer mode {args.mode}, lambda={lam}" + (", INT8 stage 1" if int8 else "")},
+                               f"h-indexer mode {args.mode}, lambda={lam}" + (", INT8 stage 1" if int8 else "") + (", decomposed gate (Algorithm 1)" if decomposed else "")},
         "roofline": {"kernel": "k_stage1_scan (corpus scan + threshold filter)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_unit": "bytes per launch (rocprofv3 --pmc, calibrated)",
                      "algorithmic_bytes": scan_bytes,
@@ -259,7 +269,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not decomposed:
         log("timing the CPU oracle on a slice of the workload ...")
         result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, n_sub, 4096)
     print(json.dumps(result), flush=True)

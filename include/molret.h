@@ -42,6 +42,7 @@ typedef enum {
 
 enum { MOL_F32 = 0, MOL_BF16 = 1, MOL_INT8 = 2 }; /* stage1_dtype */
 enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
+enum { MOL_GATE_CONCAT = 0, MOL_GATE_DECOMPOSED = 1 }; /* gate_form */
 
 /* pack flags */
 #define MOL_PACK_BORROW_STAGE1 1u /* keep the caller's stage-1 table (no copy); it must outlive the handle */
@@ -75,6 +76,25 @@ typedef struct {
   const void *W2;  /* device, bf16 [P, H] */
   const float *b2; /* device, f32 [P], or NULL for zeros */
   uint32_t flags;  /* MOL_PACK_* */
+  /*
+   * gate_form = MOL_GATE_DECOMPOSED selects Algorithm 1's decomposedGating with the choices of Section 3.4 instead of
+   * the concatenated MLP above:
+   *   uw = Wu2 * act(Wu1 * user_gate + bu1) + bu2      (userWeightFn, once per query)
+   *   xw = Wx2 * act(Wx1 * item_gate + bx1) + bx2      (itemWeightFn, cached per item by mol_corpus_pack as f32 [N, P])
+   *   cw = W2  * act(W1  * cl        + b1 ) + b2       (crossWeightFn; W1 is then bf16 [H, P])
+   *   pi = softmax_P( SiLU( uw * xw + cw ) ),   phi = sum_p pi_p * cl_p
+   * All second layers have P outputs; 16 <= d_hu, d_hx <= 1024.  Zero-initialise the struct to get MOL_GATE_CONCAT.
+   */
+  int32_t gate_form;
+  int32_t d_hu, d_hx; /* hidden widths of the user and item weight MLPs */
+  const void *Wu1;  /* device, bf16 [d_hu, d_gu] */
+  const float *bu1; /* device, f32 [d_hu] or NULL */
+  const void *Wu2;  /* device, bf16 [P, d_hu] */
+  const float *bu2; /* device, f32 [P] or NULL */
+  const void *Wx1;  /* device, bf16 [d_hx, d_gx] */
+  const float *bx1; /* device, f32 [d_hx] or NULL */
+  const void *Wx2;  /* device, bf16 [P, d_hx] */
+  const float *bx2; /* device, f32 [P] or NULL */
 } mol_config_t;
 
 /*

@@ -40,6 +40,9 @@ class _Config(C.Structure):
         ("act", C.c_int32), ("logit_scale", C.c_float),
         ("W1", C.c_void_p), ("b1", C.c_void_p), ("W2", C.c_void_p), ("b2", C.c_void_p),
         ("flags", C.c_uint32),
+        ("gate_form", C.c_int32), ("d_hu", C.c_int32), ("d_hx", C.c_int32),
+        ("Wu1", C.c_void_p), ("bu1", C.c_void_p), ("Wu2", C.c_void_p), ("bu2", C.c_void_p),
+        ("Wx1", C.c_void_p), ("bx1", C.c_void_p), ("Wx2", C.c_void_p), ("bx2", C.c_void_p),
     ]
 
 
@@ -132,8 +135,14 @@ class Corpus:
 
 def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tensor, item_gate: torch.Tensor,
                     W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
-                    k_u: int, logit_scale: float = 1.0, act: str = "relu", borrow: bool = False) -> Corpus:
+                    k_u: int, logit_scale: float = 1.0, act: str = "relu", borrow: bool = False,
+                    user_mlp=None, item_mlp=None) -> Corpus:
+    """user_mlp / item_mlp = (Wa bf16 [d_h, d_in], ba f32 [d_h] or None, Wb bf16 [P, d_h], bb f32 [P] or None) select
+    Algorithm 1's decomposed gate; W1 [H, P], b1, W2 [P, H], b2 are then the cross MLP."""
     lib = load_library()
+    decomposed = user_mlp is not None or item_mlp is not None
+    if decomposed and (user_mlp is None or item_mlp is None):
+        raise ValueError("the decomposed gate needs both user_mlp and item_mlp")
     N, k_x, d_p = item_embs.shape
     _dev(item_embs, torch.bfloat16, "item_embs")
     _dev(item_gate, torch.bfloat16, "item_gate")
@@ -145,10 +154,29 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
         _dev(b2, torch.float32, "b2")
     P, H = W2.shape
     d_gx = item_gate.shape[1]
-    d_gu = W1.shape[1] - P - d_gx
+    if decomposed:
+        for name, mlp, d_in in (("user_mlp", user_mlp, None), ("item_mlp", item_mlp, d_gx)):
+            Wa, ba, Wb, bb = mlp
+            _dev(Wa, torch.bfloat16, name + " Wa")
+            _dev(Wb, torch.bfloat16, name + " Wb")
+            for bias in (ba, bb):
+                if bias is not None:
+                    _dev(bias, torch.float32, name + " bias")
+            if Wb.shape != (P, Wa.shape[0]) or (d_in is not None and Wa.shape[1] != d_in):
+                raise ValueError(f"inconsistent {name} shapes")
+        d_gu = user_mlp[0].shape[1]
+        if W1.shape != (H, P):
+            raise ValueError("decomposed gate: W1 must be [H, P]")
+    else:
+        d_gu = W1.shape[1] - P - d_gx
     if P != k_u * k_x or W1.shape[0] != H or d_gu < 1 or item_gate.shape[0] != N:
         raise ValueError("inconsistent model shapes")
     cfg = _Config()
+    if decomposed:
+        cfg.gate_form = 1
+        cfg.d_hu, cfg.d_hx = user_mlp[0].shape[0], item_mlp[0].shape[0]
+        cfg.Wu1, cfg.bu1, cfg.Wu2, cfg.bu2 = (_ptr(t) for t in user_mlp)
+        cfg.Wx1, cfg.bx1, cfg.Wx2, cfg.bx2 = (_ptr(t) for t in item_mlp)
     cfg.N = N
     if stage1_items is not None:
         if stage1_items.dtype not in (torch.float32, torch.bfloat16, torch.int8):

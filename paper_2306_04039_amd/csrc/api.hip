@@ -116,8 +116,13 @@ extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp,
   return p0.total > p1.total ? p0.total : p1.total;
 }
 
+// U [B, H] followed by UW [B, P] (the per-query inputs of the scoring kernel)
+static size_t mol_user_bytes(const mol_corpus_t *c, int B) {
+  return align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256);
+}
+
 static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, int k, size_t *off_scores, size_t *off_topk) {
-  size_t off = align_up((size_t)B * c->H * 4, 256);
+  size_t off = mol_user_bytes(c, B);
   if (off_scores) *off_scores = off;
   off = align_up(off + (size_t)B * row * 4, 256);
   if (off_topk) *off_topk = off;
@@ -171,14 +176,15 @@ extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, 
   mol_status_t rc = mol_common_checks(c, user_embs, user_gate, B, cand_idx, Kp);
   if (rc != MOL_OK) return rc;
   if (!scores) return mol_fail(MOL_EINVAL, "scores is NULL");
-  const size_t need = align_up((size_t)B * c->H * 4, 256);
+  const size_t need = mol_user_bytes(c, B);
   rc = check_ws(workspace, workspace_bytes, need);
   if (rc != MOL_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *U = static_cast<float *>(workspace);
-  rc = launch_user_gate(c, user_gate, B, U, st);
+  float *UW = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)B * c->H * 4, 256));
+  rc = launch_user_gate(c, user_gate, B, U, UW, st);
   if (rc != MOL_OK) return rc;
-  return launch_mol_score(c, user_embs, U, B, cand_idx, Kp, scores, st);
+  return launch_mol_score(c, user_embs, U, UW, B, cand_idx, Kp, scores, st);
 }
 
 extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
@@ -195,10 +201,11 @@ extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, c
   if (rc != MOL_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   float *U = static_cast<float *>(workspace);
+  float *UW = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)B * c->H * 4, 256));
   float *scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_scores);
-  rc = launch_user_gate(c, user_gate, B, U, st);
+  rc = launch_user_gate(c, user_gate, B, U, UW, st);
   if (rc != MOL_OK) return rc;
-  rc = launch_mol_score(c, user_embs, U, B, cand_idx, row, scores, st);
+  rc = launch_mol_score(c, user_embs, U, UW, B, cand_idx, row, scores, st);
   if (rc != MOL_OK) return rc;
   return launch_final_topk(scores, cand_idx, B, row, k, out_idx, out_score, static_cast<char *>(workspace) + off_topk, st);
 }

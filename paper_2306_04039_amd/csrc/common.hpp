@@ -89,6 +89,11 @@ struct mol_corpus {
   void *w1u;            // bf16 [H, d_gu] row-major (user part of layer 1)
   float *b2;            // f32 [32*ceil(P/32)] (padded with zeros)
   bool own_stage1, own_embs;
+  // decomposed gate (Algorithm 1): cached item weights and the user-side MLP
+  int32_t gate_form, d_hu;
+  float *xw;            // f32 [N, P]
+  void *wu1, *wu2;      // bf16 [d_hu, d_gu], bf16 [P, d_hu]
+  float *bu1, *bu2, *b1c;  // f32 [d_hu], f32 [P], f32 [H] (zeros when the caller gave none)
 };
 
 // error plumbing (api.hip)
@@ -132,8 +137,9 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
 mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, const void *w1x_rowmajor,
                                     const float *b1, hipStream_t st);
 // mol.hip
-mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, hipStream_t st);
-mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
+// U [B, H] and (decomposed gate) UW [B, P]: the per-query inputs of the scoring kernel
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, hipStream_t st);
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
                               const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st);
 // select.hip
 size_t final_topk_workspace_bytes(int B, int64_t Kp, int k);

@@ -28,7 +28,9 @@ struct MolArgs {
   const char *w2_frag;   // bf16 fragments
   const float *b2;       // f32 [32*PT]
   const char *F;         // bf16 [B, K_U, D_P]
-  const float *U;        // f32 [B, H]
+  const float *U;        // f32 [B, H]   per-query additive term of layer 1 (user part; for the decomposed gate just b1)
+  const float *xw;       // decomposed gate: f32 [N, P] cached item weights
+  const float *UW;       // decomposed gate: f32 [B, P] user weights
   const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
   float *scores;         // [B, Kp]
   int64_t Kp;            // row length of cand / scores
@@ -51,7 +53,7 @@ struct MolShape {
   static constexpr int CLS = P + 4;          // LDS row stride of the logit tile (floats)
   static constexpr int W1B = MT * S1 * 1024; // bytes
   static constexpr int W2B = PT * S2 * 1024;
-  static constexpr int WAVE_FLOATS = 32 * CLS + H;
+  static constexpr int WAVE_FLOATS = 32 * CLS + H + 32 * PT;  // logit tile, U[b], user weights (decomposed gate)
   static constexpr size_t LDS = W1B + W2B + PT * 32 * 4 + 4 * WAVE_FLOATS * 4;
 };
 
@@ -71,7 +73,10 @@ __device__ __forceinline__ float act_fn(float x, int act) {
 #ifndef MOL_PF_XI
 #define MOL_PF_XI 0    // also start the next tile's cached item-gate loads early
 #endif
-template <int K_U, int K_X, int D_P, int H, bool EXH>
+// FORM = 0: the gate is one 2-layer MLP on [cl | user feature | item feature] (first layer split into a cross part on the
+//           matrix cores, U[b] and the cached Xi[n]).
+// FORM = 1: Algorithm 1's decomposedGating: z = SiLU(uw[b] * xw[n] + crossMLP(cl)), uw per query, xw cached per item.
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM>
 __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
   constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
@@ -83,6 +88,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   const int wv = threadIdx.x >> 6;
   float *cl = b2s + PT * 32 + wv * S::WAVE_FLOATS;  // [32][CLS]
   float *Us = cl + 32 * CLS;                        // [H]
+  float *UWs = Us + H;                              // [32 * PT] (FORM 1)
 
   // stage the weight fragments once per workgroup
   for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
@@ -104,7 +110,8 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   uint4 Ff[SA];
   constexpr int PD = RT < 8 ? RT : 8;
   uint4 A[PD][SA];
-  uint2 xi[MT][4];
+  uint2 xi[MT][4];      // FORM 0: cached item half of layer 1 (bf16 x 4)
+  float4 xwv[PT][4];    // FORM 1: cached item weights of this lane's components
   int idx = -1, idxc = 0;
   bool ok = false;
   const int64_t n_qch = EXH ? (a.B + MOL_QCHUNK - 1) / MOL_QCHUNK : 1;
@@ -154,15 +161,27 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
       for (int s = 0; s < SA; ++s)
         Ff[s] = (r16 < K_U) ? ld16(a.F + ((size_t)(b * K_U + r16) * D_P + 32 * s + 8 * g) * 2) : make_uint4(0, 0, 0, 0);
       for (int i = lane; i < H; i += 64) Us[i] = a.U[(size_t)b * H + i];
+      if constexpr (FORM == 1)
+        for (int i = lane; i < 32 * PT; i += 64) UWs[i] = i < P ? a.UW[(size_t)b * P + i] : 0.f;
     }
 
     // item half of layer 1 for this lane's candidate: hidden units 32*mt + 8*q + 4*h + {0..3}
     auto load_xi = [&](int item) {
-      const char *xp = a.xi + ((size_t)item * H + 4 * h) * 2;
+      if constexpr (FORM == 0) {
+        const char *xp = a.xi + ((size_t)item * H + 4 * h) * 2;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) xi[mt][q] = *reinterpret_cast<const uint2 *>(xp + (32 * mt + 8 * q) * 2);
+          for (int q = 0; q < 4; ++q) xi[mt][q] = *reinterpret_cast<const uint2 *>(xp + (32 * mt + 8 * q) * 2);
+      } else {
+        const float *xp = a.xw + (size_t)item * P + 4 * h;  // components 32*pt + 8*q + 4*h + {0..3}
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            xwv[pt][q] = (32 * pt + 8 * q < P) ? *reinterpret_cast<const float4 *>(xp + 32 * pt + 8 * q)
+                                               : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     };
     if (new_items && !(primed && MOL_PF_XI)) load_xi(idxc);
 
@@ -247,11 +266,18 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
         for (int t = 0; t < 2; ++t) {
           const int q = 2 * qq + t;
           const float4 u4 = *reinterpret_cast<const float4 *>(&Us[32 * mt + 8 * q + 4 * h]);
-          const uint2 x = xi[mt][q];
-          hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x + bf16_bits_to_f32(x.x & 0xffffu), a.act);
-          hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y + bf16_bits_to_f32(x.x >> 16), a.act);
-          hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + bf16_bits_to_f32(x.y & 0xffffu), a.act);
-          hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + bf16_bits_to_f32(x.y >> 16), a.act);
+          if constexpr (FORM == 0) {
+            const uint2 x = xi[mt][q];
+            hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x + bf16_bits_to_f32(x.x & 0xffffu), a.act);
+            hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y + bf16_bits_to_f32(x.x >> 16), a.act);
+            hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + bf16_bits_to_f32(x.y & 0xffffu), a.act);
+            hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + bf16_bits_to_f32(x.y >> 16), a.act);
+          } else {  // the cross MLP sees the logits only; u4 carries its bias
+            hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x, a.act);
+            hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y, a.act);
+            hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z, a.act);
+            hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w, a.act);
+          }
         }
         uint4 bh, bl;
         split_bf16x2(hid[0], hid[1], bh.x, bl.x);
@@ -282,6 +308,14 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
           acc2[pt][4 * q + 1] += b4.y;
           acc2[pt][4 * q + 2] += b4.z;
           acc2[pt][4 * q + 3] += b4.w;
+          if constexpr (FORM == 1) {  // combineFn: uw * xw + cw, then SiLU (Section 3.4)
+            const float4 u4 = *reinterpret_cast<const float4 *>(&UWs[32 * pt + 8 * q + 4 * h]);
+            const float4 x4 = xwv[pt][q];
+            acc2[pt][4 * q + 0] = act_fn(fmaf(u4.x, x4.x, acc2[pt][4 * q + 0]), MOL_ACT_SILU);
+            acc2[pt][4 * q + 1] = act_fn(fmaf(u4.y, x4.y, acc2[pt][4 * q + 1]), MOL_ACT_SILU);
+            acc2[pt][4 * q + 2] = act_fn(fmaf(u4.z, x4.z, acc2[pt][4 * q + 2]), MOL_ACT_SILU);
+            acc2[pt][4 * q + 3] = act_fn(fmaf(u4.w, x4.w, acc2[pt][4 * q + 3]), MOL_ACT_SILU);
+          }
 #pragma unroll
           for (int i = 0; i < 4; ++i) m = fmaxf(m, acc2[pt][4 * q + i]);
         }
@@ -337,10 +371,33 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
   U[i] = acc;
 }
 
-template <int K_U, int K_X, int D_P, int H, bool EXH>
+// Decomposed gate, per query (userWeightFn of Algorithm 1): UW[b, :] = Wu2 * act(Wu1 * gu[b] + bu1) + bu2, and the
+// bias of the cross MLP's first layer broadcast into U[b, :] (the scoring kernel adds U[b] to layer 1).
+// One workgroup per query; the hidden units pass through LDS.
+__global__ __launch_bounds__(256) void k_user_weights(const uint16_t *wu1, const float *bu1, const uint16_t *wu2,
+                                                      const float *bu2, const float *b1c, const uint16_t *gu, float *UW,
+                                                      float *U, int P, int H, int d_gu, int d_hu, int act) {
+  __shared__ float hid[1024];
+  const int b = blockIdx.x;
+  for (int i = threadIdx.x; i < d_hu; i += 256) {
+    float acc = bu1[i];
+    for (int j = 0; j < d_gu; ++j)
+      acc = fmaf(bf16_bits_to_f32(wu1[(size_t)i * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+    hid[i] = act_fn(acc, act);
+  }
+  __syncthreads();
+  for (int p = threadIdx.x; p < P; p += 256) {
+    float acc = bu2[p];
+    for (int i = 0; i < d_hu; ++i) acc = fmaf(bf16_bits_to_f32(wu2[(size_t)p * d_hu + i]), hid[i], acc);
+    UW[(size_t)b * P + p] = acc;
+  }
+  for (int h = threadIdx.x; h < H; h += 256) U[(size_t)b * H + h] = b1c[h];
+}
+
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM>
 mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
-  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH>;
+  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM>;
   static bool configured = false;
   static int per_sm = 1, sm_count = 0;
   if (!configured) {
@@ -366,9 +423,16 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
 
 }  // namespace
 
-mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, hipStream_t st) {
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, hipStream_t st) {
   const int n = B * c->H;
   ProfScope ps(MOL_PROF_USER_GATE, st);
+  if (c->gate_form == MOL_GATE_DECOMPOSED) {
+    hipLaunchKernelGGL(k_user_weights, dim3(B), dim3(256), 0, st, static_cast<const uint16_t *>(c->wu1), c->bu1,
+                       static_cast<const uint16_t *>(c->wu2), c->bu2, c->b1c, static_cast<const uint16_t *>(user_gate), UW,
+                       U, c->P, c->H, c->d_gu, c->d_hu, c->act);
+    HIP_TRY(hipGetLastError());
+    return MOL_OK;
+  }
   hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
                      static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu);
   HIP_TRY(hipGetLastError());
@@ -394,7 +458,14 @@ bool mol_shape_supported(int k_u, int k_x, int d_p, int H) {
   return false;
 }
 
-mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, int B,
+template <int K_U, int K_X, int D_P, int H>
+static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, hipStream_t st) {
+  if (form == 0)
+    return exhaustive ? launch_shape<K_U, K_X, D_P, H, true, 0>(a, st) : launch_shape<K_U, K_X, D_P, H, false, 0>(a, st);
+  return exhaustive ? launch_shape<K_U, K_X, D_P, H, true, 1>(a, st) : launch_shape<K_U, K_X, D_P, H, false, 1>(a, st);
+}
+
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
                               const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st) {
   MolArgs a;
   a.embs = static_cast<const char *>(c->embs);
@@ -404,6 +475,8 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.b2 = c->b2;
   a.F = static_cast<const char *>(user_embs);
   a.U = U;
+  a.xw = c->xw;
+  a.UW = UW;
   a.cand = cand_idx;
   a.scores = scores;
   a.Kp = cand_idx ? Kp : c->N;
@@ -412,8 +485,7 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.act = c->act;
   a.logit_scale = c->logit_scale;
 #define X(KU, KX, DP, HH) \
-  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH)                                   \
-    return cand_idx ? launch_shape<KU, KX, DP, HH, false>(a, st) : launch_shape<KU, KX, DP, HH, true>(a, st);
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_variant<KU, KX, DP, HH>(a, cand_idx == nullptr, c->gate_form, st);
   MOL_SHAPES(X)
 #undef X
   return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", c->k_u, c->k_x, c->d_p, c->H);

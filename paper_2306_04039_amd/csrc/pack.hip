@@ -94,7 +94,66 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
   }
 }
 
+// Decomposed gate: xw[n, :] = Wx2 * act(Wx1 * gx[n] + bx1) + bx2 (itemWeightFn of Algorithm 1, the cachable item-side
+// gating weights), f32 [N, P].  A workgroup takes 32 items at a time: features and hidden units live in LDS, a
+// wavefront's lanes share a weight row and differ in the item, results leave through LDS in whole rows.
+__global__ __launch_bounds__(256) void k_item_weights(const uint16_t *gx, const uint16_t *Wx1, const float *bx1,
+                                                      const uint16_t *Wx2, const float *bx2, float *xw, int64_t N,
+                                                      int d_gx, int d_hx, int P, int act) {
+  extern __shared__ float lds_iw[];
+  const int sg = d_gx + 1, sh = d_hx + 1, sp = P + 1;
+  float *gxs = lds_iw;               // [32][sg], reused as out [32][sp] (P <= 128, d_gx >= 16: see the launcher)
+  float *hid = lds_iw + 32 * (sg > sp ? sg : sp);  // [32][sh]
+  const int64_t nblk = (N + 31) / 32;
+  for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+    const int64_t n0 = blk * 32;
+    const int cnt = (int)((N - n0) < 32 ? (N - n0) : 32);
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * d_gx; i += 256) {
+      const int it = i / d_gx, j = i % d_gx;
+      gxs[it * sg + j] = it < cnt ? bf16_bits_to_f32(gx[(size_t)(n0 + it) * d_gx + j]) : 0.f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * d_hx; i += 256) {
+      const int it = i & 31, u = i >> 5;
+      float acc = bx1 ? bx1[u] : 0.f;
+      const uint16_t *w = Wx1 + (size_t)u * d_gx;
+      for (int j = 0; j < d_gx; ++j) acc = fmaf(bf16_bits_to_f32(w[j]), gxs[it * sg + j], acc);
+      hid[it * sh + u] = act == MOL_ACT_RELU ? fmaxf(acc, 0.f) : acc / (1.f + __expf(-acc));
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 32 * P; i += 256) {
+      const int it = i & 31, p = i >> 5;
+      float acc = bx2 ? bx2[p] : 0.f;
+      const uint16_t *w = Wx2 + (size_t)p * d_hx;
+      for (int j = 0; j < d_hx; ++j) acc = fmaf(bf16_bits_to_f32(w[j]), hid[it * sh + j], acc);
+      gxs[it * sp + p] = acc;  // the features are no longer needed
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < cnt * P; i += 256) xw[(size_t)n0 * P + i] = gxs[(i / P) * sp + (i % P)];
+  }
+}
+
 }  // namespace
+
+mol_status_t launch_item_weights(const mol_corpus *c, const mol_config_t *cfg, const void *item_gate, hipStream_t st) {
+  int dev = 0, sms = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&sms, hipDeviceAttributeMultiprocessorCount, dev));
+  const int sg = c->d_gx + 1, sh = cfg->d_hx + 1, sp = c->P + 1;
+  const size_t lds = ((size_t)32 * (sg > sp ? sg : sp) + (size_t)32 * sh) * 4;
+  if (lds > 160 * 1024) return mol_fail(MOL_EUNSUPPORTED, "d_hx=%d is too wide for the item-weight kernel", cfg->d_hx);
+  if (lds > 48 * 1024)
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k_item_weights), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  int64_t grid = (int64_t)sms * 8;
+  const int64_t need = (c->N + 31) / 32;
+  if (grid > need) grid = need;
+  hipLaunchKernelGGL(k_item_weights, dim3((unsigned)grid), dim3(256), lds, st, static_cast<const uint16_t *>(item_gate),
+                     static_cast<const uint16_t *>(cfg->Wx1), cfg->bx1, static_cast<const uint16_t *>(cfg->Wx2), cfg->bx2,
+                     c->xw, c->N, c->d_gx, cfg->d_hx, c->P, c->act);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
 
 mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, const void *w1x, const float *b1,
                                     hipStream_t st) {
@@ -145,6 +204,14 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     case 16: case 32: case 64: case 96: case 128: case 256: break;
     default: return mol_fail(MOL_EUNSUPPORTED, "d_gx=%d: supported widths are 16, 32, 64, 96, 128, 256", cfg->d_gx);
   }
+  const bool decomposed = cfg->gate_form == MOL_GATE_DECOMPOSED;
+  if (cfg->gate_form != MOL_GATE_CONCAT && !decomposed) return mol_fail(MOL_EINVAL, "bad gate_form");
+  if (decomposed) {
+    if (!cfg->Wu1 || !cfg->Wu2 || !cfg->Wx1 || !cfg->Wx2)
+      return mol_fail(MOL_EINVAL, "the decomposed gate needs Wu1, Wu2, Wx1 and Wx2");
+    if (cfg->d_hu < 16 || cfg->d_hu > 1024 || cfg->d_hx < 16 || cfg->d_hx > 1024)
+      return mol_fail(MOL_EINVAL, "d_hu=%d, d_hx=%d must be in [16, 1024]", cfg->d_hu, cfg->d_hx);
+  }
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   mol_corpus *c = static_cast<mol_corpus *>(calloc(1, sizeof(mol_corpus)));
@@ -162,12 +229,16 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   c->act = cfg->act;
   c->logit_scale = cfg->logit_scale;
   c->flags = cfg->flags;
+  c->gate_form = cfg->gate_form;
+  c->d_hu = decomposed ? cfg->d_hu : 0;
   (void)hipGetDevice(&c->device);
 
   const int P = c->P, H = c->H;
   const int MT = H / 32, S1 = P / 16, PT = (P + 31) / 32, S2 = H / 16;
-  const size_t n1 = (size_t)MT * S1 * 512, n2 = (size_t)PT * S2 * 512, n3 = (size_t)H * c->d_gu,
-               n4 = (size_t)H * c->d_gx, n5 = (size_t)PT * 32;
+  // the first layer of the decomposed gate's cross MLP has the P logits as its only input: no user / item columns
+  const int w1_gu = decomposed ? 0 : c->d_gu, w1_gx = decomposed ? 0 : c->d_gx;
+  const size_t n1 = (size_t)MT * S1 * 512, n2 = (size_t)PT * S2 * 512, n3 = (size_t)H * w1_gu,
+               n4 = (size_t)H * w1_gx, n5 = (size_t)PT * 32;
   void *w1x = nullptr;
   mol_status_t rc = MOL_OK;
 #define ALLOC(ptr, bytes)                                                                                  \
@@ -177,10 +248,19 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   }
   ALLOC(c->w1c_frag, n1 * 2)
   ALLOC(c->w2_frag, n2 * 2)
-  ALLOC(c->w1u, n3 * 2)
-  ALLOC(w1x, n4 * 2)
+  ALLOC(c->w1u, (n3 ? n3 : 1) * 2)
+  ALLOC(w1x, (n4 ? n4 : 1) * 2)
   ALLOC(c->b2, n5 * 4)
-  ALLOC(c->xi, (size_t)c->N * H * 2)
+  if (decomposed) {
+    ALLOC(c->xw, (size_t)c->N * P * 4)
+    ALLOC(c->wu1, (size_t)cfg->d_hu * c->d_gu * 2)
+    ALLOC(c->wu2, (size_t)P * cfg->d_hu * 2)
+    ALLOC(c->bu1, (size_t)cfg->d_hu * 4)
+    ALLOC(c->bu2, (size_t)P * 4)
+    ALLOC(c->b1c, (size_t)H * 4)
+  } else {
+    ALLOC(c->xi, (size_t)c->N * H * 2)
+  }
   void *s1copy = nullptr, *embcopy = nullptr;
   const size_t s1_bytes = (size_t)c->N * c->d1 * (c->stage1_dtype == MOL_F32 ? 4 : (c->stage1_dtype == MOL_BF16 ? 2 : 1));
   const size_t emb_bytes = (size_t)c->N * c->k_x * c->d_p * 2;
@@ -201,12 +281,24 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     const size_t total = n1 + n2 + n3 + n4 + n5;
     hipLaunchKernelGGL(k_pack_weights, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        static_cast<const uint16_t *>(cfg->W1), static_cast<const uint16_t *>(cfg->W2), cfg->b2, P, H,
-                       c->d_gu, c->d_gx, static_cast<uint16_t *>(c->w1c_frag), static_cast<uint16_t *>(c->w2_frag),
+                       w1_gu, w1_gx, static_cast<uint16_t *>(c->w1c_frag), static_cast<uint16_t *>(c->w2_frag),
                        static_cast<uint16_t *>(c->w1u), static_cast<uint16_t *>(w1x), c->b2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "k_pack_weights: %s", hipGetErrorString(e));
   }
-  if (rc == MOL_OK) rc = launch_item_gate_cache(c, item_gate, w1x, cfg->b1, st);
+  if (rc == MOL_OK && !decomposed) rc = launch_item_gate_cache(c, item_gate, w1x, cfg->b1, st);
+  if (rc == MOL_OK && decomposed) {
+    auto copy_or_zero = [&](void *dst, const void *src, size_t bytes) -> hipError_t {
+      return src ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) : hipMemsetAsync(dst, 0, bytes, st);
+    };
+    hipError_t e = copy_or_zero(c->wu1, cfg->Wu1, (size_t)cfg->d_hu * c->d_gu * 2);
+    if (e == hipSuccess) e = copy_or_zero(c->wu2, cfg->Wu2, (size_t)P * cfg->d_hu * 2);
+    if (e == hipSuccess) e = copy_or_zero(c->bu1, cfg->bu1, (size_t)cfg->d_hu * 4);
+    if (e == hipSuccess) e = copy_or_zero(c->bu2, cfg->bu2, (size_t)P * 4);
+    if (e == hipSuccess) e = copy_or_zero(c->b1c, cfg->b1, (size_t)H * 4);
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "copy of the user-side gate weights failed: %s", hipGetErrorString(e));
+    if (rc == MOL_OK) rc = launch_item_weights(c, cfg, item_gate, st);
+  }
   if (rc == MOL_OK) {
     hipError_t e = hipStreamSynchronize(st);
     if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "pack kernels failed: %s", hipGetErrorString(e));
@@ -295,6 +387,12 @@ extern "C" mol_status_t mol_corpus_free(mol_corpus_t *c) {
   if (c->w1u) (void)hipFree(c->w1u);
   if (c->b2) (void)hipFree(c->b2);
   if (c->xi) (void)hipFree(c->xi);
+  if (c->xw) (void)hipFree(c->xw);
+  if (c->wu1) (void)hipFree(c->wu1);
+  if (c->wu2) (void)hipFree(c->wu2);
+  if (c->bu1) (void)hipFree(c->bu1);
+  if (c->bu2) (void)hipFree(c->bu2);
+  if (c->b1c) (void)hipFree(c->b1c);
   if (c->own_stage1 && c->stage1) (void)hipFree(const_cast<void *>(c->stage1));
   if (c->own_embs && c->embs) (void)hipFree(const_cast<void *>(c->embs));
   free(c);

@@ -5,6 +5,7 @@ from .generator import (  # noqa: F401
     GateWeights,
     make_centres,
     make_gate_weights,
+    make_decomposed_gate_weights,
     item_chunk,
     make_items,
     make_queries,

@@ -37,6 +37,7 @@ MASTER_SEED = 20230604
 # sub-stream tags
 _T_CENTRE_S, _T_CENTRE_M, _T_CENTRE_T = 11, 12, 13
 _T_W1, _T_W2, _T_B1, _T_B2 = 21, 22, 23, 24
+_T_DEC = 50  # decomposed gate: tags 50..61
 _T_ITEM, _T_QUERY = 31, 41
 
 
@@ -144,6 +145,27 @@ def make_gate_weights(w: Workload, device="cpu") -> GateWeights:
         return (torch.rand(n, generator=g, device=device, dtype=torch.float32) * 2 - 1) * w.bias_scale
 
     return GateWeights(W1=xavier(w.H, d_in, _T_W1), b1=bias(w.H, _T_B1), W2=xavier(w.P, w.H, _T_W2), b2=bias(w.P, _T_B2))
+
+
+def make_decomposed_gate_weights(w: Workload, device="cpu", d_hu: int = 0, d_hx: int = 0, bias_scale: float = 0.1):
+    """Weights of the three 2-layer MLPs of the decomposed gate (user, item, cross), Xavier-uniform -> bf16, small uniform
+    biases.  Returns (user_mlp, item_mlp, cross_mlp), each (Wa [d_h, d_in], ba [d_h], Wb [P, d_h], bb [P]).
+    Hidden widths default to H."""
+    d_hu, d_hx = d_hu or w.H, d_hx or w.H
+
+    def mlp(d_in, d_h, tag):
+        def xavier(rows, cols, t):
+            a = math.sqrt(6.0 / (rows + cols))
+            g = _gen(w.seed, t, 0, device)
+            return ((torch.rand(rows, cols, generator=g, device=device, dtype=torch.float32) * 2 - 1) * a).to(torch.bfloat16)
+
+        def bias(n, t):
+            g = _gen(w.seed, t, 0, device)
+            return (torch.rand(n, generator=g, device=device, dtype=torch.float32) * 2 - 1) * bias_scale
+
+        return (xavier(d_h, d_in, tag), bias(d_h, tag + 1), xavier(w.P, d_h, tag + 2), bias(w.P, tag + 3))
+
+    return mlp(w.d_gu, d_hu, _T_DEC), mlp(w.d_gx, d_hx, _T_DEC + 4), mlp(w.P, w.H, _T_DEC + 8)
 
 
 def item_chunk(w: Workload, centres: Dict[str, torch.Tensor], chunk_id: int,
