@@ -453,11 +453,14 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_thr_hist(const uint32_t *skeys
   msel_hist_pass(each, pass, prefix, mhist + ((size_t)pass * B + b) * MSEL_BINS, sh);
 }
 
-__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, float *thr,
-                                                             uint32_t *flags, uint32_t *gate) {
+// `passes` digit passes were made: 3 give the exact rank-th sampled key (Algorithm 2 as written); with 2 the threshold is
+// the lower end of the 22-bit bucket holding it, at most 2^10 ulps below -- enough where the threshold only has to let
+// at least K' items through (the exact top-K' of the survivors is taken afterwards) and one pass over the keys cheaper.
+__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, int passes,
+                                                             float *thr, uint32_t *flags, uint32_t *gate) {
   __shared__ MselShared sh;
   const int b = blockIdx.x;
-  const MselCut c = msel_cut(mhist, B, b, rank, MSEL_PASSES, sh);
+  const MselCut c = msel_cut(mhist, B, b, rank, passes, sh);
   if (threadIdx.x == 0) {
     thr[b] = c.K ? key_to_f32(c.prefix) : -INFINITY;
     flags[b] = 0;
@@ -946,12 +949,14 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     ProfScope ps(MOL_PROF_THRESHOLD, st);
     int G = 512 / B;
     G = G < 1 ? 1 : (G > 32 ? 32 : G);
-    for (int pass = 0; pass < MSEL_PASSES; ++pass) {
+    const int passes = (mode & 0xff) == MOL_HINDEXER_EXACT ? MSEL_PASSES - 1 : MSEL_PASSES;
+    for (int pass = 0; pass < passes; ++pass) {
       hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
                          mhist, B, pass);
       HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank, thr, flags, gate);
+    hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank, passes, thr, flags,
+                       gate);
     HIP_TRY(hipGetLastError());
   } else {
     hipLaunchKernelGGL(k_init_all_pass, dim3((B + 255) / 256), dim3(256), 0, st, thr, flags, gate, B);
