@@ -1,6 +1,6 @@
 // Multi-workgroup radix selection under the total order (key descending, index ascending).
 //
-// The lists handled here (sampled stage-1 scores, stage-1 survivors, MoL scores of the candidates) hold 1e5..1e6
+// The lists handled here (sampled stage-1 scores, stage-1 survivors) hold 1e5..1e6
 // entries per query: too much for one workgroup to walk several times at the latency the path needs, so every pass is
 // a grid of (slices x queries) workgroups.  Three histogram passes over fixed digits of the 32-bit key
 // (bits 31..21, 20..10, 9..0) find the exact K-th key; an emit pass writes everything above it, and the few items tied
