@@ -198,6 +198,18 @@ def gating_weights(cl: np.ndarray, gu_b: np.ndarray, gx_rows: np.ndarray, W1: np
     return e / e.sum(axis=1, keepdims=True)
 
 
+def gather_items(G_bits: np.ndarray, cand: np.ndarray) -> np.ndarray:
+    """Index select after the top-k' selection (Section 4.1.3): out[b, c] = the stored item row cand[b, c], bit for bit;
+    a negative id (padding) gives an all-zero row.  G_bits [N, ...] of any dtype."""
+    cand = np.asarray(cand, dtype=np.int64)
+    out = np.zeros(cand.shape + G_bits.shape[1:], dtype=G_bits.dtype)
+    for b in range(cand.shape[0]):
+        for c in range(cand.shape[1]):
+            if cand[b, c] >= 0:
+                out[b, c] = G_bits[cand[b, c]]
+    return out
+
+
 def _mlp2(x: np.ndarray, Wa: np.ndarray, ba: np.ndarray, Wb: np.ndarray, bb: np.ndarray, act: str) -> np.ndarray:
     """Two-layer MLP, rows of x: Wb * act(Wa * x + ba) + bb."""
     return _act(x @ Wa.T + ba, act) @ Wb.T + bb

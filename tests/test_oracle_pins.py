@@ -583,3 +583,14 @@ def test_decomposed_gate_loop_by_loop(act):
             e = [math.exp(v - m) for v in z]
             phi = sum(ei * ci for ei, ci in zip(e, cl)) / sum(e)
             assert abs(got[b, n] - phi) < 1e-12
+
+
+def test_gather_items_is_a_row_copy_with_zero_padding():
+    rng = np.random.default_rng(41)
+    G = rand_bf16_bits(rng, (20, 3, 8), 1.0)
+    cand = np.array([[3, 3, -1, 19], [0, -5, 7, 1]])
+    out = orc.gather_items(G, cand)
+    assert out.shape == (2, 4, 3, 8) and out.dtype == G.dtype
+    assert np.array_equal(out[0, 0], G[3]) and np.array_equal(out[0, 1], G[3]) and np.array_equal(out[1, 2], G[7])
+    assert not out[0, 2].any() and not out[1, 1].any()
+    assert np.array_equal(out[0, 3], G[19]) and np.array_equal(out[1, 0], G[0])
