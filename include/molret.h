@@ -171,6 +171,15 @@ mol_status_t mol_score(const mol_corpus_t *corpus, const void *user_embs, const 
                        void *stream);
 
 /*
+ * Index select (Section 4.1.3), for callers that want the candidates' embeddings themselves (mol_score / mol_topk gather
+ * inside the scoring kernel and never materialise this tensor).
+ *   cand_idx : int32 [B, Kp], negative = padding.
+ *   out_embs : out bf16 [B, Kp, k_x, d_p], 16-byte aligned: a bit-exact copy of item row cand_idx[b, c]; zeros for padding.
+ */
+mol_status_t mol_gather_items(const mol_corpus_t *corpus, const int32_t *cand_idx, int B, int Kp, void *out_embs,
+                              void *stream);
+
+/*
  * Stage 2 with the final selection (Algorithm 1 including its last line): the k best candidates per query.
  *   cand_idx / Kp as in mol_score (NULL = exhaustive MoL over the corpus).
  *   out_idx   : out int32 [B, k] item indices, best first (score desc, index asc); -1 where fewer than k exist.

@@ -20,7 +20,7 @@ _LIB = None
 EXPORTS = (
     "mol_corpus_pack", "mol_corpus_free", "hindexer_workspace_bytes", "mol_workspace_bytes",
     "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
-    "mol_profile_enable", "mol_profile_read", "mol_quantize_int8",
+    "mol_profile_enable", "mol_profile_read", "mol_quantize_int8", "mol_gather_items",
 )
 
 PROF_SLOTS = ("sample_scores", "threshold", "scan_filter", "select", "user_gate", "mol_score", "final_topk", "spare")
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.mol_profile_read.restype = i32
     lib.mol_quantize_int8.argtypes = [vp, i32, i64, C.c_float, vp, vp]
     lib.mol_quantize_int8.restype = i32
+    lib.mol_gather_items.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.mol_gather_items.restype = i32
     lib.mol_last_error.argtypes = []
     lib.mol_last_error.restype = C.c_char_p
     _LIB = lib
@@ -256,6 +258,17 @@ def hindexer_topk(corpus: Corpus, q1: torch.Tensor, Kp: int, lam: int = 0, seed:
     _check(lib.hindexer_topk(corpus.handle, _ptr(q1), B, Kp, _ptr(sample_idx), lam, seed, mode, _ptr(ci), _ptr(cs),
                              _ptr(cc), _ptr(ws), ws.numel(), _stream()))
     return ci, cs, cc
+
+
+def gather_items(corpus: Corpus, cand_idx: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """bf16 [B, Kp, k_x, d_p]: the item embeddings of the candidates (zeros for padding), Section 4.1.3."""
+    _dev(cand_idx, torch.int32, "cand_idx")
+    B, Kp = cand_idx.shape
+    if out is None:
+        out = torch.empty(B, Kp, corpus.k_x, corpus.d_p, dtype=torch.bfloat16, device=cand_idx.device)
+    _dev(out, torch.bfloat16, "out")
+    _check(load_library().mol_gather_items(corpus.handle, _ptr(cand_idx), B, Kp, _ptr(out), _stream()))
+    return out
 
 
 def mol_score(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor,

@@ -187,6 +187,14 @@ extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, 
   return launch_mol_score(c, user_embs, U, UW, B, cand_idx, Kp, scores, st);
 }
 
+extern "C" mol_status_t mol_gather_items(const mol_corpus_t *c, const int32_t *cand_idx, int B, int Kp, void *out_embs,
+                                         void *stream) {
+  if (!c || !cand_idx || !out_embs) return mol_fail(MOL_EINVAL, "mol_gather_items: NULL corpus / cand_idx / out_embs");
+  if (B < 1 || B > 1024 || Kp < 1) return mol_fail(MOL_EINVAL, "mol_gather_items: B=%d must be in [1, 1024] and Kp=%d >= 1", B, Kp);
+  if (reinterpret_cast<uintptr_t>(out_embs) & 15u) return mol_fail(MOL_EINVAL, "mol_gather_items: out_embs must be 16-byte aligned");
+  return launch_gather_items(c, cand_idx, B, Kp, out_embs, static_cast<hipStream_t>(stream));
+}
+
 extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
                                  const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score,
                                  void *workspace, size_t workspace_bytes, void *stream) {

@@ -458,6 +458,47 @@ bool mol_shape_supported(int k_u, int k_x, int d_p, int H) {
   return false;
 }
 
+// Index select (Section 4.1.3): out[b, c, :] = item row cand[b, c] (row_bytes = k_x * d_p * 2, a multiple of 64), zeros
+// for padding.  Consecutive lanes copy consecutive 16-byte pieces of a row, so every request covers whole cache lines
+// of one row; a wavefront handles rows_per_wave rows per instruction.
+__global__ __launch_bounds__(256) void k_gather_items(const char *embs, const int32_t *cand, int64_t npairs, int64_t N,
+                                                      int row_bytes, char *out) {
+  const int pieces = row_bytes / 16;                    // 16-byte pieces per row (4 .. 128)
+  const int64_t total = npairs * pieces;
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  for (int64_t base = ((int64_t)blockIdx.x * 256 + threadIdx.x); base < total; base += stride) {
+    uint4 v[4];
+    int64_t at[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      at[u] = base + (int64_t)u * gridDim.x * 256;
+      v[u] = make_uint4(0, 0, 0, 0);
+      if (at[u] < total) {
+        const int64_t pair = at[u] / pieces;
+        const int piece = (int)(at[u] % pieces);
+        const int32_t id = cand[pair];
+        if (id >= 0 && id < N) v[u] = ld16(embs + (size_t)id * row_bytes + (size_t)piece * 16);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (at[u] < total) *reinterpret_cast<uint4 *>(out + (size_t)at[u] * 16) = v[u];
+  }
+}
+
+mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, int B, int64_t Kp, void *out, hipStream_t st) {
+  const int row_bytes = c->k_x * c->d_p * 2;
+  const int64_t npairs = (int64_t)B * Kp;
+  const int64_t total = npairs * (row_bytes / 16);
+  int64_t grid = (total + 1023) / 1024;
+  if (grid > 256 * 16) grid = 256 * 16;
+  if (grid < 1) grid = 1;
+  hipLaunchKernelGGL(k_gather_items, dim3((unsigned)grid), dim3(256), 0, st, static_cast<const char *>(c->embs), cand_idx,
+                     npairs, c->N, row_bytes, static_cast<char *>(out));
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
+
 template <int K_U, int K_X, int D_P, int H>
 static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, hipStream_t st) {
   if (form == 0)

@@ -104,3 +104,26 @@ def test_final_selection_levels_with_ties_and_padding(Kp, k):
         assert np.array_equal(sc[b, :kk], scores[b][valid][want])
         assert np.all(idx[b, kk:] == -1) and np.all(np.isneginf(sc[b, kk:]))
     corpus.free()
+
+
+@pytest.mark.parametrize("shape", [dict(k_u=16, k_x=1, d_p=32, H=32, d_gu=32, d_gx=32), dict(k_u=8, k_x=8, d_p=64, H=128, d_gu=128, d_gx=128)])
+def test_gather_items_is_a_bit_exact_row_copy(shape):
+    """Index select (Section 4.1.3): rows of 64 B and of 1 KB, with padding and repeated ids."""
+    wl = synth.CONFIGS["C2"].replace(N=5000, B=4, n_clusters=8, **shape)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(5)
+    cand = torch.randint(0, wl.N, (4, 777), generator=g).to(torch.int32)
+    cand[0, ::7] = -1
+    cand[1, :] = 4999
+    cand[2, 100:] = -1
+    got = m().gather_items(corpus, cand.to(DEV))
+    torch.cuda.synchronize()
+    want = orc.gather_items(bits(items["G"]), cand.numpy())
+    assert np.array_equal(bits(got), want)
+    # timing-free sanity of the error path
+    with pytest.raises(m().MolError):
+        m().load_library()
+        from paper_2306_04039_amd import binding
+        binding._check(binding.load_library().mol_gather_items(corpus.handle, None, 4, 777, None, None))
+    corpus.free()
