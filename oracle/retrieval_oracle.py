@@ -58,11 +58,11 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
 
 
 def as_f64(a: np.ndarray) -> np.ndarray:
-    """uint16 => bf16 bit patterns; float32/float64 => widened; int8 => the integers (quantised stage-1 vectors)."""
+    """uint16 => bf16 bit patterns; float16/float32/float64 => widened; int8 => the integers (quantised stage-1 vectors)."""
     a = np.asarray(a)
     if a.dtype == np.uint16:
         return bf16_bits_to_f64(a)
-    if a.dtype in (np.float32, np.float64, np.int8):
+    if a.dtype in (np.float16, np.float32, np.float64, np.int8):
         return a.astype(np.float64)
     raise TypeError(f"unsupported input dtype {a.dtype}")
 

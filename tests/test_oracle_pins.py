@@ -594,3 +594,16 @@ def test_gather_items_is_a_row_copy_with_zero_padding():
     assert np.array_equal(out[0, 0], G[3]) and np.array_equal(out[0, 1], G[3]) and np.array_equal(out[1, 2], G[7])
     assert not out[0, 2].any() and not out[1, 1].any()
     assert np.array_equal(out[0, 3], G[19]) and np.array_equal(out[1, 0], G[0])
+
+
+def test_half_precision_inputs_decode_exactly():
+    """FP16 inference inputs (Section 4.3) reach the oracle as numpy float16: hand-decoded bit patterns."""
+    pat = np.array([0x3C00, 0x3555, 0x0001, 0xFBFF, 0x8000, 0x0400], dtype=np.uint16).view(np.float16)
+    want = [1.0, 0.333251953125, 2.0 ** -24, -65504.0, 0.0, 2.0 ** -14]
+    assert orc.as_f64(pat).tolist() == want
+    # bf16 -> fp16 is exact for the magnitudes the path uses (8 significant bits, exponents well inside half's range)
+    rng = np.random.default_rng(51)
+    b = rand_bf16_bits(rng, (500,), 1.0)
+    v = orc.bf16_bits_to_f64(b)
+    v = v[(np.abs(v) > 2.0 ** -14) & (np.abs(v) < 60000)]
+    assert np.array_equal(v.astype(np.float16).astype(np.float64), v)
