@@ -8,7 +8,8 @@
  *
  * Conventions
  *   - Every data pointer is a DEVICE pointer unless the comment says "host".  Tensors are row-major
- *     and contiguous.  bf16 tensors are raw 16-bit patterns.  Item indices are int32 (N < 2^31).
+ *     and contiguous.  bf16 tensors are raw 16-bit patterns ("bf16" below reads "fp16" for a corpus packed with
+ *     mol_dtype = MOL_F16).  Item indices are int32 (N < 2^31).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on it
  *     and return; none of them synchronises the device, except mol_corpus_pack / mol_corpus_free.
  *   - The caller owns all inputs, outputs and workspaces.  A corpus handle owns only what pack
@@ -40,7 +41,7 @@ typedef enum {
   MOL_EHIP = -5          /* a HIP runtime call failed */
 } mol_status_t;
 
-enum { MOL_F32 = 0, MOL_BF16 = 1, MOL_INT8 = 2 }; /* stage1_dtype */
+enum { MOL_F32 = 0, MOL_BF16 = 1, MOL_INT8 = 2, MOL_F16 = 3 }; /* stage1_dtype: F32, BF16 or INT8; mol_dtype: BF16 or F16 */
 enum { MOL_ACT_RELU = 0, MOL_ACT_SILU = 1 }; /* act */
 enum { MOL_GATE_CONCAT = 0, MOL_GATE_DECOMPOSED = 1 }; /* gate_form */
 
@@ -95,6 +96,12 @@ typedef struct {
   const float *bx1; /* device, f32 [d_hx] or NULL */
   const void *Wx2;  /* device, bf16 [P, d_hx] */
   const float *bx2; /* device, f32 [P] or NULL */
+  /*
+   * mol_dtype = MOL_F16: every 16-bit tensor of stage 2 (item_embs, item_gate, all weight matrices here, and user_embs /
+   * user_gate in mol_score / mol_topk, the output of mol_gather_items) is IEEE half instead of bfloat16 -- Section 4.3
+   * serves in FP16; a model trained in BF16 converts to it without rounding.  0 or MOL_BF16 = bfloat16.
+   */
+  int32_t mol_dtype;
 } mol_config_t;
 
 /*

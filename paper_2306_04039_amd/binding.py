@@ -43,6 +43,7 @@ class _Config(C.Structure):
         ("gate_form", C.c_int32), ("d_hu", C.c_int32), ("d_hx", C.c_int32),
         ("Wu1", C.c_void_p), ("bu1", C.c_void_p), ("Wu2", C.c_void_p), ("bu2", C.c_void_p),
         ("Wx1", C.c_void_p), ("bx1", C.c_void_p), ("Wx2", C.c_void_p), ("bx2", C.c_void_p),
+        ("mol_dtype", C.c_int32),
     ]
 
 
@@ -116,7 +117,8 @@ class Corpus:
     """Owns a mol_corpus_t handle (and references to borrowed tensors)."""
 
     def __init__(self, handle: int, N: int, d1: int, stage1_dtype, k_u: int, k_x: int, d_p: int, H: int, d_gu: int,
-                 keep):
+                 keep, mol_dtype=torch.bfloat16):
+        self.mol_dtype = mol_dtype
         self.handle = handle
         self.N, self.d1, self.stage1_dtype = N, d1, stage1_dtype
         self.k_u, self.k_x, self.d_p, self.H, self.d_gu = k_u, k_x, d_p, H, d_gu
@@ -146,10 +148,13 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     if decomposed and (user_mlp is None or item_mlp is None):
         raise ValueError("the decomposed gate needs both user_mlp and item_mlp")
     N, k_x, d_p = item_embs.shape
-    _dev(item_embs, torch.bfloat16, "item_embs")
-    _dev(item_gate, torch.bfloat16, "item_gate")
-    _dev(W1, torch.bfloat16, "W1")
-    _dev(W2, torch.bfloat16, "W2")
+    t16 = item_embs.dtype
+    if t16 not in (torch.bfloat16, torch.float16):
+        raise ValueError("item_embs must be bfloat16 or float16")
+    _dev(item_embs, t16, "item_embs")
+    _dev(item_gate, t16, "item_gate")
+    _dev(W1, t16, "W1")
+    _dev(W2, t16, "W2")
     if b1 is not None:
         _dev(b1, torch.float32, "b1")
     if b2 is not None:
@@ -159,8 +164,8 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     if decomposed:
         for name, mlp, d_in in (("user_mlp", user_mlp, None), ("item_mlp", item_mlp, d_gx)):
             Wa, ba, Wb, bb = mlp
-            _dev(Wa, torch.bfloat16, name + " Wa")
-            _dev(Wb, torch.bfloat16, name + " Wb")
+            _dev(Wa, t16, name + " Wa")
+            _dev(Wb, t16, name + " Wb")
             for bias in (ba, bb):
                 if bias is not None:
                     _dev(bias, torch.float32, name + " bias")
@@ -174,6 +179,7 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     if P != k_u * k_x or W1.shape[0] != H or d_gu < 1 or item_gate.shape[0] != N:
         raise ValueError("inconsistent model shapes")
     cfg = _Config()
+    cfg.mol_dtype = 3 if t16 == torch.float16 else 1
     if decomposed:
         cfg.gate_form = 1
         cfg.d_hu, cfg.d_hx = user_mlp[0].shape[0], item_mlp[0].shape[0]
@@ -202,7 +208,7 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
                                C.byref(out)))
     keep = (stage1_items, item_embs) if borrow else None
     return Corpus(out.value, N, cfg.d1, None if stage1_items is None else stage1_items.dtype, k_u, k_x, d_p, H, d_gu,
-                  keep)
+                  keep, t16)
 
 
 def quantize_int8(src: torch.Tensor, scale: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -265,8 +271,8 @@ def gather_items(corpus: Corpus, cand_idx: torch.Tensor, out: Optional[torch.Ten
     _dev(cand_idx, torch.int32, "cand_idx")
     B, Kp = cand_idx.shape
     if out is None:
-        out = torch.empty(B, Kp, corpus.k_x, corpus.d_p, dtype=torch.bfloat16, device=cand_idx.device)
-    _dev(out, torch.bfloat16, "out")
+        out = torch.empty(B, Kp, corpus.k_x, corpus.d_p, dtype=corpus.mol_dtype, device=cand_idx.device)
+    _dev(out, corpus.mol_dtype, "out")
     _check(load_library().mol_gather_items(corpus.handle, _ptr(cand_idx), B, Kp, _ptr(out), _stream()))
     return out
 
@@ -275,8 +281,8 @@ def mol_score(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor,
               cand_idx: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
               out: Optional[torch.Tensor] = None) -> torch.Tensor:
     lib = load_library()
-    _dev(user_embs, torch.bfloat16, "user_embs")
-    _dev(user_gate, torch.bfloat16, "user_gate")
+    _dev(user_embs, corpus.mol_dtype, "user_embs")
+    _dev(user_gate, corpus.mol_dtype, "user_gate")
     B = user_embs.shape[0]
     if tuple(user_embs.shape[1:]) != (corpus.k_u, corpus.d_p) or tuple(user_gate.shape) != (B, corpus.d_gu):
         raise ValueError("user tensor shapes do not match the corpus")
@@ -297,8 +303,8 @@ def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, c
              k: int, workspace: Optional[torch.Tensor] = None,
              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     lib = load_library()
-    _dev(user_embs, torch.bfloat16, "user_embs")
-    _dev(user_gate, torch.bfloat16, "user_gate")
+    _dev(user_embs, corpus.mol_dtype, "user_embs")
+    _dev(user_gate, corpus.mol_dtype, "user_gate")
     B = user_embs.shape[0]
     if tuple(user_embs.shape[1:]) != (corpus.k_u, corpus.d_p) or tuple(user_gate.shape) != (B, corpus.d_gu):
         raise ValueError("user tensor shapes do not match the corpus")

@@ -63,6 +63,42 @@ __device__ __forceinline__ void mfma_settle() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
+// ---- the 16-bit type of the MoL-side tensors: F16 = false bfloat16, true IEEE half (Section 4.3 serves in FP16) ----
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+template <bool F16>
+__device__ __forceinline__ float dec16(uint32_t bits) {  // low 16 bits -> fp32, exact
+  if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+  else return __uint_as_float(bits << 16);
+}
+__device__ __forceinline__ float dec16(uint32_t bits, bool f16) { return f16 ? dec16<true>(bits) : dec16<false>(bits); }
+template <bool F16>
+__device__ __forceinline__ uint32_t pack16x2(float lo, float hi) {  // round to nearest even
+  if constexpr (F16) {
+    f32x2v v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2v));
+  } else {
+    return pack_bf16x2(lo, hi);
+  }
+}
+// a ~= hi + lo with both parts in the 16-bit type (see split_bf16x2)
+template <bool F16>
+__device__ __forceinline__ void split16x2(float a, float b, uint32_t &hi, uint32_t &lo) {
+  hi = pack16x2<F16>(a, b);
+  lo = pack16x2<F16>(a - dec16<F16>(hi & 0xffffu), b - dec16<F16>(hi >> 16));
+}
+template <bool F16>
+__device__ __forceinline__ f32x4 mfma16_16x16x32(uint4 a, uint4 b, f32x4 c) {
+  if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(as_f16x8(a), as_f16x8(b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma16_32x32x16(uint4 a, uint4 b, f32x16 c) {
+  if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(a), as_f16x8(b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(a), as_bf16x8(b), c, 0, 0, 0);
+}
+
 __device__ __forceinline__ i32x4 as_i32x4(uint4 v) {
   i32x4 r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w};
   return r;
@@ -91,6 +127,7 @@ struct mol_corpus {
   bool own_stage1, own_embs;
   // decomposed gate (Algorithm 1): cached item weights and the user-side MLP
   int32_t gate_form, d_hu;
+  bool f16;             // the 16-bit MoL-side tensors (embeddings, gate features, weights, Xi) are IEEE half, not bfloat16
   float *xw;            // f32 [N, P]
   void *wu1, *wu2;      // bf16 [d_hu, d_gu], bf16 [P, d_hu]
   float *bu1, *bu2, *b1c;  // f32 [d_hu], f32 [P], f32 [H] (zeros when the caller gave none)

@@ -76,7 +76,8 @@ __device__ __forceinline__ float act_fn(float x, int act) {
 // FORM = 0: the gate is one 2-layer MLP on [cl | user feature | item feature] (first layer split into a cross part on the
 //           matrix cores, U[b] and the cached Xi[n]).
 // FORM = 1: Algorithm 1's decomposedGating: z = SiLU(uw[b] * xw[n] + crossMLP(cl)), uw per query, xw cached per item.
-template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM>
+// F16: the 16-bit inputs are IEEE half instead of bfloat16 (same layouts, the half-precision MFMA forms).
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16>
 __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
   constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < SA; ++s)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[rt % PD][s]), as_bf16x8(Ff[s]), acc, 0, 0, 0);
+        acc = mfma16_16x16x32<F16>(A[rt % PD][s], Ff[s], acc);
       if (rt + PD < RT) load_rows(A[rt % PD], rt + PD);
       // acc[j]: row 4*g + j of the tile = (candidate rt*CPR + (4g+j)/K_X, kx (4g+j)%K_X); column ku = r16
       if (r16 < K_U) {
@@ -239,15 +240,15 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
       const float4 lo = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h]);
       const float4 hi = *reinterpret_cast<const float4 *>(&cl[c * CLS + 16 * s + 8 * h + 4]);
       uint4 bh, bl;
-      split_bf16x2(lo.x, lo.y, bh.x, bl.x);
-      split_bf16x2(lo.z, lo.w, bh.y, bl.y);
-      split_bf16x2(hi.x, hi.y, bh.z, bl.z);
-      split_bf16x2(hi.z, hi.w, bh.w, bl.w);
+      split16x2<F16>(lo.x, lo.y, bh.x, bl.x);
+      split16x2<F16>(lo.z, lo.w, bh.y, bl.y);
+      split16x2<F16>(hi.x, hi.y, bh.z, bl.z);
+      split16x2<F16>(hi.z, hi.w, bh.w, bl.w);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const uint4 af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
-        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bl), acc1[mt], 0, 0, 0);
-        acc1[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc1[mt], 0, 0, 0);
+        acc1[mt] = mfma16_32x32x16<F16>(af, bl, acc1[mt]);
+        acc1[mt] = mfma16_32x32x16<F16>(af, bh, acc1[mt]);
       }
     }
 
@@ -268,10 +269,10 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
           const float4 u4 = *reinterpret_cast<const float4 *>(&Us[32 * mt + 8 * q + 4 * h]);
           if constexpr (FORM == 0) {
             const uint2 x = xi[mt][q];
-            hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x + bf16_bits_to_f32(x.x & 0xffffu), a.act);
-            hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y + bf16_bits_to_f32(x.x >> 16), a.act);
-            hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + bf16_bits_to_f32(x.y & 0xffffu), a.act);
-            hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + bf16_bits_to_f32(x.y >> 16), a.act);
+            hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x + dec16<F16>(x.x & 0xffffu), a.act);
+            hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y + dec16<F16>(x.x >> 16), a.act);
+            hid[4 * t + 2] = act_fn(acc1[mt][4 * q + 2] + u4.z + dec16<F16>(x.y & 0xffffu), a.act);
+            hid[4 * t + 3] = act_fn(acc1[mt][4 * q + 3] + u4.w + dec16<F16>(x.y >> 16), a.act);
           } else {  // the cross MLP sees the logits only; u4 carries its bias
             hid[4 * t + 0] = act_fn(acc1[mt][4 * q + 0] + u4.x, a.act);
             hid[4 * t + 1] = act_fn(acc1[mt][4 * q + 1] + u4.y, a.act);
@@ -280,15 +281,15 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
           }
         }
         uint4 bh, bl;
-        split_bf16x2(hid[0], hid[1], bh.x, bl.x);
-        split_bf16x2(hid[2], hid[3], bh.y, bl.y);
-        split_bf16x2(hid[4], hid[5], bh.z, bl.z);
-        split_bf16x2(hid[6], hid[7], bh.w, bl.w);
+        split16x2<F16>(hid[0], hid[1], bh.x, bl.x);
+        split16x2<F16>(hid[2], hid[3], bh.y, bl.y);
+        split16x2<F16>(hid[4], hid[5], bh.z, bl.z);
+        split16x2<F16>(hid[6], hid[7], bh.w, bl.w);
 #pragma unroll
         for (int pt = 0; pt < PT; ++pt) {
           const uint4 af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
-          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bl), acc2[pt], 0, 0, 0);
-          acc2[pt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bh), acc2[pt], 0, 0, 0);
+          acc2[pt] = mfma16_32x32x16<F16>(af, bl, acc2[pt]);
+          acc2[pt] = mfma16_32x32x16<F16>(af, bh, acc2[pt]);
         }
       }
     }
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 
 // U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
 // One thread per output, 8 bf16 of each operand per load when the rows allow it.
-__global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, int B, int H, int d_gu) {
+__global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, int B, int H, int d_gu, bool f16) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * H) return;
   const int b = i / H, hh = i % H;
@@ -355,7 +356,7 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
   float acc = 0.f;
   if (d_gu % 8 != 0) {  // rows are not 16-byte aligned: element by element
     for (int j = 0; j < d_gu; ++j)
-      acc = fmaf(bf16_bits_to_f32(w1u[(size_t)hh * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+      acc = fmaf(dec16(w1u[(size_t)hh * d_gu + j], f16), dec16(gu[(size_t)b * d_gu + j], f16), acc);
     U[i] = acc;
     return;
   }
@@ -364,8 +365,8 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
     const uint32_t wv[4] = {w.x, w.y, w.z, w.w}, gv[4] = {g.x, g.y, g.z, g.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      acc = fmaf(bf16_bits_to_f32(wv[e] & 0xffffu), bf16_bits_to_f32(gv[e] & 0xffffu), acc);
-      acc = fmaf(bf16_bits_to_f32(wv[e] >> 16), bf16_bits_to_f32(gv[e] >> 16), acc);
+      acc = fmaf(dec16(wv[e] & 0xffffu, f16), dec16(gv[e] & 0xffffu, f16), acc);
+      acc = fmaf(dec16(wv[e] >> 16, f16), dec16(gv[e] >> 16, f16), acc);
     }
   }
   U[i] = acc;
@@ -376,28 +377,28 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
 // One workgroup per query; the hidden units pass through LDS.
 __global__ __launch_bounds__(256) void k_user_weights(const uint16_t *wu1, const float *bu1, const uint16_t *wu2,
                                                       const float *bu2, const float *b1c, const uint16_t *gu, float *UW,
-                                                      float *U, int P, int H, int d_gu, int d_hu, int act) {
+                                                      float *U, int P, int H, int d_gu, int d_hu, int act, bool f16) {
   __shared__ float hid[1024];
   const int b = blockIdx.x;
   for (int i = threadIdx.x; i < d_hu; i += 256) {
     float acc = bu1[i];
     for (int j = 0; j < d_gu; ++j)
-      acc = fmaf(bf16_bits_to_f32(wu1[(size_t)i * d_gu + j]), bf16_bits_to_f32(gu[(size_t)b * d_gu + j]), acc);
+      acc = fmaf(dec16(wu1[(size_t)i * d_gu + j], f16), dec16(gu[(size_t)b * d_gu + j], f16), acc);
     hid[i] = act_fn(acc, act);
   }
   __syncthreads();
   for (int p = threadIdx.x; p < P; p += 256) {
     float acc = bu2[p];
-    for (int i = 0; i < d_hu; ++i) acc = fmaf(bf16_bits_to_f32(wu2[(size_t)p * d_hu + i]), hid[i], acc);
+    for (int i = 0; i < d_hu; ++i) acc = fmaf(dec16(wu2[(size_t)p * d_hu + i], f16), hid[i], acc);
     UW[(size_t)b * P + p] = acc;
   }
   for (int h = threadIdx.x; h < H; h += 256) U[(size_t)b * H + h] = b1c[h];
 }
 
-template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM>
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16>
 mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
-  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM>;
+  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM, F16>;
   static bool configured = false;
   static int per_sm = 1, sm_count = 0;
   if (!configured) {
@@ -429,12 +430,12 @@ mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B,
   if (c->gate_form == MOL_GATE_DECOMPOSED) {
     hipLaunchKernelGGL(k_user_weights, dim3(B), dim3(256), 0, st, static_cast<const uint16_t *>(c->wu1), c->bu1,
                        static_cast<const uint16_t *>(c->wu2), c->bu2, c->b1c, static_cast<const uint16_t *>(user_gate), UW,
-                       U, c->P, c->H, c->d_gu, c->d_hu, c->act);
+                       U, c->P, c->H, c->d_gu, c->d_hu, c->act, c->f16);
     HIP_TRY(hipGetLastError());
     return MOL_OK;
   }
   hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
-                     static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu);
+                     static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu, c->f16);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
@@ -500,10 +501,15 @@ mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, i
 }
 
 template <int K_U, int K_X, int D_P, int H>
-static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, hipStream_t st) {
-  if (form == 0)
-    return exhaustive ? launch_shape<K_U, K_X, D_P, H, true, 0>(a, st) : launch_shape<K_U, K_X, D_P, H, false, 0>(a, st);
-  return exhaustive ? launch_shape<K_U, K_X, D_P, H, true, 1>(a, st) : launch_shape<K_U, K_X, D_P, H, false, 1>(a, st);
+static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, bool f16, hipStream_t st) {
+#define V(E, F, T) launch_shape<K_U, K_X, D_P, H, E, F, T>(a, st)
+  if (f16) {
+    if (form == 0) return exhaustive ? V(true, 0, true) : V(false, 0, true);
+    return exhaustive ? V(true, 1, true) : V(false, 1, true);
+  }
+  if (form == 0) return exhaustive ? V(true, 0, false) : V(false, 0, false);
+  return exhaustive ? V(true, 1, false) : V(false, 1, false);
+#undef V
 }
 
 mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
@@ -526,7 +532,7 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.act = c->act;
   a.logit_scale = c->logit_scale;
 #define X(KU, KX, DP, HH) \
-  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_variant<KU, KX, DP, HH>(a, cand_idx == nullptr, c->gate_form, st);
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_variant<KU, KX, DP, HH>(a, cand_idx == nullptr, c->gate_form, c->f16, st);
   MOL_SHAPES(X)
 #undef X
   return mol_fail(MOL_EUNSUPPORTED, "no MoL kernel built for k_u=%d k_x=%d d_p=%d H=%d", c->k_u, c->k_x, c->d_p, c->H);

@@ -53,7 +53,7 @@ __global__ void k_pack_weights(const uint16_t *W1, const uint16_t *W2, const flo
 
 // Xi^T[h, n] = W1x[h, :] . gx[n, :] + b1[h] on 32x32x16 MFMA: A = W1x rows (hidden units), B = item rows.
 // A wavefront takes 32 items; lane (c = lane%32, half) loads its item's row chunks once and walks the hidden tiles.
-template <int KS>  // d_gx / 16
+template <int KS, bool F16>  // d_gx / 16; 16-bit type of the inputs and of Xi
 __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const char *w1x, const float *b1,
                                                          uint16_t *xi, int64_t N, int H) {
   const int lane = threadIdx.x & 63;
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         const uint4 af = ld16(w1x + ((size_t)(32 * mt + c) * DG + 16 * s + 8 * h) * 2);
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(af), as_bf16x8(bfrag[s]), acc, 0, 0, 0);
+        acc = mfma16_32x32x16<F16>(af, bfrag[s], acc);
       }
       mfma_settle();
       if (ok) {
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
           float v[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) v[i] = acc[4 * q + i] + (b1 ? b1[hu + i] : 0.f);
-          uint2 o = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+          uint2 o = make_uint2(pack16x2<F16>(v[0], v[1]), pack16x2<F16>(v[2], v[3]));
           *reinterpret_cast<uint2 *>(xi + (size_t)n * H + hu) = o;
         }
       }
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void k_item_gate_cache(const char *gx, const c
 // wavefront's lanes share a weight row and differ in the item, results leave through LDS in whole rows.
 __global__ __launch_bounds__(256) void k_item_weights(const uint16_t *gx, const uint16_t *Wx1, const float *bx1,
                                                       const uint16_t *Wx2, const float *bx2, float *xw, int64_t N,
-                                                      int d_gx, int d_hx, int P, int act) {
+                                                      int d_gx, int d_hx, int P, int act, bool f16) {
   extern __shared__ float lds_iw[];
   const int sg = d_gx + 1, sh = d_hx + 1, sp = P + 1;
   float *gxs = lds_iw;               // [32][sg], reused as out [32][sp] (P <= 128, d_gx >= 16: see the launcher)
@@ -111,14 +111,14 @@ __global__ __launch_bounds__(256) void k_item_weights(const uint16_t *gx, const 
     __syncthreads();
     for (int i = threadIdx.x; i < 32 * d_gx; i += 256) {
       const int it = i / d_gx, j = i % d_gx;
-      gxs[it * sg + j] = it < cnt ? bf16_bits_to_f32(gx[(size_t)(n0 + it) * d_gx + j]) : 0.f;
+      gxs[it * sg + j] = it < cnt ? dec16(gx[(size_t)(n0 + it) * d_gx + j], f16) : 0.f;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < 32 * d_hx; i += 256) {
       const int it = i & 31, u = i >> 5;
       float acc = bx1 ? bx1[u] : 0.f;
       const uint16_t *w = Wx1 + (size_t)u * d_gx;
-      for (int j = 0; j < d_gx; ++j) acc = fmaf(bf16_bits_to_f32(w[j]), gxs[it * sg + j], acc);
+      for (int j = 0; j < d_gx; ++j) acc = fmaf(dec16(w[j], f16), gxs[it * sg + j], acc);
       hid[it * sh + u] = act == MOL_ACT_RELU ? fmaxf(acc, 0.f) : acc / (1.f + __expf(-acc));
     }
     __syncthreads();
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void k_item_weights(const uint16_t *gx, const 
       const int it = i & 31, p = i >> 5;
       float acc = bx2 ? bx2[p] : 0.f;
       const uint16_t *w = Wx2 + (size_t)p * d_hx;
-      for (int j = 0; j < d_hx; ++j) acc = fmaf(bf16_bits_to_f32(w[j]), hid[it * sh + j], acc);
+      for (int j = 0; j < d_hx; ++j) acc = fmaf(dec16(w[j], f16), hid[it * sh + j], acc);
       gxs[it * sp + p] = acc;  // the features are no longer needed
     }
     __syncthreads();
@@ -150,7 +150,7 @@ mol_status_t launch_item_weights(const mol_corpus *c, const mol_config_t *cfg, c
   if (grid > need) grid = need;
   hipLaunchKernelGGL(k_item_weights, dim3((unsigned)grid), dim3(256), lds, st, static_cast<const uint16_t *>(item_gate),
                      static_cast<const uint16_t *>(cfg->Wx1), cfg->bx1, static_cast<const uint16_t *>(cfg->Wx2), cfg->bx2,
-                     c->xw, c->N, c->d_gx, cfg->d_hx, c->P, c->act);
+                     c->xw, c->N, c->d_gx, cfg->d_hx, c->P, c->act, c->f16);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
@@ -167,8 +167,11 @@ mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, 
   const char *gx = static_cast<const char *>(item_gate);
   const char *w = static_cast<const char *>(w1x);
   uint16_t *xi = static_cast<uint16_t *>(c->xi);
-#define LAUNCH(KS)                                                                                              \
-  hipLaunchKernelGGL(k_item_gate_cache<KS>, dim3((unsigned)grid), dim3(256), 0, st, gx, w, b1, xi, c->N, c->H); \
+#define LAUNCH(KS)                                                                                                      \
+  if (c->f16)                                                                                                           \
+    hipLaunchKernelGGL((k_item_gate_cache<KS, true>), dim3((unsigned)grid), dim3(256), 0, st, gx, w, b1, xi, c->N, c->H);  \
+  else                                                                                                                  \
+    hipLaunchKernelGGL((k_item_gate_cache<KS, false>), dim3((unsigned)grid), dim3(256), 0, st, gx, w, b1, xi, c->N, c->H); \
   break;
   switch (c->d_gx / 16) {
     case 1: LAUNCH(1)
@@ -204,6 +207,8 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     case 16: case 32: case 64: case 96: case 128: case 256: break;
     default: return mol_fail(MOL_EUNSUPPORTED, "d_gx=%d: supported widths are 16, 32, 64, 96, 128, 256", cfg->d_gx);
   }
+  if (cfg->mol_dtype != 0 && cfg->mol_dtype != MOL_BF16 && cfg->mol_dtype != MOL_F16)
+    return mol_fail(MOL_EINVAL, "mol_dtype must be 0, MOL_BF16 or MOL_F16");
   const bool decomposed = cfg->gate_form == MOL_GATE_DECOMPOSED;
   if (cfg->gate_form != MOL_GATE_CONCAT && !decomposed) return mol_fail(MOL_EINVAL, "bad gate_form");
   if (decomposed) {
@@ -230,6 +235,7 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   c->logit_scale = cfg->logit_scale;
   c->flags = cfg->flags;
   c->gate_form = cfg->gate_form;
+  c->f16 = cfg->mol_dtype == MOL_F16;
   c->d_hu = decomposed ? cfg->d_hu : 0;
   (void)hipGetDevice(&c->device);
 
