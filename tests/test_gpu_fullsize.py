@@ -70,3 +70,51 @@ def test_c4_100m_two_stage_sampled_parity():
     assert int(cc2.min()) == Kp and int(cc2.max()) == Kp
     assert torch.equal(ci.sort(dim=1).values, ci2.sort(dim=1).values)
     corpus.free()
+
+
+def test_c4_100m_int8_stage1_sampled_parity():
+    """INT8 stage 1 at the full size, in the bench launch configuration: integer scores, so the checks are exact."""
+    import paper_2306_04039_amd as m
+    free, total = torch.cuda.mem_get_info()
+    if total < 200 * 2**30:
+        pytest.skip("needs the 288 GB device")
+    wl = synth.CONFIGS["C4"].replace(k_u=16, k_x=1, d_p=32, H=32, d_gu=32, d_gx=32)   # small stage-2 tensors: stage 1 is under test
+    cen = synth.make_centres(wl, DEV)
+    items = synth.make_items(wl, cen)
+    q = synth.make_queries(wl, cen)
+    gw = synth.make_gate_weights(wl, DEV)
+    sx = 127.0 / float(items["x1"].float().abs().max())
+    sq = 127.0 / float(q["q1"].float().abs().max())
+    x8 = m.quantize_int8(items["x1"], sx)
+    q8 = m.quantize_int8(q["q1"], sq)
+    # the quantiser against the oracle on a slice of the table and on the queries
+    assert np.array_equal(x8[:200_000].cpu().numpy(), orc.quantize_int8(bits(items["x1"][:200_000]), sx))
+    assert np.array_equal(x8[-70_001:].cpu().numpy(), orc.quantize_int8(bits(items["x1"][-70_001:]), sx))
+    q8_o = orc.quantize_int8(bits(q["q1"]), sq)
+    assert np.array_equal(q8.cpu().numpy(), q8_o)
+    corpus = m.mol_corpus_pack(x8, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u, borrow=True)
+    B, Kp = wl.B, wl.Kp
+    ci, cs, cc = m.hindexer_topk(corpus, q8, Kp, seed=1003)
+    torch.cuda.synchronize()
+    assert int(cc.min()) == Kp and int(cc.max()) == Kp
+    g = torch.Generator(device=DEV).manual_seed(12)
+    probe = torch.randint(0, wl.N, (3_000_000,), generator=g, device=DEV)
+    probe_x = x8[probe].cpu().numpy()
+    probe_np = probe.cpu().numpy()
+    for b in (0, 17, 31):
+        cand = ci[b].long()
+        assert int(cand.min()) >= 0 and cand.unique().numel() == Kp
+        s_cand = orc.stage1_scores(q8_o[b:b + 1], x8[cand].cpu().numpy())[0]
+        assert np.array_equal(cs[b].cpu().numpy().astype(np.float64), s_cand)           # integer scores, exactly
+        boundary = s_cand.min()
+        tie_limit = cand[torch.from_numpy(s_cand == boundary).to(DEV)].max().item()      # ties are taken by lowest index
+        s_probe = orc.stage1_scores(q8_o[b:b + 1], probe_x)[0]
+        inside = np.isin(probe_np, cand.cpu().numpy())
+        out = ~inside
+        assert np.all(s_probe[out] <= boundary), "an item above the K'-th score was left out"
+        assert np.all(probe_np[out][s_probe[out] == boundary] > tie_limit), "a tie with a lower index was left out"
+        assert inside.sum() >= 1000 and np.all(s_probe[inside] >= boundary)
+    ci2, cs2, cc2 = m.hindexer_topk(corpus, q8, Kp, seed=1003, mode=m.HINDEXER_EXACT | 0x100)
+    torch.cuda.synchronize()
+    assert int(cc2.min()) == Kp and torch.equal(ci.sort(dim=1).values, ci2.sort(dim=1).values)
+    corpus.free()
