@@ -23,6 +23,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the corpus scan moves on the default workload, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
 # this script (KiB per dispatch), each scaled by what the same counter reads for a 1 GiB device copy (--calibrate-copy):
 # FETCH_SIZE counts half the bytes (x2.000), WRITE_SIZE all of them (x1.000).  Re-measure when the scan kernel changes.
+# matrix-core busy fraction of the MoL kernel from a rocprofv3 --pmc run of this script (profiles/k_mol_score_C4-100M.md)
+MOL_MFMA_BUSY_FRAC = {"C4-100M": 0.157}
 SCAN_TRAFFIC_KIB = {("C4-100M", False): {"fetch": 6250189.3, "fetch_scale": 2.0, "write": 31767.9, "write_scale": 1.0},
                     ("C4-100M", True): {"fetch": 3125102.7, "fetch_scale": 2.0, "write": 33731.6, "write_scale": 1.0}}  # key: (workload, int8 stage 1)
 
@@ -257,11 +259,14 @@ def main():
         "kernels_note": "from a second, untimed set of steps with every kernel group bracketed by events",
         "mol_stage": {"gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,
                       "gather_frac_of_hbm_peak": (gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 / HBM_PEAK_GBS) if mol_n else 0.0,
-                      "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0},
+                      "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0,
+                      "model_frac_of_bf16_mfma_peak": (mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 / 2500.0) if mol_n else 0.0,
+                      "mfma_busy_frac_rocprof": MOL_MFMA_BUSY_FRAC.get(wl.name) if not decomposed else None},
         "paper_context": PAPER_CONTEXT,
     }
-    if int8:
-        result["int8_stage1_recall_vs_unquantised_topKp"] = stage1_recall(items["x1"], q["q1"], out1[0], Kp)
+    # stage-1 recall@K' against the exact top-K' of the stored (unquantised) table, first 4 queries, torch fp32 matmul
+    rec = stage1_recall(items["x1"], q["q1"], out1[0], Kp)
+    result["int8_stage1_recall_vs_unquantised_topKp" if int8 else "stage1_recall_at_Kp"] = rec
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
