@@ -143,6 +143,14 @@ static mol_status_t check_ws(const void *ws, size_t have, size_t need) {
   return MOL_OK;
 }
 
+// The kernels run on the current device: it has to be the one that holds the corpus.
+static mol_status_t check_device(const mol_corpus_t *c) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != c->device) return mol_fail(MOL_EINVAL, "the corpus lives on device %d but device %d is current", c->device, dev);
+  return MOL_OK;
+}
+
 extern "C" mol_status_t hindexer_topk(const mol_corpus_t *c, const void *q1, int B, int Kp, const int32_t *sample_idx,
                                       int64_t lambda, uint64_t seed, int mode, int32_t *cand_idx, float *cand_score,
                                       int32_t *cand_count, void *workspace, size_t workspace_bytes, void *stream) {
@@ -154,7 +162,9 @@ extern "C" mol_status_t hindexer_topk(const mol_corpus_t *c, const void *q1, int
     return mol_fail(MOL_EINVAL, "unknown mode %d", mode);
   if (sample_idx && lambda < 1) return mol_fail(MOL_EINVAL, "an explicit sample needs lambda >= 1");
   HindexerPlan p;
-  mol_status_t rc = hindexer_plan(c, B, Kp, lambda, mode & ~MOL_HINDEXER_FORCE_REDO, &p);
+  mol_status_t rc = check_device(c);
+  if (rc != MOL_OK) return rc;
+  rc = hindexer_plan(c, B, Kp, lambda, mode & ~MOL_HINDEXER_FORCE_REDO, &p);
   if (rc != MOL_OK) return rc;
   rc = check_ws(workspace, workspace_bytes, p.total);
   if (rc != MOL_OK) return rc;
@@ -167,7 +177,7 @@ static mol_status_t mol_common_checks(const mol_corpus_t *c, const void *ue, con
   if (!c || !ue || !ug) return mol_fail(MOL_EINVAL, "NULL corpus / user_embs / user_gate");
   if (B < 1 || B > 1024) return mol_fail(MOL_EINVAL, "B=%d must be in [1, 1024]", B);
   if (cand && Kp < 1) return mol_fail(MOL_EINVAL, "Kp=%d must be >= 1 when cand_idx is given", Kp);
-  return MOL_OK;
+  return check_device(c);
 }
 
 extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
@@ -192,6 +202,8 @@ extern "C" mol_status_t mol_gather_items(const mol_corpus_t *c, const int32_t *c
   if (!c || !cand_idx || !out_embs) return mol_fail(MOL_EINVAL, "mol_gather_items: NULL corpus / cand_idx / out_embs");
   if (B < 1 || B > 1024 || Kp < 1) return mol_fail(MOL_EINVAL, "mol_gather_items: B=%d must be in [1, 1024] and Kp=%d >= 1", B, Kp);
   if (reinterpret_cast<uintptr_t>(out_embs) & 15u) return mol_fail(MOL_EINVAL, "mol_gather_items: out_embs must be 16-byte aligned");
+  const mol_status_t rc = check_device(c);
+  if (rc != MOL_OK) return rc;
   return launch_gather_items(c, cand_idx, B, Kp, out_embs, static_cast<hipStream_t>(stream));
 }
 

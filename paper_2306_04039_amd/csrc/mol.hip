@@ -17,6 +17,8 @@
 // to ~16 mantissa bits, which keeps phi within 2e-3 of the fp64 definition even for large logit scales.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 namespace {
@@ -399,17 +401,22 @@ template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16>
 mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
   auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM, F16>;
+  // launch shape of this instantiation, found once per process (one GPU; concurrent first calls are serialised)
+  static std::mutex mu;
   static bool configured = false;
   static int per_sm = 1, sm_count = 0;
-  if (!configured) {
-    int dev = 0;
-    HIP_TRY(hipGetDevice(&dev));
-    HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)S::LDS));
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, S::LDS));
-    if (per_sm < 1) per_sm = 1;
-    configured = true;
+  {
+    std::lock_guard<std::mutex> lk(mu);
+    if (!configured) {
+      int dev = 0;
+      HIP_TRY(hipGetDevice(&dev));
+      HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)S::LDS));
+      HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, S::LDS));
+      if (per_sm < 1) per_sm = 1;
+      configured = true;
+    }
   }
   const int64_t ntiles = EXH ? ((a.Kp + 31) / 32) * ((a.B + MOL_QCHUNK - 1) / MOL_QCHUNK) : ((a.Kp + 31) / 32) * a.B;
   int64_t grid = (int64_t)sm_count * per_sm;

@@ -16,6 +16,8 @@
 #include <math.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.hpp"
 #include "msel.hpp"
 #include "select.hpp"
@@ -736,13 +738,15 @@ size_t scan_lds_bytes(int epi, int nqg) {
 }
 
 int device_cus() {
-  static int cus = 0;
-  if (!cus) {
+  static std::atomic<int> cus{0};  // one GPU per process: the first answer is kept
+  int v = cus.load(std::memory_order_relaxed);
+  if (!v) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      v = 0;
+    cus.store(v, std::memory_order_relaxed);
   }
-  return cus;
+  return v;
 }
 
 // Workgroups (of 4 wavefronts) a scan over `ntiles` tiles is launched with: resident blocks, at most one tile each.
