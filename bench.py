@@ -127,12 +127,53 @@ def stage1_recall(x1, q1, cand_idx, Kp, n_queries=4, chunk=10_000_000):
     return hit / float(nq * Kp)
 
 
+def exhaustive(args, m, wl, dev):
+    """The exhaustive configuration: MoL over every item for every query, then the top-k (no stage 1).  The scoring kernel
+    is a dense contraction (matrix cores) co-limited by its vector epilogue; the line reports the model arithmetic against
+    the bf16 MFMA peak."""
+    import torch
+    items, q, gw = generate(wl, dev)
+    corpus = m.mol_corpus_pack(None, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
+                               logit_scale=wl.logit_scale, act=wl.act, borrow=True)
+    B, k = wl.B, wl.k
+    ws = torch.empty(m.mol_workspace_bytes(corpus, B, 0, k), dtype=torch.uint8, device=dev)
+    out = (torch.empty(B, k, dtype=torch.int32, device=dev), torch.empty(B, k, dtype=torch.float32, device=dev))
+    steps, warmup = min(args.steps, 10), min(args.warmup, 2)
+    for _ in range(warmup):
+        m.mol_topk(corpus, q["F"], q["gu"], None, k, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    m.profile_read()
+    m.profile_enable(True, slots=["mol_score"])
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        m.mol_topk(corpus, q["F"], q["gu"], None, k, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    m.profile_enable(False)
+    mol_ms, mol_n = m.profile_read()["mol_score"]
+    ms_per_step = wall * 1e3 / steps
+    flops = B * wl.N * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
+    achieved = flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "queries/s, exhaustive MoL top-100 over 1M items, 1 GPU", "value": B / (ms_per_step * 1e-3), "unit": "queries/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, exhaustive, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}"},
+        "roofline": {"kernel": "k_mol_score (item-stationary exhaustive form)", "bound": "mfma", "achieved": achieved, "peak": 2500.0,
+                     "unit": "TFLOP/s", "frac": achieved / 2500.0, "traffic": None, "avg_launch_ms": mol_ms / max(1, mol_n),
+                     "launches": mol_n,
+                     "note": "model arithmetic 2*P*d_P + 4*P*H flop per pair; the kernel is co-limited by its vector epilogue "
+                             "(activation, hi/lo split, softmax: about 1000 lane-operations per pair)"},
+    }), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C4 is the workload the metric is quoted on; C5 is the exhaustive-MoL configuration (no stage 1)")
     ap.add_argument("--n-items", type=int, default=0, help="override N (debugging; the result is then not the named workload)")
     ap.add_argument("--mode", type=int, default=0, help="0 = exact-on-success h-indexer (default), 1 = Algorithm 2 as written")
     ap.add_argument("--stage1", default="config", choices=["config", "int8"],
@@ -159,6 +200,8 @@ def main():
     wl = build_workload(args.workload, args.n_items)
     log(f"workload {wl.name}: N={wl.N} B={wl.B} K'={wl.Kp} P={wl.k_u}x{wl.k_x} d_P={wl.d_p} H={wl.H} k={wl.k}")
 
+    if wl.Kp == 0:
+        return exhaustive(args, m, wl, dev)
     items, q, gw = generate(wl, dev)
     t0 = time.time()
     int8 = args.stage1 == "int8"

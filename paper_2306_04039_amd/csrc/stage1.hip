@@ -167,8 +167,11 @@ __device__ inline bool last_workgroup(uint32_t *ticket) {
 //                the integer scores go to the selection as they are, no scale is applied).
 // Lane (r = lane%32, h = lane/32) takes chunks 2*ci + h of row r; the query operand uses the same chunk
 // numbering, so the contraction pairs equal positions whatever order the hardware walks them in.
+#ifndef MOL_SCAN_MIN_WAVES
+#define MOL_SCAN_MIN_WAVES 2  // keeps the 4-query-group variants at two wavefronts per SIMD (they need 260 registers otherwise)
+#endif
 template <int DT, int NQG, int EPI, bool GATHER, int DEPTH>
-__global__ __launch_bounds__(256) void k_stage1_scan(ScanArgs a) {
+__global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArgs a) {
   constexpr int NCH = DT == MOL_F32 ? 8 : (DT == MOL_BF16 ? 4 : 2);
   constexpr int ROWB = DT == MOL_F32 ? 256 : (DT == MOL_BF16 ? 128 : 64);
   constexpr bool REDO = EPI >= EPI_HIST_KEY;
