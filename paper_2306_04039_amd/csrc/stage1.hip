@@ -733,6 +733,10 @@ void (*scan_kernel(int nqg))(ScanArgs) {
                   : (nqg == 2 ? k_stage1_scan<DT, 2, EPI, GATHER, DEPTH> : k_stage1_scan<DT, 1, EPI, GATHER, DEPTH>);
 }
 
+// Queries one scan launch serves (a wavefront keeps them all in registers): 128, or 64 for an fp32 table, whose operands
+// are twice as wide and would not leave room for two wavefronts per SIMD.
+constexpr int scan_query_span(int dt) { return dt == MOL_F32 ? 64 : 128; }
+
 // dynamic LDS of one scan workgroup
 size_t scan_lds_bytes(int epi, int nqg) {
   if (epi == EPI_HIST_KEY || epi == EPI_HIST_IDX) return (size_t)32 * nqg * EXACT_BINS * 4;
@@ -778,10 +782,11 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
 template <int DT, int EPI, bool GATHER>
 mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStream_t st) {
   const int64_t ntiles = (a0.n_rows + 31) / 32;
-  for (int qb = 0; qb < B; qb += 128) {
+  const int span = scan_query_span(DT);
+  for (int qb = 0; qb < B; qb += span) {
     ScanArgs a = a0;
     a.qbase = qb;
-    const int rem = B - qb;
+    const int rem = B - qb < span ? B - qb : span;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
     auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
     int64_t grid = 0;
@@ -811,8 +816,9 @@ mol_status_t launch_scan_dt(int dt, const ScanArgs &a, int B, int64_t fixed_grid
 mol_status_t list_scan_grid(int dt, int B, int64_t N, int64_t *grid_out) {
   const int64_t ntiles = (N + 31) / 32;
   int64_t best = -1;
-  for (int qb = 0; qb < B; qb += 128) {
-    const int rem = B - qb;
+  const int span = scan_query_span(dt);
+  for (int qb = 0; qb < B; qb += span) {
+    const int rem = B - qb < span ? B - qb : span;
     const int nqg = rem > 64 ? 4 : (rem > 32 ? 2 : 1);
     int64_t g = 0;
     mol_status_t rc = dt == MOL_F32 ? scan_grid<MOL_F32, EPI_FILTER, false>(nqg, ntiles, &g)

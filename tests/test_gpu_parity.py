@@ -44,6 +44,7 @@ S1_TOL = 2e-6   # fp32 accumulation of 64 products of magnitude <= 1 vs fp64
     ("f32", 40_001, 16, 1024),
     ("bf16", 70_000, 70, 300),      # three query groups -> NQG = 4 with padding
     ("bf16", 33_000, 130, 200),     # two launches over the query dimension
+    ("f32", 30_000, 150, 256),      # fp32 table: 64 queries per launch, three launches
 ])
 def test_hindexer_exact_mode_matches_exact_topk(dtype, N, B, Kp):
     wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype=dtype, n_clusters=64)
