@@ -65,30 +65,47 @@ __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
     if (valid && match) atomicAdd(&sh.hist[(k >> lo) & dmask], 1u);
   });
   __syncthreads();
-  // locate the digit that holds rank krem counting from the largest digit
+  // locate the digit that holds rank krem counting from the largest digit: the first wavefront alone, with lane scans
+  // (chunk t covers `per` consecutive digits from the top; then the lanes take one digit each of the chunk that holds it)
   const int nb = 1 << w;
-  const int per = (nb + 63) / 64;  // bins per chunk (<= 32)
+  const int per = (nb + 63) / 64;  // digits per chunk (<= 32)
   if (tid < 64) {
+    const uint32_t krem = sh.krem;
     uint32_t s = 0;
-    int top = nb - 1 - tid * per;  // chunk tid covers digits top, top-1, ..., top-per+1
+    const int top = nb - 1 - tid * per;
     for (int j = 0; j < per; ++j) {
-      int d = top - j;
+      const int d = top - j;
       if (d >= 0) s += sh.hist[d];
     }
-    sh.chunk[tid] = s;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t krem = sh.krem, acc = 0;
-    int c = 0;
-    while (c < 63 && acc + sh.chunk[c] < krem) acc += sh.chunk[c++];
-    int d = nb - 1 - c * per;
-    int stop = d - per + 1;
-    if (stop < 0) stop = 0;
-    while (d > stop && acc + sh.hist[d] < krem) acc += sh.hist[d--];
-    sh.krem = krem - acc;  // rank inside digit d
-    sh.prefix = prefix | ((uint32_t)d << lo);
-    sh.ties = sh.hist[d];
+    uint32_t incl = s;  // inclusive sum over chunks 0..tid
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = (uint32_t)__shfl_up((int)incl, o);
+      if (tid >= o) incl += up;
+    }
+    // first chunk whose inclusive sum reaches krem (the last chunk if none does: krem never exceeds the total)
+    const uint64_t reach = __ballot(incl >= krem);
+    const int c = reach ? __ffsll((unsigned long long)reach) - 1 : 63;
+    const uint32_t before = (uint32_t)__shfl((int)(incl - s), c);  // elements in the chunks above chunk c
+    // inside chunk c: lane j takes digit dtop - j
+    const int dtop = nb - 1 - c * per;
+    const int d_mine = dtop - tid;
+    const uint32_t h = (tid < per && d_mine >= 0) ? sh.hist[d_mine] : 0u;
+    uint32_t hin = h;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+      const uint32_t up = (uint32_t)__shfl_up((int)hin, o);
+      if (tid >= o) hin += up;
+    }
+    const uint64_t hit = __ballot(tid < per && d_mine >= 0 && before + hin >= krem);
+    int j = hit ? __ffsll((unsigned long long)hit) - 1 : (dtop < per ? dtop : per - 1);  // fall back to the chunk's last digit
+    const uint32_t above = before + (uint32_t)__shfl((int)(hin - h), j);
+    if (tid == 0) {
+      const int d = dtop - j;
+      sh.krem = krem - above;  // rank inside digit d
+      sh.prefix = prefix | ((uint32_t)d << lo);
+      sh.ties = sh.hist[d];
+    }
   }
   __syncthreads();
 }
