@@ -16,7 +16,6 @@ namespace {
 __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores, const int32_t *cand, int64_t Kp, int k,
                                                              float *st_score, int32_t *st_idx) {
   __shared__ SelectShared sh;
-  __shared__ uint32_t nvalid_s;
   const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
   const int tid = threadIdx.x;
   const int64_t per = (Kp + G - 1) / G;
@@ -32,20 +31,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
       if (id >= 0) f(f32_to_key(v), (uint32_t)id);
     });
   };
-  if (tid == 0) {
-    nvalid_s = 0;
-    sh.out_count = 0;
-  }
-  __syncthreads();
-  uint32_t mine = 0;
-  for (int64_t i = tid; i < n; i += SELECT_THREADS) mine += (ci ? ci[i] >= 0 : true) ? 1u : 0u;
-  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor((int)mine, o);
-  if ((tid & 63) == 0 && mine) atomicAdd(&nvalid_s, mine);
-  __syncthreads();
-  const uint32_t nvalid = nvalid_s;
-  const uint32_t kk = nvalid < (uint32_t)k ? nvalid : (uint32_t)k;
+  if (tid == 0) sh.out_count = 0;
+  const uint32_t kk = block_select_kth<true>(each, (uint32_t)k, sh);  // min(k, valid entries of the slice)
   if (kk > 0) {
-    block_select_kth<true>(each, kk, sh);
     each([&](uint32_t key, uint32_t idx) {
       if (select_accept(key, idx, sh)) {
         const uint32_t slot = atomicAdd(&sh.out_count, 1u);
@@ -69,7 +57,6 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
   __shared__ SelectShared sh;
   __shared__ uint32_t skey[TOPK_MAX];
   __shared__ uint32_t sidx[TOPK_MAX];
-  __shared__ uint32_t nvalid_s;
   const int b = blockIdx.x;
   const int tid = threadIdx.x;
   const float *sc = scores + (size_t)b * Kp;
@@ -80,24 +67,13 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
       if (id >= 0) f(f32_to_key(v), (uint32_t)id);
     });
   };
-  // number of valid candidates
-  if (tid == 0) nvalid_s = 0;
-  __syncthreads();
-  uint32_t mine = 0;
-  for (int64_t i = tid; i < Kp; i += SELECT_THREADS) mine += (ci ? ci[i] >= 0 : true) ? 1u : 0u;
-  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor((int)mine, o);
-  if ((tid & 63) == 0 && mine) atomicAdd(&nvalid_s, mine);
-  __syncthreads();
-  const uint32_t nvalid = nvalid_s;
-  const uint32_t kk = nvalid < (uint32_t)k ? nvalid : (uint32_t)k;  // how many real results
   for (int i = tid; i < TOPK_MAX; i += SELECT_THREADS) {
     skey[i] = 0u;            // sorts last
     sidx[i] = 0xffffffffu;
   }
   if (tid == 0) sh.out_count = 0;
-  __syncthreads();
+  const uint32_t kk = block_select_kth<true>(each, (uint32_t)k, sh);  // how many real results: min(k, valid candidates)
   if (kk > 0) {
-    block_select_kth<true>(each, kk, sh);
     each([&](uint32_t key, uint32_t idx) {
       if (select_accept(key, idx, sh)) {
         uint32_t slot = atomicAdd(&sh.out_count, 1u);

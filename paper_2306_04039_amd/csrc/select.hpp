@@ -14,6 +14,8 @@ struct SelectShared {
   uint32_t chunk[64];
   uint32_t red_min[SELECT_THREADS / WAVE];
   uint32_t red_max[SELECT_THREADS / WAVE];
+  uint32_t red_cnt[SELECT_THREADS / WAVE];
+  uint32_t count;      // number of elements of the list
   uint32_t prefix;     // bits decided so far
   uint32_t krem;       // rank still to resolve inside the matching set
   uint32_t kmin, kmax;
@@ -110,32 +112,40 @@ __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
   __syncthreads();
 }
 
-// Finds the K-th element (1 <= K <= number of valid elements) of the list.  On return sh.kth_key / sh.idx_limit
-// describe the accepted set { key > kth_key } U { key == kth_key and idx <= idx_limit }, which has exactly K members.
+// Finds the K-th element of the list, K clamped to the number of elements (returned; sh.count holds that number).
+// On return sh.kth_key / sh.idx_limit describe the accepted set { key > kth_key } U { key == kth_key and
+// idx <= idx_limit }, which has exactly the returned number of members; 0 is returned for an empty list or K = 0 and
+// nothing may then be accepted.
 // WITH_TIES = false skips the index stage (idx_limit = all ones): used when only the key value matters.
 template <bool WITH_TIES, class Each>
-__device__ void block_select_kth(Each each, uint32_t K, SelectShared &sh) {
+__device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   const int tid = threadIdx.x;
-  // 1. range of the keys: bits above the highest differing bit are common and need no pass
-  uint32_t mn = 0xffffffffu, mx = 0u;
+  // 1. size of the list and range of the keys: bits above the highest differing bit are common and need no pass
+  uint32_t mn = 0xffffffffu, mx = 0u, n_mine = 0;
   each([&](uint32_t key, uint32_t) {
     mn = min(mn, key);
     mx = max(mx, key);
+    ++n_mine;
   });
   for (int o = 32; o > 0; o >>= 1) {
     mn = min(mn, (uint32_t)__shfl_xor((int)mn, o));
     mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+    n_mine += (uint32_t)__shfl_xor((int)n_mine, o);
   }
   if ((tid & 63) == 0) {
     sh.red_min[tid >> 6] = mn;
     sh.red_max[tid >> 6] = mx;
+    sh.red_cnt[tid >> 6] = n_mine;
   }
   __syncthreads();
   if (tid == 0) {
     for (int i = 1; i < SELECT_THREADS / WAVE; ++i) {
       mn = min(mn, sh.red_min[i]);
       mx = max(mx, sh.red_max[i]);
+      n_mine += sh.red_cnt[i];
     }
+    sh.count = n_mine;
+    K = K < n_mine ? K : n_mine;
     sh.kmin = mn;
     sh.kmax = mx;
     sh.krem = K;
@@ -148,6 +158,8 @@ __device__ void block_select_kth(Each each, uint32_t K, SelectShared &sh) {
     sh.ties = 0;
   }
   __syncthreads();
+  K = sh.krem;  // the clamped rank, in every thread
+  if (K == 0) return 0;
   {
     uint32_t diff = sh.kmin ^ sh.kmax;
     int hi = diff ? 31 - __clz(diff) : -1;
@@ -160,11 +172,11 @@ __device__ void block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   }
   if (tid == 0) sh.kth_key = sh.prefix;
   __syncthreads();
-  if (!WITH_TIES) return;
+  if (!WITH_TIES) return K;
   // 2. ties at the K-th key: keep the krem smallest indices among them
   //    (when the keys were all equal no pass ran and `ties` is not known: always resolve by index then)
   const bool all_equal = (sh.kmin == sh.kmax);
-  if (!all_equal && sh.krem == sh.ties) return;  // every tie is accepted
+  if (!all_equal && sh.krem == sh.ties) return K;  // every tie is accepted
   __syncthreads();
   if (tid == 0) sh.prefix = 0;
   __syncthreads();
@@ -176,6 +188,7 @@ __device__ void block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   }
   if (tid == 0) sh.idx_limit = ~sh.prefix;
   __syncthreads();
+  return K;
 }
 
 __device__ __forceinline__ bool select_accept(uint32_t key, uint32_t idx, const SelectShared &sh) {
