@@ -512,38 +512,46 @@ __global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_
   }
 }
 
-// Walks lists [lo, hi) of query b.  A wavefront takes 64 lists at a time: the lanes fetch the 64 counts with one load,
-// then the lists are read four at a time (independent loads in flight), lanes across the entries of a list.
+// Walks lists [lo, hi) of query b.  A wavefront takes 32 lists at a time: the lanes fetch the counts with one load, then
+// the lists are read sixteen at a time (independent loads in flight), each half of the wavefront across the entries of
+// one list (a list holds about 30 entries at the sizes the path is tuned for).
 // f(entry, valid) is called the same number of times by all 64 lanes of a wavefront (wavefront collectives are safe).
 template <class F>
 __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int B, int b,
                                                   int64_t lo, int64_t hi, int nwaves_in_block, F f) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int hf = lane >> 5, sub = lane & 31;
   const uint32_t cap32 = (uint32_t)cap;
-  for (int64_t l0 = lo + (int64_t)wv * 64; l0 < hi; l0 += (int64_t)nwaves_in_block * 64) {
-    uint32_t mine = 0;
-    if (l0 + lane < hi) mine = cnt[(size_t)b * L + l0 + lane];
+  constexpr int CHUNK = 32;  // lists a wavefront takes at a time (small, so that all wavefronts of a workgroup get lists)
+  constexpr int UNR = 8;     // list pairs in flight
+  for (int64_t l0 = lo + (int64_t)wv * CHUNK; l0 < hi; l0 += (int64_t)nwaves_in_block * CHUNK) {
+    uint32_t mine = 0;  // lane j (and j + 32) holds the count of list l0 + j
+    if (l0 + sub < hi) mine = cnt[(size_t)b * L + l0 + sub];
     if (mine > cap32) mine = cap32;
-    const int nl = (int)((hi - l0) < 64 ? (hi - l0) : 64);
+    const int nl = (int)((hi - l0) < CHUNK ? (hi - l0) : CHUNK);
     const uint2 *base = surv + ((size_t)l0 * B + b) * cap;  // list l of query b starts at (l * B + b) * cap
     const size_t lstride = (size_t)B * cap;
-    for (int i0 = 0; i0 < nl; i0 += 4) {
-      uint32_t n[4];
-      uint2 v[4];
+    for (int i0 = 0; i0 < nl; i0 += 2 * UNR) {
+      uint32_t n[UNR], nmax[UNR];
+      uint2 v[UNR];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        n[u] = (i0 + u < nl) ? (uint32_t)__shfl((int)mine, i0 + u) : 0u;
+      for (int u = 0; u < UNR; ++u) {  // the lower half of the wavefront reads list i0 + 2u, the upper half the next one
+        const int l_lo = i0 + 2 * u, l_hi = l_lo + 1;
+        const uint32_t n_lo = (l_lo < nl) ? (uint32_t)__shfl((int)mine, l_lo) : 0u;
+        const uint32_t n_hi = (l_hi < nl) ? (uint32_t)__shfl((int)mine, l_hi & 31) : 0u;
+        n[u] = hf ? n_hi : n_lo;
+        nmax[u] = n_lo > n_hi ? n_lo : n_hi;
         v[u] = make_uint2(0u, 0u);
-        if ((uint32_t)lane < n[u]) v[u] = base[(size_t)(i0 + u) * lstride + lane];
+        if ((uint32_t)sub < n[u]) v[u] = base[(size_t)(l_lo + hf) * lstride + sub];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if (n[u]) f(v[u], (uint32_t)lane < n[u]);
-        for (uint32_t e0 = 64; e0 < n[u]; e0 += 64) {  // lists longer than a wavefront (rare)
-          const uint32_t e = e0 + lane;
+      for (int u = 0; u < UNR; ++u) {
+        if (nmax[u]) f(v[u], (uint32_t)sub < n[u]);
+        for (uint32_t e0 = 32; e0 < nmax[u]; e0 += 32) {  // lists longer than half a wavefront
+          const uint32_t e = e0 + sub;
           const bool valid = e < n[u];
           uint2 w = make_uint2(0u, 0u);
-          if (valid) w = base[(size_t)(i0 + u) * lstride + e];
+          if (valid) w = base[(size_t)(i0 + 2 * u + hf) * lstride + e];
           f(w, valid);
         }
       }
@@ -988,8 +996,11 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   {
     hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, force_redo, sstat);
     HIP_TRY(hipGetLastError());
-    int G = 1024 / B;
-    G = G < 1 ? 1 : (G > 32 ? 32 : G);
+#ifndef MOL_SURV_BLOCKS
+#define MOL_SURV_BLOCKS 1024
+#endif
+    int G = MOL_SURV_BLOCKS / B;
+    G = G < 1 ? 1 : (G > MOL_SURV_BLOCKS / 32 ? MOL_SURV_BLOCKS / 32 : G);
     for (int pass = 0; pass < MSEL_PASSES; ++pass) {
       hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
                          pass);
