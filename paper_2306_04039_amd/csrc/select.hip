@@ -111,9 +111,15 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
 }  // namespace
 
 // slices per query of the two-level form (1 = single level)
+#ifndef MOL_TOPK_SLICE
+#define MOL_TOPK_SLICE 8192  // entries of a row one level-1 workgroup reduces
+#endif
+#ifndef MOL_TOPK_MAXG
+#define MOL_TOPK_MAXG 32
+#endif
 static int topk_slices(int64_t Kp, int k) {
-  int64_t G = Kp / 4096;
-  if (G > 32) G = 32;
+  int64_t G = Kp / MOL_TOPK_SLICE;
+  if (G > MOL_TOPK_MAXG) G = MOL_TOPK_MAXG;
   if (G < 2 || G * (int64_t)k * 2 > Kp) G = 1;
   return (int)G;
 }

@@ -968,8 +968,11 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     }
     if (rc != MOL_OK) return rc;
     ProfScope ps(MOL_PROF_THRESHOLD, st);
-    int G = 512 / B;
-    G = G < 1 ? 1 : (G > 32 ? 32 : G);
+#ifndef MOL_THR_BLOCKS
+#define MOL_THR_BLOCKS 1024
+#endif
+    int G = MOL_THR_BLOCKS / B;
+    G = G < 1 ? 1 : (G > MOL_THR_BLOCKS / 16 ? MOL_THR_BLOCKS / 16 : G);
     const int passes = (mode & 0xff) == MOL_HINDEXER_EXACT ? MSEL_PASSES - 1 : MSEL_PASSES;
     for (int pass = 0; pass < passes; ++pass) {
       hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
