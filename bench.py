@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE counts half the bytes (x2.000), WRITE_SIZE all of them (x1.000).  Re-measure when the scan kernel changes.
 # matrix-core busy fraction of the MoL kernel from a rocprofv3 --pmc run of this script (profiles/k_mol_score_C4-100M.md)
 MOL_MFMA_BUSY_FRAC = {"C4-100M": 0.157}
-SCAN_TRAFFIC_KIB = {("C4-100M", False): {"fetch": 6250157.6, "fetch_scale": 2.0, "write": 31840.4, "write_scale": 1.0},
-                    ("C4-100M", True): {"fetch": 3125102.6, "fetch_scale": 2.0, "write": 33806.4, "write_scale": 1.0}}  # key: (workload, int8 stage 1)
+SCAN_TRAFFIC_KIB = {("C4-100M", False): {"fetch": 6250157.8, "fetch_scale": 2.0, "write": 31848.2, "write_scale": 1.0},
+                    ("C4-100M", True): {"fetch": 3125108.3, "fetch_scale": 2.0, "write": 33815.5, "write_scale": 1.0}}  # key: (workload, int8 stage 1)
 
 # context only: the paper's serving latency for MoL + h-indexer on its (unnamed) production GPU, Section 5.3
 PAPER_CONTEXT = {"median_latency_ms_incl_batching_wait": 30.0, "hardware": "unnamed production GPU", "source": "Section 5.3"}
