@@ -219,7 +219,7 @@ def main():
         corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
                                    logit_scale=wl.logit_scale, act=wl.act, borrow=True)
     log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
-    n_sub = min(wl.N, 2_000_000)
+    n_sub = min(wl.N, 4_000_000)
     items["gx_sub"] = items["gx"][:n_sub].clone()
     del items["gx"]                       # the raw item gate features are not needed after pack
     torch.cuda.empty_cache()
@@ -319,7 +319,7 @@ def main():
         del src, dst
     if not args.no_cpu_baseline and not decomposed:
         log("timing the CPU oracle on a slice of the workload ...")
-        result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, n_sub, 4096)
+        result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, n_sub, 16384)
     print(json.dumps(result), flush=True)
 
 
