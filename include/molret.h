@@ -108,7 +108,7 @@ typedef struct {
  * Build the item-side cache (Section 2.2 "cache item-side gating weights"; the loops marked cachable in
  * Algorithm 1): keeps the stage-1 table [N, d1] and the item component embeddings [N, k_x, d_p] (already
  * L2-normalised by the caller, Eq. 9), and precomputes the item half of the first gating layer,
- * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H].
+ * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H] (decomposed gate: the item weights xw, f32 [N, P]).
  *   stage1_items : [N, d1] of stage1_dtype (fp32, bf16 or int8), or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
  *   item_embs    : bf16 [N, k_x, d_p].      item_gate : bf16 [N, d_gx]; not referenced after the call returns.
  * Allocates device memory with hipMalloc; synchronises `stream` before returning.  *out is set on MOL_OK only.
@@ -149,7 +149,8 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *                 item passes and the exact top-K' is taken).
  *   mode        : MOL_HINDEXER_PAPER  r = max(1, floor(Kp*lambda/N)); more than K' survivors are cut to the K' best,
  *                                     fewer are returned as they are (cand_count[b] < Kp).
- *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive, then the exact
+ *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive (the threshold is
+ *                                     the rank-r sampled score resolved to its leading 22 key bits, rounded down), then the exact
  *                                     top-K' of the survivors; a query whose survivors number fewer than K' or overflow the
  *                                     workspace is redone on the device with an exact multi-pass radix threshold.  The
  *                                     result is the exact stage-1 top-K' under fp32 scores.  cand_count[b] = -1 (row
