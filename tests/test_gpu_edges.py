@@ -127,3 +127,34 @@ def test_gather_items_is_a_bit_exact_row_copy(shape):
         from paper_2306_04039_amd import binding
         binding._check(binding.load_library().mol_gather_items(corpus.handle, None, 4, 777, None, None))
     corpus.free()
+
+
+@pytest.mark.parametrize("shape", [dict(k_u=8, k_x=8, d_p=64, H=128, d_gu=128, d_gx=128), dict(k_u=4, k_x=4, d_p=64, H=64, d_gu=64, d_gx=64)])
+def test_scores_do_not_depend_on_launch_size(shape):
+    """The same (query, item) pairs scored alone (a handful of wavefronts on the whole chip) and inside a large call must
+    agree bit for bit, and so must the stage-1 scores of a tiny and a large scan: results may not depend on how busy the
+    compute units are (matrix-core results read too early would show up here)."""
+    wl = synth.CONFIGS["C2"].replace(N=60_000, B=8, n_clusters=16, **shape)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(9)
+    big = torch.stack([torch.randperm(wl.N, generator=g)[:20_000] for _ in range(8)]).to(torch.int32).to(DEV)
+    s_big = m().mol_score(corpus, q["F"], q["gu"], big)
+    for b in (0, 5):
+        for lo, n in ((0, 64), (777, 33), (19_000, 1000)):
+            small = big[b:b + 1, lo:lo + n].contiguous()
+            s_small = m().mol_score(corpus, q["F"][b:b + 1], q["gu"][b:b + 1], small)
+            assert torch.equal(s_small[0], s_big[b, lo:lo + n]), (b, lo, n)
+    # stage 1: every score of the full corpus (K' = N: one big scan) vs the scan of a 64-item slice of it (one wavefront busy)
+    ci, cs, cc = m().hindexer_topk(corpus, q["q1"], wl.N)
+    small_corpus = m().mol_corpus_pack(items["x1"][:64].contiguous(), items["G"][:64].contiguous(), items["gx"][:64].contiguous(),
+                                       gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u)
+    ci2, cs2, cc2 = m().hindexer_topk(small_corpus, q["q1"], 64)
+    torch.cuda.synchronize()
+    for b in range(8):
+        full = dict(zip(ci[b].tolist(), cs[b].tolist()))
+        part = dict(zip(ci2[b].tolist(), cs2[b].tolist()))
+        assert sorted(part) == list(range(64)) and len(full) == wl.N
+        assert all(part[i] == full[i] for i in part)
+    small_corpus.free()
+    corpus.free()
