@@ -52,7 +52,8 @@ enum { MOL_GATE_CONCAT = 0, MOL_GATE_DECOMPOSED = 1 }; /* gate_form */
 /* h-indexer modes */
 #define MOL_HINDEXER_EXACT 0 /* sampled threshold at a deeper rank, exact top-K' of the survivors, exact redo on a miss */
 #define MOL_HINDEXER_PAPER 1 /* Algorithm 2 as written: rank K'*lambda/N, strict filter, at most K' kept */
-#define MOL_HINDEXER_FORCE_REDO 0x100 /* OR into mode: send every query through the exact radix redo (diagnostics, timing of an exact top-K') */
+#define MOL_HINDEXER_FORCE_REDO 0x100 /* OR into mode: send every query through the exact radix redo (diagnostics, timing of an exact top-K');
+                                         the result is that of the mode without the flag */
 
 /*
  * Model description (host struct; read during mol_corpus_pack only).
@@ -67,7 +68,7 @@ enum { MOL_GATE_CONCAT = 0, MOL_GATE_DECOMPOSED = 1 }; /* gate_form */
 typedef struct {
   int64_t N;            /* corpus size */
   int32_t d1;           /* stage-1 embedding width (Section 4.1.1); 0 = no stage-1 table */
-  int32_t stage1_dtype; /* MOL_F32 or MOL_BF16 */
+  int32_t stage1_dtype; /* MOL_F32, MOL_BF16 or MOL_INT8 */
   int32_t k_u, k_x, d_p;
   int32_t d_gu, d_gx, H;
   int32_t act;
@@ -105,8 +106,8 @@ typedef struct {
 } mol_config_t;
 
 /*
- * Build the item-side cache (Section 2.2 "cache item-side gating weights"; the loops marked cachable in
- * Algorithm 1): keeps the stage-1 table [N, d1] and the item component embeddings [N, k_x, d_p] (already
+ * Build the item-side cache (Section 2.2: whatever depends on the item alone is computed once and kept; the loops
+ * marked cachable in Algorithm 1): keeps the stage-1 table [N, d1] and the item component embeddings [N, k_x, d_p] (already
  * L2-normalised by the caller, Eq. 9), and precomputes the item half of the first gating layer,
  * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H] (decomposed gate: the item weights xw, f32 [N, P]).
  *   stage1_items : [N, d1] of stage1_dtype (fp32, bf16 or int8), or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
@@ -148,7 +149,10 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *   lambda      : sample size (a count); <= 0 = hindexer_default_lambda().  Ignored when 4*Kp >= N (no sampling: every
  *                 item passes and the exact top-K' is taken).
  *   mode        : MOL_HINDEXER_PAPER  r = max(1, floor(Kp*lambda/N)); more than K' survivors are cut to the K' best,
- *                                     fewer are returned as they are (cand_count[b] < Kp).
+ *                                     fewer are returned as they are (cand_count[b] < Kp).  A query whose survivors
+ *                                     overflow the workspace lists (items above the threshold packed into a few
+ *                                     neighbouring rows) is redone on the device and gives the same set: the K' best
+ *                                     that lie above t_b.
  *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive (the threshold is
  *                                     the rank-r sampled score resolved to its leading 22 key bits, rounded down), then the exact
  *                                     top-K' of the survivors; a query whose survivors number fewer than K' or overflow the
@@ -190,12 +194,15 @@ mol_status_t mol_gather_items(const mol_corpus_t *corpus, const int32_t *cand_id
 /*
  * Stage 2 with the final selection (Algorithm 1 including its last line): the k best candidates per query.
  *   cand_idx / Kp as in mol_score (NULL = exhaustive MoL over the corpus).
+ *   cand_count: int32 [B] or NULL.  When given (hindexer_topk's output of that name), only the first cand_count[b] slots
+ *               of row b are read -- the rest of the row is neither scored nor gathered, whatever it holds; a negative
+ *               count reads as 0.  NULL = all Kp slots (negative entries are still padding).  Needs cand_idx.
  *   out_idx   : out int32 [B, k] item indices, best first (score desc, index asc); -1 where fewer than k exist.
  *   out_score : out f32 [B, k] their MoL scores (-inf padding).
  */
 mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const void *user_gate, int B,
-                      const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score, void *workspace,
-                      size_t workspace_bytes, void *stream);
+                      const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k, int32_t *out_idx,
+                      float *out_score, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Optional per-kernel timing, for benchmarks.  While enabled, the kernel launches of the calls above are bracketed by

@@ -74,7 +74,7 @@ def load_library() -> C.CDLL:
     lib.hindexer_topk.restype = i32
     lib.mol_score.argtypes = [vp, vp, vp, i32, vp, i32, vp, vp, sz, vp]
     lib.mol_score.restype = i32
-    lib.mol_topk.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.mol_topk.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.mol_topk.restype = i32
     lib.mol_profile_enable.argtypes = [i32]
     lib.mol_profile_enable.restype = i32
@@ -301,7 +301,8 @@ def mol_score(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor,
 
 def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, cand_idx: Optional[torch.Tensor],
              k: int, workspace: Optional[torch.Tensor] = None,
-             out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+             out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+             cand_count: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     lib = load_library()
     _dev(user_embs, corpus.mol_dtype, "user_embs")
     _dev(user_gate, corpus.mol_dtype, "user_gate")
@@ -316,8 +317,12 @@ def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, c
         out = (torch.empty(B, k, dtype=torch.int32, device=user_embs.device),
                torch.empty(B, k, dtype=torch.float32, device=user_embs.device))
     ws = _workspace(lib.mol_workspace_bytes(corpus.handle, B, Kp, k), user_embs.device, workspace)
-    _check(lib.mol_topk(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), Kp, k, _ptr(out[0]),
-                        _ptr(out[1]), _ptr(ws), ws.numel(), _stream()))
+    if cand_count is not None:
+        _dev(cand_count, torch.int32, "cand_count")
+        if cand_count.numel() != B:
+            raise ValueError("cand_count must have B entries")
+    _check(lib.mol_topk(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), _ptr(cand_count), Kp, k,
+                        _ptr(out[0]), _ptr(out[1]), _ptr(ws), ws.numel(), _stream()))
     return out
 
 

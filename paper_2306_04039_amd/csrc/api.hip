@@ -194,7 +194,7 @@ extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, 
   float *UW = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)B * c->H * 4, 256));
   rc = launch_user_gate(c, user_gate, B, U, UW, st);
   if (rc != MOL_OK) return rc;
-  return launch_mol_score(c, user_embs, U, UW, B, cand_idx, Kp, scores, st);
+  return launch_mol_score(c, user_embs, U, UW, B, cand_idx, nullptr, Kp, scores, st);
 }
 
 extern "C" mol_status_t mol_gather_items(const mol_corpus_t *c, const int32_t *cand_idx, int B, int Kp, void *out_embs,
@@ -207,25 +207,44 @@ extern "C" mol_status_t mol_gather_items(const mol_corpus_t *c, const int32_t *c
   return launch_gather_items(c, cand_idx, B, Kp, out_embs, static_cast<hipStream_t>(stream));
 }
 
-extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
-                                 const int32_t *cand_idx, int Kp, int k, int32_t *out_idx, float *out_score,
-                                 void *workspace, size_t workspace_bytes, void *stream) {
+// Argument checks of mol_topk and the size of the workspace it needs.
+static mol_status_t mol_topk_checks(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                    const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k,
+                                    const int32_t *out_idx, const float *out_score, size_t *need) {
   mol_status_t rc = mol_common_checks(c, user_embs, user_gate, B, cand_idx, Kp);
   if (rc != MOL_OK) return rc;
   if (!out_idx || !out_score) return mol_fail(MOL_EINVAL, "out_idx / out_score is NULL");
   if (k < 1 || k > 1024) return mol_fail(MOL_EINVAL, "k=%d must be in [1, 1024]", k);
+  if (cand_count && !cand_idx) return mol_fail(MOL_EINVAL, "cand_count needs cand_idx");
+  *need = mol_ws_layout(c, B, cand_idx ? Kp : c->N, k, nullptr, nullptr);
+  return MOL_OK;
+}
+
+// The three launches of mol_topk on a workspace of mol_ws_layout's shape.
+static mol_status_t mol_topk_run(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                 const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k, int32_t *out_idx,
+                                 float *out_score, char *ws, hipStream_t st) {
   const int64_t row = cand_idx ? Kp : c->N;
   size_t off_scores = 0, off_topk = 0;
-  const size_t need = mol_ws_layout(c, B, row, k, &off_scores, &off_topk);
+  (void)mol_ws_layout(c, B, row, k, &off_scores, &off_topk);
+  float *U = reinterpret_cast<float *>(ws);
+  float *UW = reinterpret_cast<float *>(ws + align_up((size_t)B * c->H * 4, 256));
+  float *scores = reinterpret_cast<float *>(ws + off_scores);
+  mol_status_t rc = launch_user_gate(c, user_gate, B, U, UW, st);
+  if (rc != MOL_OK) return rc;
+  rc = launch_mol_score(c, user_embs, U, UW, B, cand_idx, cand_count, row, scores, st);
+  if (rc != MOL_OK) return rc;
+  return launch_final_topk(scores, cand_idx, cand_count, B, row, k, out_idx, out_score, ws + off_topk, st);
+}
+
+extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                 const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k, int32_t *out_idx,
+                                 float *out_score, void *workspace, size_t workspace_bytes, void *stream) {
+  size_t need = 0;
+  mol_status_t rc = mol_topk_checks(c, user_embs, user_gate, B, cand_idx, cand_count, Kp, k, out_idx, out_score, &need);
+  if (rc != MOL_OK) return rc;
   rc = check_ws(workspace, workspace_bytes, need);
   if (rc != MOL_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  float *U = static_cast<float *>(workspace);
-  float *UW = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)B * c->H * 4, 256));
-  float *scores = reinterpret_cast<float *>(static_cast<char *>(workspace) + off_scores);
-  rc = launch_user_gate(c, user_gate, B, U, UW, st);
-  if (rc != MOL_OK) return rc;
-  rc = launch_mol_score(c, user_embs, U, UW, B, cand_idx, row, scores, st);
-  if (rc != MOL_OK) return rc;
-  return launch_final_topk(scores, cand_idx, B, row, k, out_idx, out_score, static_cast<char *>(workspace) + off_topk, st);
+  return mol_topk_run(c, user_embs, user_gate, B, cand_idx, cand_count, Kp, k, out_idx, out_score,
+                      static_cast<char *>(workspace), static_cast<hipStream_t>(stream));
 }

@@ -177,9 +177,10 @@ mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, 
 // U [B, H] and (decomposed gate) UW [B, P]: the per-query inputs of the scoring kernel
 mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, hipStream_t st);
 mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
-                              const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st);
+                              const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp, float *scores,
+                              hipStream_t st);
 mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, int B, int64_t Kp, void *out, hipStream_t st);
 // select.hip
 size_t final_topk_workspace_bytes(int B, int64_t Kp, int k);
-mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
-                               int32_t *out_idx, float *out_score, char *ws, hipStream_t st);
+mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, const int32_t *cand_count, int B, int64_t Kp,
+                               int k, int32_t *out_idx, float *out_score, char *ws, hipStream_t st);

@@ -34,6 +34,7 @@ struct MolArgs {
   const float *xw;       // decomposed gate: f32 [N, P] cached item weights
   const float *UW;       // decomposed gate: f32 [B, P] user weights
   const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
+  const int32_t *cand_count;  // [B] or nullptr: only the first cand_count[b] slots of row b are candidates
   float *scores;         // [B, Kp]
   int64_t Kp;            // row length of cand / scores
   int64_t N;
@@ -125,7 +126,8 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   auto task_cand = [&](int64_t t) -> int {
     const int tb = (int)(t / tpq);
     const int64_t tc = ((t % tpq) << 5) + c;
-    return tc < a.Kp ? (a.cand ? a.cand[(size_t)tb * a.Kp + tc] : (int)tc) : -1;
+    const int64_t row_len = a.cand_count ? (int64_t)a.cand_count[tb] : a.Kp;
+    return tc < a.Kp && tc < row_len ? (a.cand ? a.cand[(size_t)tb * a.Kp + tc] : (int)tc) : -1;
   };
   int idx_n = -1, idxc_n = 0;
   bool primed = false;
@@ -520,7 +522,8 @@ static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, 
 }
 
 mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
-                              const int32_t *cand_idx, int64_t Kp, float *scores, hipStream_t st) {
+                              const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp, float *scores,
+                              hipStream_t st) {
   MolArgs a;
   a.embs = static_cast<const char *>(c->embs);
   a.xi = static_cast<const char *>(c->xi);
@@ -532,6 +535,7 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.xw = c->xw;
   a.UW = UW;
   a.cand = cand_idx;
+  a.cand_count = cand_idx ? cand_count : nullptr;
   a.scores = scores;
   a.Kp = cand_idx ? Kp : c->N;
   a.N = c->N;

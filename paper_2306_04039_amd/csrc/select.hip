@@ -13,14 +13,16 @@ namespace {
 // With k much smaller than the row (k = 100 of K' = 1e5) the k best of the row are among the k best of each of G slices,
 // so G workgroups per query cut the row to G*k staged candidates in one pass over it, and one workgroup per query
 // finishes.  Staged rows are (score, item index) pairs, unordered, padded with (-inf, -1).
-__global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores, const int32_t *cand, int64_t Kp, int k,
+__global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores, const int32_t *cand,
+                                                             const int32_t *cand_count, int64_t Kp, int k,
                                                              float *st_score, int32_t *st_idx) {
   __shared__ SelectShared sh;
   const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
   const int tid = threadIdx.x;
   const int64_t per = (Kp + G - 1) / G;
   const int64_t lo = (int64_t)g * per;
-  const int64_t n = lo >= Kp ? 0 : (lo + per <= Kp ? per : Kp - lo);
+  const int64_t row = (cand_count && cand_count[b] < Kp) ? (cand_count[b] < 0 ? 0 : cand_count[b]) : Kp;  // slots in use
+  const int64_t n = lo >= row ? 0 : (lo + per <= row ? per : row - lo);
   const float *sc = scores + (size_t)b * Kp + lo;
   const int32_t *ci = cand ? cand + (size_t)b * Kp + lo : nullptr;
   float *os = st_score + ((size_t)b * G + g) * k;
@@ -51,9 +53,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
 }
 
 // ---- one workgroup per query: radix select of the k-th element, then a sort of the k winners -----------------------
-__global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scores, const int32_t *cand, int64_t Kp,
-                                                               int k, int nsort, int32_t *out_idx,
-                                                               float *out_score) {
+__global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scores, const int32_t *cand,
+                                                               const int32_t *cand_count, int64_t Kp, int k, int nsort,
+                                                               int32_t *out_idx, float *out_score) {
   __shared__ SelectShared sh;
   __shared__ uint32_t skey[TOPK_MAX];
   __shared__ uint32_t sidx[TOPK_MAX];
@@ -61,8 +63,9 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
   const int tid = threadIdx.x;
   const float *sc = scores + (size_t)b * Kp;
   const int32_t *ci = cand ? cand + (size_t)b * Kp : nullptr;
+  const int64_t row = (cand_count && cand_count[b] < Kp) ? (cand_count[b] < 0 ? 0 : cand_count[b]) : Kp;  // slots in use
   auto each = [&](auto f) {
-    block_for_each<4>(sc, Kp, [&](int64_t i, float v) {
+    block_for_each<4>(sc, row, [&](int64_t i, float v) {
       const int32_t id = ci ? ci[i] : (int32_t)i;
       if (id >= 0) f(f32_to_key(v), (uint32_t)id);
     });
@@ -129,8 +132,8 @@ size_t final_topk_workspace_bytes(int B, int64_t Kp, int k) {
   return G > 1 ? 2 * align_up((size_t)B * G * k * 4, 256) : 0;
 }
 
-mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int B, int64_t Kp, int k,
-                               int32_t *out_idx, float *out_score, char *ws, hipStream_t st) {
+mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, const int32_t *cand_count, int B, int64_t Kp,
+                               int k, int32_t *out_idx, float *out_score, char *ws, hipStream_t st) {
   if (k > TOPK_MAX) return mol_fail(MOL_EUNSUPPORTED, "k=%d exceeds the supported maximum %d", k, TOPK_MAX);
   ProfScope ps(MOL_PROF_FINAL_TOPK, st);
   int nsort = 64;
@@ -139,13 +142,16 @@ mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, int
   if (G > 1) {
     float *st_score = reinterpret_cast<float *>(ws);
     int32_t *st_idx = reinterpret_cast<int32_t *>(ws + align_up((size_t)B * G * k * 4, 256));
-    hipLaunchKernelGGL(k_seg_topk, dim3(G, B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, Kp, k, st_score, st_idx);
+    hipLaunchKernelGGL(k_seg_topk, dim3(G, B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, cand_count, Kp, k, st_score,
+                       st_idx);
     HIP_TRY(hipGetLastError());
     scores = st_score;
     cand_idx = st_idx;
+    cand_count = nullptr;
     Kp = (int64_t)G * k;
   }
-  hipLaunchKernelGGL(k_final_topk, dim3(B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, Kp, k, nsort, out_idx, out_score);
+  hipLaunchKernelGGL(k_final_topk, dim3(B), dim3(SELECT_THREADS), 0, st, scores, cand_idx, cand_count, Kp, k, nsort, out_idx,
+                     out_score);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }

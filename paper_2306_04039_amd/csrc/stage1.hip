@@ -91,6 +91,7 @@ struct ScanArgs {
   uint32_t *hist;           // exact redo: [B][EXACT_BINS] digit histogram
   const uint32_t *gate;     // exact redo: the kernel returns at once when *gate == 0
   int shift;                // exact redo: bit position of the digit
+  int paper;                // FILTER_EXACT: Algorithm 2 as written -- of the K' best only those above the sampled threshold are kept
 };
 
 // One step of the exact redo, run for query b by the 256 threads of the last workgroup of a histogram scan to finish:
@@ -210,6 +211,7 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
     for (int ci = 0; ci < NCH; ++ci)
       q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
     thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
+    if constexpr (EPI == EPI_FILTER_EXACT) thr[g] = (a.paper && b < a.B) ? a.thr[b] : -INFINITY;
     st_active[g] = 0;
     cnt[g] = 0;
     lst[g] = nullptr;
@@ -338,9 +340,10 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
             for (int j = 0; j < 16; ++j) {
               const int64_t n = row0 + 8 * (j >> 2) + (j & 3);
               const uint32_t k = f32_to_key(acc[g][j]);
-              if ((k > st_tkey[g] || (k == st_tkey[g] && (uint32_t)n <= st_ilim[g])) && n < a.n_rows) {
+              if ((k > st_tkey[g] || (k == st_tkey[g] && (uint32_t)n <= st_ilim[g])) && n < a.n_rows &&
+                  acc[g][j] > thr[g]) {
                 const uint32_t slot = atomicAdd(&a.state[b].emitted, 1u);
-                if (slot < (uint32_t)a.Kp) {  // exactly K' items qualify; the check only guards the buffer
+                if (slot < (uint32_t)a.Kp) {  // at most K' items qualify; the check only guards the buffer
                   a.out_idx[(size_t)b * a.Kp + slot] = (int32_t)n;
                   if (a.out_score) a.out_score[(size_t)b * a.Kp + slot] = key_to_f32(k);
                 }
@@ -398,22 +401,21 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
     }
   }
   if constexpr (EPI == EPI_FILTER_EXACT) {
-    // the last workgroup closes the redo: a redone query holds exactly K' candidates; anything else (a threshold that
-    // was never resolved, a count that is not K') is reported as cand_count = -1 with an empty row
+    // the last workgroup closes the redo: a redone query holds exactly K' candidates (Algorithm 2 as written: those of
+    // the K' best that lie above the sampled threshold, so possibly fewer; the unused slots are padded); anything else
+    // (a threshold that was never resolved, a count that does not fit) is reported as cand_count = -1 with an empty row
     if (last_workgroup(a.gate_rw + 2)) {
       for (int b = a.qbase; b < a.B && b < a.qbase + 32 * NQG; ++b) {
         if (a.flags[b] == 0u) continue;  // not redone
         const uint32_t emitted = __hip_atomic_load(&a.state[b].emitted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool ok = a.state[b].active == 3u && emitted == (uint32_t)a.Kp;
-        if (!ok) {
-          for (int i = threadIdx.x; i < a.Kp; i += 256) {
-            a.out_idx[(size_t)b * a.Kp + i] = -1;
-            if (a.out_score) a.out_score[(size_t)b * a.Kp + i] = -INFINITY;
-          }
+        const bool ok = a.state[b].active == 3u && (a.paper ? emitted <= (uint32_t)a.Kp : emitted == (uint32_t)a.Kp);
+        for (int i = (ok ? (int)emitted : 0) + threadIdx.x; i < a.Kp; i += 256) {
+          a.out_idx[(size_t)b * a.Kp + i] = -1;
+          if (a.out_score) a.out_score[(size_t)b * a.Kp + i] = -INFINITY;
         }
         __syncthreads();
         if (threadIdx.x == 0) {
-          a.out_count[b] = ok ? a.Kp : -1;
+          a.out_count[b] = ok ? (int32_t)emitted : -1;
           a.flags[b] = ok ? 0u : 3u;
         }
       }
@@ -1041,6 +1043,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     if (rc != MOL_OK) return rc;
   }
   a.gate = gate;
+  a.paper = (mode == MOL_HINDEXER_PAPER && p.sampling) ? 1 : 0;
   rc = launch_scan_dt<EPI_FILTER_EXACT, false>(dt, a, B, 0, st);
   if (rc != MOL_OK) return rc;
   return MOL_OK;
