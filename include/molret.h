@@ -205,6 +205,27 @@ mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const v
                       float *out_score, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * mol_topk for callers that cannot allocate device memory or supply a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as mol_topk, minus the workspace:
+ * the per-query gate inputs, the [B, Kp] score matrix and the staging of the final selection live in a static device
+ * array of MOL_TOPK_STATIC_MAX_BYTES that every GPU the library runs on holds until the process ends.
+ *   - Calls nothing that allocates (no hipMalloc / hipFree, no library allocation); enqueues on `stream` and returns.
+ *   - MOL_EWORKSPACE when mol_workspace_bytes(corpus, B, Kp, k) exceeds MOL_TOPK_STATIC_MAX_BYTES (the 100M-item
+ *     workload, B = 32, Kp = 100000, k = 100, needs 13.1 MB); nothing is enqueued then.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap (different streams, or one stream
+ *     captured into graphs replayed concurrently) race; callers serialise them.  The contents left by one call are never
+ *     read by the next (every buffer is written in full before it is read), so nothing needs clearing between calls.
+ *   - The array's device address is looked up on the first call on each device (hipGetSymbolAddress, which may load
+ *     the code object); mol_static_init() does the lookup for the current device ahead of time, e.g. before a capture.
+ */
+#define MOL_TOPK_STATIC_MAX_BYTES (16u << 20)
+mol_status_t mol_static_init(void);
+size_t mol_topk_static_max_bytes(void);
+mol_status_t mol_topk_static(const mol_corpus_t *corpus, const void *user_embs, const void *user_gate, int B,
+                             const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k, int32_t *out_idx,
+                             float *out_score, void *stream);
+
+/*
  * Optional per-kernel timing, for benchmarks.  While enabled, the kernel launches of the calls above are bracketed by
  * HIP events on the caller's stream (each bracket costs about 10 microseconds of idle device time).  mol_profile_read
  * synchronises on the recorded events, adds up the elapsed time per slot since the last read and clears the record.

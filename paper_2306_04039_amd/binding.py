@@ -21,6 +21,7 @@ EXPORTS = (
     "mol_corpus_pack", "mol_corpus_free", "hindexer_workspace_bytes", "mol_workspace_bytes",
     "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
     "mol_profile_enable", "mol_profile_read", "mol_quantize_int8", "mol_gather_items",
+    "mol_topk_static", "mol_static_init", "mol_topk_static_max_bytes",
 )
 
 PROF_SLOTS = ("sample_scores", "threshold", "scan_filter", "select", "user_gate", "mol_score", "final_topk", "spare")
@@ -76,6 +77,12 @@ def load_library() -> C.CDLL:
     lib.mol_score.restype = i32
     lib.mol_topk.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.mol_topk.restype = i32
+    lib.mol_topk_static.argtypes = [vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp]
+    lib.mol_topk_static.restype = i32
+    lib.mol_static_init.argtypes = []
+    lib.mol_static_init.restype = i32
+    lib.mol_topk_static_max_bytes.argtypes = []
+    lib.mol_topk_static_max_bytes.restype = sz
     lib.mol_profile_enable.argtypes = [i32]
     lib.mol_profile_enable.restype = i32
     lib.mol_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
@@ -323,6 +330,39 @@ def mol_topk(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, c
             raise ValueError("cand_count must have B entries")
     _check(lib.mol_topk(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), _ptr(cand_count), Kp, k,
                         _ptr(out[0]), _ptr(out[1]), _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
+def static_init() -> None:
+    _check(load_library().mol_static_init())
+
+
+def topk_static_max_bytes() -> int:
+    return int(load_library().mol_topk_static_max_bytes())
+
+
+def mol_topk_static(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Tensor, cand_idx: Optional[torch.Tensor],
+                    k: int, out: Tuple[torch.Tensor, torch.Tensor], cand_count: Optional[torch.Tensor] = None
+                    ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """mol_topk on the library's static workspace: the caller brings the outputs, nothing is allocated here or below."""
+    lib = load_library()
+    _dev(user_embs, corpus.mol_dtype, "user_embs")
+    _dev(user_gate, corpus.mol_dtype, "user_gate")
+    B = user_embs.shape[0]
+    if tuple(user_embs.shape[1:]) != (corpus.k_u, corpus.d_p) or tuple(user_gate.shape) != (B, corpus.d_gu):
+        raise ValueError("user tensor shapes do not match the corpus")
+    Kp = 0
+    if cand_idx is not None:
+        _dev(cand_idx, torch.int32, "cand_idx")
+        Kp = cand_idx.shape[1]
+    if cand_count is not None:
+        _dev(cand_count, torch.int32, "cand_count")
+    _dev(out[0], torch.int32, "out_idx")
+    _dev(out[1], torch.float32, "out_score")
+    if tuple(out[0].shape) != (B, k) or tuple(out[1].shape) != (B, k):
+        raise ValueError("out tensors must be [B, k]")
+    _check(lib.mol_topk_static(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), _ptr(cand_count), Kp, k,
+                               _ptr(out[0]), _ptr(out[1]), _stream()))
     return out
 
 

@@ -248,3 +248,57 @@ extern "C" mol_status_t mol_topk(const mol_corpus_t *c, const void *user_embs, c
   return mol_topk_run(c, user_embs, user_gate, B, cand_idx, cand_count, Kp, k, out_idx, out_score,
                       static_cast<char *>(workspace), static_cast<hipStream_t>(stream));
 }
+
+// ------------------------------------------------------------------------------------------------ no-allocation variant
+// mol_topk for callers that cannot allocate (HIP graph capture, tight serving loops): the workspace of mol_topk -- U, UW,
+// the [B, Kp] score matrix and the staging of the two-level selection -- lives in a file-scope device array.  Each GPU
+// holds its own copy of the array at its own address; the address is looked up once per device and only that pointer is
+// ever handed to kernels (the array's name is a host-side stand-in, not a device address).
+static __device__ __align__(256) unsigned char scratch[MOL_TOPK_STATIC_MAX_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+// Device address of `scratch` on the current device (resolved on the first call per device).
+static mol_status_t scratch_for_current_device(unsigned char **out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return mol_fail(MOL_EUNSUPPORTED, "device ordinal %d is beyond %d", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return mol_fail(MOL_EHIP, "hipGetSymbolAddress returned a null address for the static workspace");
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return MOL_OK;
+}
+
+extern "C" mol_status_t mol_static_init(void) {
+  unsigned char *p = nullptr;
+  return scratch_for_current_device(&p);
+}
+
+extern "C" size_t mol_topk_static_max_bytes(void) { return MOL_TOPK_STATIC_MAX_BYTES; }
+
+extern "C" mol_status_t mol_topk_static(const mol_corpus_t *c, const void *user_embs, const void *user_gate, int B,
+                                        const int32_t *cand_idx, const int32_t *cand_count, int Kp, int k,
+                                        int32_t *out_idx, float *out_score, void *stream) {
+  size_t need = 0;
+  mol_status_t rc = mol_topk_checks(c, user_embs, user_gate, B, cand_idx, cand_count, Kp, k, out_idx, out_score, &need);
+  if (rc != MOL_OK) return rc;
+  if (need > MOL_TOPK_STATIC_MAX_BYTES)
+    return mol_fail(MOL_EWORKSPACE, "mol_topk_static: B=%d, row length %lld, k=%d need %zu bytes of workspace, the static one has %zu",
+                    B, (long long)(cand_idx ? Kp : c->N), k, need, (size_t)MOL_TOPK_STATIC_MAX_BYTES);
+  unsigned char *ws = nullptr;
+  rc = scratch_for_current_device(&ws);
+  if (rc != MOL_OK) return rc;
+  // nothing in the workspace has to start at zero: U, UW, the scores and the staged candidates are all written in full by
+  // the kernels before they are read, so what an earlier call left behind is never seen
+  return mol_topk_run(c, user_embs, user_gate, B, cand_idx, cand_count, Kp, k, out_idx, out_score,
+                      reinterpret_cast<char *>(ws), static_cast<hipStream_t>(stream));
+}
