@@ -32,7 +32,9 @@ to one and phi lies between the smallest and largest component logit, a uniform 
 logit in closed form, a user-only gate reproduces Eq. 5 through a different evaluation order, one-hot
 gates expose the component index order, softmax shift invariance, a loop-by-loop re-derivation,
 K' = N two-stage equals exhaustive MoL, corpus permutation and batch-split invariance; INT8 quantisation against
-exact rational round-half-even on dyadic scales and hand-worked cases, INT8 scores against Python integers;
+exact rational round-half-even on dyadic scales, hand-worked cases and hand-built values that separate "round the fp32
+product" from "round the exact product" (the rule itself is the library's contract -- parity unpinned against the
+paper, which gives no scheme), INT8 scores against Python integers;
 Algorithm 1's decomposed gate: distribution / convexity, P = 1, all-zero heads give the mean logit, constant heads in
 the two SiLU limits (softmax of the product; uniform), one-hot selection, scalar-loop re-derivation.
 The recall level of the approximate (sampled) mode is "parity unpinned": the paper's recall figure
@@ -93,9 +95,12 @@ def nth_largest(values: np.ndarray, r: int) -> float:
 
 # --------------------------------------------------------------------------- stage 1
 def quantize_int8(x: np.ndarray, scale: float) -> np.ndarray:
-    """INT8 stage-1 vectors (Section 4.1.1).  The paper gives no scheme; the reading taken is the plain symmetric one
-    with one scale per tensor: q = clamp(round_half_even(x * scale), -127, 127).  The product decides an integer, so it
-    is taken in the precision the kernel uses: both factors in fp32, one fp32 rounding, then the rounding to integer."""
+    """INT8 stage-1 vectors.  Section 4.1.1 names INT8 operands but no quantisation scheme, so this function is defined
+    by the library's documented contract (its header), not by the paper: symmetric, one scale per tensor,
+    q = clamp(round_half_even(fl32(x * scale)), -127, 127), where fl32 is ONE rounding of the product of the two fp32
+    factors to fp32.  Rounding the product first matters only when the exact product lies within half an fp32 ulp of a
+    half-integer; a pin separates the two rules on hand-built values.  PARITY UNPINNED against the paper for scales
+    that are not powers of two: nothing in the paper fixes which of the two rules (or any other scheme) is meant."""
     xf = as_f64(x).astype(np.float32)                     # bf16 / fp32 inputs: exact
     t = (xf * np.float32(scale)).astype(np.float32)       # fp32 * fp32 -> fp32, rounded once
     return np.clip(np.rint(t), -127.0, 127.0).astype(np.int8)   # rint: halves to even

@@ -435,6 +435,34 @@ def test_quantize_int8_matches_exact_rational_rounding_on_dyadic_scales():
         assert np.array_equal(got, orc.quantize_int8(xs.astype(np.float32), scale))               # bf16 bits == fp32 path
 
 
+def test_quantize_int8_rounds_the_fp32_product_not_the_exact_one():
+    """The contract (the library header's: the product x * scale is rounded once to fp32, then halves go to even)
+    differs from rounding the exact product when the exact product sits just off a half-integer and its fp32 rounding
+    lands on it.  Hand-built fp32 inputs for scale = fp32(311.7) = 0x1.37b334p+8; the exact products are taken with
+    rationals, the fp32 ones follow from them by hand: each is within half an fp32 ulp of k + 1/2."""
+    from fractions import Fraction
+    scale = float(np.float32(311.7))
+    assert scale.hex() == "0x1.37b3340000000p+8"
+    cases = [
+        # (x as fp32 hex, k + 1/2 the fp32 product lands on, code by the contract, code if the exact product were rounded)
+        ("-0x1.10ac240000000p-3", -41.5, -42, -41),   # exact magnitude just below 41.5: contract ties to even 42
+        ("0x1.58f2720000000p-3", 52.5, 52, 53),       # exact just above 52.5: contract ties to even 52
+        ("0x1.71960c0000000p-2", 112.5, 112, 112),    # exact below 112.5, and 112 is the even neighbour: both agree
+        ("-0x1.e97f0e0000000p-3", -74.5, -74, -75),   # exact magnitude just above 74.5: contract ties to even 74
+    ]
+    for xhex, half, by_contract, by_exact in cases:
+        x = float.fromhex(xhex)
+        assert float(np.float32(x)) == x                                  # the input is an fp32 value
+        exact = Fraction(x) * Fraction(scale)
+        assert exact != Fraction(half)
+        ulp = Fraction(1, 2**(23 - int(np.floor(np.log2(abs(half))))))
+        assert abs(exact - Fraction(half)) < ulp / 2                      # so the fp32 product is exactly k + 1/2
+        assert round(exact) == by_exact                                   # Fraction.round: nearest, halves to even
+        assert round(Fraction(half)) == by_contract
+        got = int(orc.quantize_int8(np.array([x], dtype=np.float32), scale)[0])
+        assert got == by_contract, (xhex, got)
+
+
 def test_quantize_int8_is_monotone_and_within_half_a_step():
     rng = np.random.default_rng(6)
     x = np.sort(rng.uniform(-1, 1, size=2000).astype(np.float32))
