@@ -12,8 +12,8 @@ What it follows (paper sections, in the paper's notation):
   * the sampled threshold: Algorithm 2 (sample, nthElement at rank k/|data| * lambda, strict >),
     Section 4.1.2 for "up to k' items that meet the threshold".
   * component logits: Eq. 6 (all k_u x k_x pairwise dot products), Eq. 9 (division by tau, applied
-    here as multiplication by logit_scale = 1/tau), Algorithm 1 (mm, then view/permute that makes
-    the component index user-major: p = ku * k_x + kx).
+    here as multiplication by logit_scale = 1/tau); the component index is user-major,
+    p = ku * k_x + kx, the order Algorithm 1 hands the logits to the gate in.
   * gating: Eq. 8 / Section 3.2 (a network of item-side, user-side and cross inputs whose output is
     a probability distribution over the k_u*k_x components, Section 3.2 last paragraph), in the
     concrete form of the benchmark workloads: a 2-layer MLP on [component logits || user gate
@@ -180,15 +180,18 @@ def _act(x: np.ndarray, act: str) -> np.ndarray:
 
 
 def component_logits(F_b: np.ndarray, G_rows: np.ndarray, logit_scale: float) -> np.ndarray:
-    """cl[c, ku*k_x + kx] = logit_scale * <F_b[ku], G_rows[c, kx]>   (Eq. 6, Eq. 9, Algorithm 1).
+    """cl[c, p] = logit_scale * <F_b[ku], G_rows[c, kx]> for every pair (ku, kx)   (Eq. 6; Eq. 9 with 1/tau = logit_scale).
 
-    F_b [k_u, d], G_rows [n, k_x, d] (fp64).  Written as Algorithm 1 does: one matrix product of the
-    user embeddings with all item embeddings, then the view/permute to (n, k_u*k_x).
+    F_b [k_u, d], G_rows [n, k_x, d] (fp64).  The component index is user-major, p = ku * k_x + kx: the order in which
+    Algorithm 1 lays the k_u * k_x logits of one item out before they enter the gate.
     """
-    k_u, d = F_b.shape
+    k_u, _ = F_b.shape
     n, k_x, _ = G_rows.shape
-    cl = (F_b @ G_rows.reshape(n * k_x, d).T) * logit_scale       # (k_u, n*k_x)
-    return cl.reshape(k_u, n, k_x).transpose(1, 0, 2).reshape(n, k_u * k_x)
+    cl = np.empty((n, k_u * k_x), dtype=np.float64)
+    for ku in range(k_u):
+        for kx in range(k_x):
+            cl[:, ku * k_x + kx] = logit_scale * (G_rows[:, kx, :] @ F_b[ku])
+    return cl
 
 
 def gating_weights(cl: np.ndarray, gu_b: np.ndarray, gx_rows: np.ndarray, W1: np.ndarray, b1: np.ndarray,
