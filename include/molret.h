@@ -246,6 +246,20 @@ enum {
 mol_status_t mol_profile_enable(int on);
 mol_status_t mol_profile_read(double *slot_ms, int *slot_launches);
 
+/*
+ * Memory-system ceilings, for benchmarks (no arithmetic; nothing is written): the time these take is what the device
+ * delivers to any kernel that has to move the same bytes.
+ *   mol_bench_stream_read : reads `bytes` (a multiple of 16) from p once, front to back, with `blocks` workgroups of 256
+ *                           threads -- the traffic of the stage-1 corpus scan (Section 4.1.1).
+ *   mol_bench_gather      : for every candidate of cand_idx [B, Kp] reads the item's embedding block and cached gate row
+ *                           with the lane-to-address mapping of the scoring kernel (Section 4.1.3) -- the traffic of
+ *                           mol_score.  Negative / out-of-range ids read item 0.
+ *   sink : device, 4 bytes, never written in practice (it keeps the loads alive).
+ */
+mol_status_t mol_bench_stream_read(const void *p, size_t bytes, int blocks, void *sink, void *stream);
+mol_status_t mol_bench_gather(const mol_corpus_t *corpus, const int32_t *cand_idx, int B, int Kp, int blocks, void *sink,
+                              void *stream);
+
 /* Message for the last non-OK status returned on this thread (host string, valid until the next call). */
 const char *mol_last_error(void);
 

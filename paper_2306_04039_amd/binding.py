@@ -22,6 +22,7 @@ EXPORTS = (
     "hindexer_default_lambda", "hindexer_topk", "mol_score", "mol_topk", "mol_last_error",
     "mol_profile_enable", "mol_profile_read", "mol_quantize_int8", "mol_gather_items",
     "mol_topk_static", "mol_static_init", "mol_topk_static_max_bytes",
+    "mol_bench_stream_read", "mol_bench_gather",
 )
 
 PROF_SLOTS = ("sample_scores", "threshold", "scan_filter", "select", "user_gate", "mol_score", "final_topk", "spare")
@@ -83,6 +84,10 @@ def load_library() -> C.CDLL:
     lib.mol_static_init.restype = i32
     lib.mol_topk_static_max_bytes.argtypes = []
     lib.mol_topk_static_max_bytes.restype = sz
+    lib.mol_bench_stream_read.argtypes = [vp, sz, i32, vp, vp]
+    lib.mol_bench_stream_read.restype = i32
+    lib.mol_bench_gather.argtypes = [vp, vp, i32, i32, i32, vp, vp]
+    lib.mol_bench_gather.restype = i32
     lib.mol_profile_enable.argtypes = [i32]
     lib.mol_profile_enable.restype = i32
     lib.mol_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int)]
@@ -364,6 +369,19 @@ def mol_topk_static(corpus: Corpus, user_embs: torch.Tensor, user_gate: torch.Te
     _check(lib.mol_topk_static(corpus.handle, _ptr(user_embs), _ptr(user_gate), B, _ptr(cand_idx), _ptr(cand_count), Kp, k,
                                _ptr(out[0]), _ptr(out[1]), _stream()))
     return out
+
+
+def bench_stream_read(t: torch.Tensor, blocks: int, sink: torch.Tensor) -> None:
+    """Read-only sweep over t's bytes (benchmark ceiling of the corpus scan)."""
+    nbytes = t.numel() * t.element_size() // 16 * 16
+    _check(load_library().mol_bench_stream_read(_ptr(t), nbytes, blocks, _ptr(sink), _stream()))
+
+
+def bench_gather(corpus: Corpus, cand_idx: torch.Tensor, blocks: int, sink: torch.Tensor) -> None:
+    """Bare gather with the scoring kernel's access pattern (benchmark ceiling of mol_score)."""
+    _dev(cand_idx, torch.int32, "cand_idx")
+    B, Kp = cand_idx.shape
+    _check(load_library().mol_bench_gather(corpus.handle, _ptr(cand_idx), B, Kp, blocks, _ptr(sink), _stream()))
 
 
 def profile_enable(on, slots=None) -> None:

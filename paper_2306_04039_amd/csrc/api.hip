@@ -116,9 +116,14 @@ extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp,
   return p0.total > p1.total ? p0.total : p1.total;
 }
 
-// U [B, H] followed by UW [B, P] (the per-query inputs of the scoring kernel)
+// U [B, H], UW [B, P], UP [B, H] (the per-query inputs of the scoring kernels)
 static size_t mol_user_bytes(const mol_corpus_t *c, int B) {
-  return align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256);
+  return 2 * align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256);
+}
+static void mol_user_ptrs(const mol_corpus_t *c, int B, char *ws, float **U, float **UW, uint32_t **UP) {
+  *U = reinterpret_cast<float *>(ws);
+  *UW = reinterpret_cast<float *>(ws + align_up((size_t)B * c->H * 4, 256));
+  *UP = reinterpret_cast<uint32_t *>(ws + align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256));
 }
 
 static size_t mol_ws_layout(const mol_corpus_t *c, int B, int64_t row, int k, size_t *off_scores, size_t *off_topk) {
@@ -190,11 +195,13 @@ extern "C" mol_status_t mol_score(const mol_corpus_t *c, const void *user_embs, 
   rc = check_ws(workspace, workspace_bytes, need);
   if (rc != MOL_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  float *U = static_cast<float *>(workspace);
-  float *UW = reinterpret_cast<float *>(static_cast<char *>(workspace) + align_up((size_t)B * c->H * 4, 256));
-  rc = launch_user_gate(c, user_gate, B, U, UW, st);
+  float *U, *UW;
+  uint32_t *UP;
+  mol_user_ptrs(c, B, static_cast<char *>(workspace), &U, &UW, &UP);
+  if (cand_idx || !mol_exh_fast_form(c)) UP = nullptr;
+  rc = launch_user_gate(c, user_gate, B, U, UW, UP, st);
   if (rc != MOL_OK) return rc;
-  return launch_mol_score(c, user_embs, U, UW, B, cand_idx, nullptr, Kp, scores, st);
+  return launch_mol_score(c, user_embs, U, UW, UP, B, cand_idx, nullptr, Kp, scores, st);
 }
 
 extern "C" mol_status_t mol_gather_items(const mol_corpus_t *c, const int32_t *cand_idx, int B, int Kp, void *out_embs,
@@ -227,12 +234,14 @@ static mol_status_t mol_topk_run(const mol_corpus_t *c, const void *user_embs, c
   const int64_t row = cand_idx ? Kp : c->N;
   size_t off_scores = 0, off_topk = 0;
   (void)mol_ws_layout(c, B, row, k, &off_scores, &off_topk);
-  float *U = reinterpret_cast<float *>(ws);
-  float *UW = reinterpret_cast<float *>(ws + align_up((size_t)B * c->H * 4, 256));
+  float *U, *UW;
+  uint32_t *UP;
+  mol_user_ptrs(c, B, ws, &U, &UW, &UP);
+  if (cand_idx || !mol_exh_fast_form(c)) UP = nullptr;
   float *scores = reinterpret_cast<float *>(ws + off_scores);
-  mol_status_t rc = launch_user_gate(c, user_gate, B, U, UW, st);
+  mol_status_t rc = launch_user_gate(c, user_gate, B, U, UW, UP, st);
   if (rc != MOL_OK) return rc;
-  rc = launch_mol_score(c, user_embs, U, UW, B, cand_idx, cand_count, row, scores, st);
+  rc = launch_mol_score(c, user_embs, U, UW, UP, B, cand_idx, cand_count, row, scores, st);
   if (rc != MOL_OK) return rc;
   return launch_final_topk(scores, cand_idx, cand_count, B, row, k, out_idx, out_score, ws + off_topk, st);
 }

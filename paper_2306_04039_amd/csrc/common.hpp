@@ -122,6 +122,8 @@ struct mol_corpus {
   void *xi;             // bf16 [N, H]   item half of gating layer 1 (+ b1)
   void *w1c_frag;       // bf16, MFMA fragment order, [H/32][P/16][64][8]
   void *w2_frag;        // bf16, MFMA fragment order, [ceil(P/32)][H/16][64][8]
+  void *w1c_frag_h;     // the same two fragment buffers as IEEE half (bf16 -> half is exact for |w| >= 2^-14); they alias
+  void *w2_frag_h;      // the buffers above when the corpus is half already
   void *w1u;            // bf16 [H, d_gu] row-major (user part of layer 1)
   float *b2;            // f32 [32*ceil(P/32)] (padded with zeros)
   bool own_stage1, own_embs;
@@ -175,10 +177,13 @@ mol_status_t launch_item_gate_cache(const mol_corpus *c, const void *item_gate, 
                                     const float *b1, hipStream_t st);
 // mol.hip
 // U [B, H] and (decomposed gate) UW [B, P]: the per-query inputs of the scoring kernel
-mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, hipStream_t st);
-mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
-                              const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp, float *scores,
+// UP [B, H] (may be NULL): U as half head | half remainder << 16, read by the exhaustive fast form only
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, uint32_t *UP,
                               hipStream_t st);
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW,
+                              const uint32_t *UP, int B, const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp,
+                              float *scores, hipStream_t st);
+bool mol_exh_fast_form(const mol_corpus *c);
 mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, int B, int64_t Kp, void *out, hipStream_t st);
 // select.hip
 size_t final_topk_workspace_bytes(int B, int64_t Kp, int k);

@@ -33,6 +33,9 @@ struct MolArgs {
   const float *U;        // f32 [B, H]   per-query additive term of layer 1 (user part; for the decomposed gate just b1)
   const float *xw;       // decomposed gate: f32 [N, P] cached item weights
   const float *UW;       // decomposed gate: f32 [B, P] user weights
+  const char *w1c_frag_h;   // the layer-1 / layer-2 fragments as IEEE half (exhaustive fast path)
+  const char *w2_frag_h;
+  const uint32_t *UP;       // [B, H] U[b, h] as a half head | half remainder << 16 (exhaustive fast path)
   const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
   const int32_t *cand_count;  // [B] or nullptr: only the first cand_count[b] slots of row b are candidates
   float *scores;         // [B, Kp]
@@ -349,9 +352,218 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   }
 }
 
+// Exhaustive scoring, fast form (cand_idx = NULL, concatenated gate, ReLU, shapes whose item tile fits registers).
+// Every (query, item) pair costs the same arithmetic, so what bounds this kernel is instruction issue -- matrix-core
+// and vector -- not memory (Section 4.2: the non-GEMM operators dominate once the GEMMs are on the matrix cores).
+// Against the general kernel above it
+//   * keeps a block of 32 items (rows and decoded gate halves) in registers and walks a chunk of queries over it;
+//   * scores 16 / K_U queries per component-logit MFMA (the 16 columns hold (query, ku) pairs instead of K_U columns
+//     and padding), the logits of the group go to an LDS tile per query;
+//   * runs both gating layers on the half-precision MFMA forms: the bf16 weights convert to half exactly (pack does it
+//     once), logits and hidden units are rounded once to half (11 significant bits) instead of being split into two
+//     bf16 parts -- one MFMA and one conversion per operand instead of two MFMAs and a split;
+//   * lets the matrix cores add what is constant over a tile: the cached item half Xi[n] and b2 enter as the MFMA's
+//     initial accumulators, the user half U[b] as one more k-step (a half head + remainder against a column of ones);
+//   * applies ReLU on packed halves (it commutes with the rounding).
+template <int K_U, int K_X, int D_P, int H, bool F16>
+__global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
+  using S = MolShape<K_U, K_X, D_P, H>;
+  constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
+                CLS = S::CLS;
+  constexpr int QPM = 16 / K_U;  // queries per component-logit MFMA
+  static_assert(RT <= 8, "the item tile must fit the register file");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  char *w1s = smem;
+  char *w2s = smem + S::W1B;
+  const int wv = threadIdx.x >> 6;
+  float *cl = reinterpret_cast<float *>(smem + S::W1B + S::W2B) + wv * (QPM * 32 * CLS);  // [QPM][32][CLS]
+
+  for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
+    reinterpret_cast<uint4 *>(w1s)[i] = reinterpret_cast<const uint4 *>(a.w1c_frag_h)[i];
+  for (int i = threadIdx.x; i < S::W2B / 16; i += 256)
+    reinterpret_cast<uint4 *>(w2s)[i] = reinterpret_cast<const uint4 *>(a.w2_frag_h)[i];
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63;
+  const int c = lane & 31, h = lane >> 5;
+  const int r16 = lane & 15, g = lane >> 4;
+  const int64_t n_tiles = (a.N + 31) >> 5;
+  const int64_t n_qch = (a.B + MOL_QCHUNK - 1) / MOL_QCHUNK;
+  const int64_t ntasks = n_tiles * n_qch;
+  const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+  const int64_t nwaves = (int64_t)gridDim.x * 4;
+
+  // b2 in the accumulator layout of layer 2: component 32 pt + 8 (j / 4) + 4 h + j % 4
+  f32x16 b2v[PT];
+#pragma unroll
+  for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+    for (int j = 0; j < 16; ++j) b2v[pt][j] = a.b2[32 * pt + 8 * (j >> 2) + 4 * h + (j & 3)];
+  const uint4 ones = make_uint4(h == 0 ? 0x3C003C00u : 0u, 0u, 0u, 0u);  // k-slots 0 and 1 of the extra k-step: 1.0
+
+  for (int64_t task = wave; task < ntasks; task += nwaves) {
+    const int64_t tile = task / n_qch;
+    const int b_lo = (int)(task % n_qch) * MOL_QCHUNK;
+    const int b_hi = b_lo + MOL_QCHUNK < a.B ? b_lo + MOL_QCHUNK : a.B;
+    const int64_t cpos = tile * 32 + c;
+    const bool ok = cpos < a.N;
+    const int64_t item = ok ? cpos : 0;
+
+    // the item block: rows in MFMA operand order, and the cached gate halves decoded to fp32 in the layer-1
+    // accumulator layout (hidden unit 32 mt + 8 q + 4 h + i at [mt][4 q + i])
+    uint4 A[RT][SA];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      int64_t n = tile * 32 + rt * CPR + r16 / K_X;
+      if (n >= a.N) n = 0;
+      const char *rowp = a.embs + ((n * K_X + (r16 % K_X)) * D_P + 8 * g) * 2;
+#pragma unroll
+      for (int s = 0; s < SA; ++s) A[rt][s] = ld16(rowp + 64 * s);
+    }
+    f32x16 xif[MT];
+    {
+      const char *xp = a.xi + ((size_t)item * H + 4 * h) * 2;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const uint2 x = *reinterpret_cast<const uint2 *>(xp + (32 * mt + 8 * q) * 2);
+          xif[mt][4 * q + 0] = dec16<F16>(x.x & 0xffffu);
+          xif[mt][4 * q + 1] = dec16<F16>(x.x >> 16);
+          xif[mt][4 * q + 2] = dec16<F16>(x.y & 0xffffu);
+          xif[mt][4 * q + 3] = dec16<F16>(x.y >> 16);
+        }
+    }
+
+    for (int b0 = b_lo; b0 < b_hi; b0 += QPM) {
+      // ---- A: component logits of QPM queries -> LDS tiles (column r16 = (query b0 + r16 / K_U, ku = r16 % K_U)) ----
+      uint4 Ff[SA];
+      const bool qvalid = b0 * K_U + r16 < b_hi * K_U;
+#pragma unroll
+      for (int s = 0; s < SA; ++s)
+        Ff[s] = qvalid ? ld16(a.F + ((size_t)(b0 * K_U + r16) * D_P + 32 * s + 8 * g) * 2) : make_uint4(0, 0, 0, 0);
+      float *clw = cl + (r16 / K_U) * (32 * CLS) + (r16 % K_U) * K_X;
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < SA; ++s) acc = mfma16_16x16x32<F16>(A[rt][s], Ff[s], acc);
+        // acc[j]: row 4 g + j of the tile = (candidate rt * CPR + (4 g + j) / K_X, kx (4 g + j) % K_X)
+        if constexpr (K_X % 4 == 0) {
+          float4 v = make_float4(acc[0] * a.logit_scale, acc[1] * a.logit_scale, acc[2] * a.logit_scale,
+                                 acc[3] * a.logit_scale);
+          *reinterpret_cast<float4 *>(&clw[(rt * CPR + (4 * g) / K_X) * CLS + (4 * g) % K_X]) = v;
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            clw[(rt * CPR + (4 * g + j) / K_X) * CLS + (4 * g + j) % K_X] = acc[j] * a.logit_scale;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+#pragma unroll 1
+      for (int qi = 0; qi < QPM; ++qi) {
+        const int b = b0 + qi;
+        if (b >= b_hi) break;
+        const float *clq = cl + qi * (32 * CLS);
+        // ---- B: layer 1 (transposed), accumulators start at the cached item half; one more k-step adds U[b] ----
+        uint32_t upk[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) upk[mt] = a.UP[(size_t)b * H + 32 * mt + c];
+        f32x16 acc1[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc1[mt] = xif[mt];
+#pragma unroll
+        for (int s = 0; s < S1; ++s) {
+          const float4 lo = *reinterpret_cast<const float4 *>(&clq[c * CLS + 16 * s + 8 * h]);
+          const float4 hi = *reinterpret_cast<const float4 *>(&clq[c * CLS + 16 * s + 8 * h + 4]);
+          const uint4 bf = make_uint4(pack16x2<true>(lo.x, lo.y), pack16x2<true>(lo.z, lo.w), pack16x2<true>(hi.x, hi.y),
+                                      pack16x2<true>(hi.z, hi.w));
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const uint4 af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
+            acc1[mt] = mfma16_32x32x16<true>(af, bf, acc1[mt]);
+          }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc1[mt] = mfma16_32x32x16<true>(make_uint4(h == 0 ? upk[mt] : 0u, 0u, 0u, 0u), ones, acc1[mt]);
+
+        // ---- C: ReLU on packed halves, layer 2 (transposed), accumulators start at b2 ----
+        f32x16 acc2[PT];
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt) acc2[pt] = b2v[pt];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+          for (int qq = 0; qq < 2; ++qq) {
+            uint4 bf;
+            uint32_t *bw = reinterpret_cast<uint32_t *>(&bf);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              f32x2v v = {acc1[mt][8 * qq + 2 * e], acc1[mt][8 * qq + 2 * e + 1]};
+              f16x2v hv = __builtin_convertvector(v, f16x2v);
+              const f16x2v zero = {(_Float16)0.f, (_Float16)0.f};
+              hv = __builtin_elementwise_max(hv, zero);
+              bw[e] = __builtin_bit_cast(uint32_t, hv);
+            }
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) {
+              const uint4 af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
+              acc2[pt] = mfma16_32x32x16<true>(af, bf, acc2[pt]);
+            }
+          }
+        }
+
+        // ---- D: softmax over the components (base-2 exponentials) and the weighted sum ----
+        float m = -INFINITY;
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+          for (int j = 0; j < 16; ++j)
+            if (32 * pt + 8 * (j >> 2) < P) m = fmaxf(m, acc2[pt][j]);
+        m = fmaxf(m, __shfl_xor(m, 32));
+        constexpr float L2E = 1.4426950408889634f;
+        const float mm = m * L2E;
+        float den = 0.f, num = 0.f;
+#pragma unroll
+        for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (32 * pt + 8 * q < P) {
+              const float4 c4 = *reinterpret_cast<const float4 *>(&clq[c * CLS + 32 * pt + 8 * q + 4 * h]);
+              const float e0 = __builtin_amdgcn_exp2f(fmaf(acc2[pt][4 * q + 0], L2E, -mm)),
+                          e1 = __builtin_amdgcn_exp2f(fmaf(acc2[pt][4 * q + 1], L2E, -mm)),
+                          e2 = __builtin_amdgcn_exp2f(fmaf(acc2[pt][4 * q + 2], L2E, -mm)),
+                          e3 = __builtin_amdgcn_exp2f(fmaf(acc2[pt][4 * q + 3], L2E, -mm));
+              den += (e0 + e1) + (e2 + e3);
+              num += (e0 * c4.x + e1 * c4.y) + (e2 * c4.z + e3 * c4.w);
+            }
+          }
+        den += __shfl_xor(den, 32);
+        num += __shfl_xor(num, 32);
+        if (h == 0 && ok) a.scores[(size_t)b * a.Kp + cpos] = num * __builtin_amdgcn_rcpf(den);
+      }
+      // the next group overwrites the LDS logit tiles: all lanes must be done reading them
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
 // U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
 // One thread per output, 8 bf16 of each operand per load when the rows allow it.
-__global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, int B, int H, int d_gu, bool f16) {
+// UP (optional): the same value as a half head and half remainder, head | remainder << 16 (exhaustive fast path).
+__device__ __forceinline__ uint32_t half_head_and_rest(float v) {
+  const _Float16 hd = (_Float16)v;
+  const _Float16 rs = (_Float16)(v - (float)hd);
+  return (uint32_t)__builtin_bit_cast(uint16_t, hd) | ((uint32_t)__builtin_bit_cast(uint16_t, rs) << 16);
+}
+
+__global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, uint32_t *UP, int B, int H, int d_gu,
+                            bool f16) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * H) return;
   const int b = i / H, hh = i % H;
@@ -362,6 +574,7 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
     for (int j = 0; j < d_gu; ++j)
       acc = fmaf(dec16(w1u[(size_t)hh * d_gu + j], f16), dec16(gu[(size_t)b * d_gu + j], f16), acc);
     U[i] = acc;
+    if (UP) UP[i] = half_head_and_rest(acc);
     return;
   }
   for (int j = 0; j < d_gu / 8; ++j) {
@@ -374,6 +587,7 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, i
     }
   }
   U[i] = acc;
+  if (UP) UP[i] = half_head_and_rest(acc);
 }
 
 // Decomposed gate, per query (userWeightFn of Algorithm 1): UW[b, :] = Wu2 * act(Wu1 * gu[b] + bu1) + bu2, and the
@@ -431,9 +645,43 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   return MOL_OK;
 }
 
+// launch of the exhaustive fast form
+template <int K_U, int K_X, int D_P, int H, bool F16>
+mol_status_t launch_exh(const MolArgs &a, hipStream_t st) {
+  using S = MolShape<K_U, K_X, D_P, H>;
+  constexpr int QPM = 16 / K_U;
+  constexpr size_t LDS = S::W1B + S::W2B + (size_t)4 * QPM * 32 * S::CLS * 4;
+  auto kern = k_mol_exh<K_U, K_X, D_P, H, F16>;
+  static std::mutex mu;
+  static bool configured = false;
+  static int per_sm = 1, sm_count = 0;
+  {
+    std::lock_guard<std::mutex> lk(mu);
+    if (!configured) {
+      int dev = 0;
+      HIP_TRY(hipGetDevice(&dev));
+      HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS));
+      HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, LDS));
+      if (per_sm < 1) per_sm = 1;
+      configured = true;
+    }
+  }
+  const int64_t ntasks = ((a.N + 31) / 32) * ((a.B + MOL_QCHUNK - 1) / MOL_QCHUNK);
+  int64_t grid = (int64_t)sm_count * per_sm;
+  const int64_t need = (ntasks + 3) / 4;
+  if (grid > need) grid = need;
+  if (grid < 1) grid = 1;
+  ProfScope ps(MOL_PROF_MOL_SCORE, st);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), LDS, st, a);
+  HIP_TRY(hipGetLastError());
+  return MOL_OK;
+}
+
 }  // namespace
 
-mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, hipStream_t st) {
+mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B, float *U, float *UW, uint32_t *UP,
+                              hipStream_t st) {
   const int n = B * c->H;
   ProfScope ps(MOL_PROF_USER_GATE, st);
   if (c->gate_form == MOL_GATE_DECOMPOSED) {
@@ -444,12 +692,29 @@ mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B,
     return MOL_OK;
   }
   hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
-                     static_cast<const uint16_t *>(user_gate), U, B, c->H, c->d_gu, c->f16);
+                     static_cast<const uint16_t *>(user_gate), U, UP, B, c->H, c->d_gu, c->f16);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
 
 bool mol_shape_supported(int k_u, int k_x, int d_p, int H);
+
+// shapes the exhaustive fast form is built for: those whose 32-item tile fits the register file (k_x <= 4)
+#define MOL_EXH_SHAPES(X) \
+  X(4, 4, 32, 32)         \
+  X(4, 4, 64, 64)         \
+  X(8, 4, 64, 128)        \
+  X(16, 1, 32, 32)        \
+  X(8, 2, 128, 96)
+
+bool mol_exh_fast_form(const mol_corpus *c) {
+  if (c->gate_form != MOL_GATE_CONCAT || c->act != MOL_ACT_RELU || !c->w1c_frag_h || !c->w2_frag_h) return false;
+#define X(KU, KX, DP, HH) \
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return true;
+  MOL_EXH_SHAPES(X)
+#undef X
+  return false;
+}
 
 #define MOL_SHAPES(X) \
   X(4, 4, 32, 32)     \
@@ -521,9 +786,9 @@ static mol_status_t launch_variant(const MolArgs &a, bool exhaustive, int form, 
 #undef V
 }
 
-mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW, int B,
-                              const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp, float *scores,
-                              hipStream_t st) {
+mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const float *U, const float *UW,
+                              const uint32_t *UP, int B, const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp,
+                              float *scores, hipStream_t st) {
   MolArgs a;
   a.embs = static_cast<const char *>(c->embs);
   a.xi = static_cast<const char *>(c->xi);
@@ -542,6 +807,16 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.B = B;
   a.act = c->act;
   a.logit_scale = c->logit_scale;
+  a.w1c_frag_h = static_cast<const char *>(c->w1c_frag_h);
+  a.w2_frag_h = static_cast<const char *>(c->w2_frag_h);
+  a.UP = UP;
+  if (mol_exh_fast_form(c) && cand_idx == nullptr && UP != nullptr) {
+#define XF(KU, KX, DP, HH)                                                \
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH)         \
+    return c->f16 ? launch_exh<KU, KX, DP, HH, true>(a, st) : launch_exh<KU, KX, DP, HH, false>(a, st);
+    MOL_EXH_SHAPES(XF)
+#undef XF
+  }
 #define X(KU, KX, DP, HH) \
   if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return launch_variant<KU, KX, DP, HH>(a, cand_idx == nullptr, c->gate_form, c->f16, st);
   MOL_SHAPES(X)

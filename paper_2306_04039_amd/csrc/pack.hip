@@ -51,6 +51,13 @@ __global__ void k_pack_weights(const uint16_t *W1, const uint16_t *W2, const flo
   if (i < n5) b2p[i] = (b2 && i < P) ? b2[i] : 0.f;
 }
 
+// bf16 -> IEEE half, element by element (exact for normal halves: 8 significant bits fit 11; magnitudes below 2^-14 land
+// on the half subnormal grid, absolute error <= 2^-25).  For the fragment buffers of the exhaustive fast form.
+__global__ void k_bf16_to_f16(const uint16_t *src, uint16_t *dst, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = __builtin_bit_cast(uint16_t, (_Float16)bf16_bits_to_f32(src[i]));
+}
+
 // Xi^T[h, n] = W1x[h, :] . gx[n, :] + b1[h] on 32x32x16 MFMA: A = W1x rows (hidden units), B = item rows.
 // A wavefront takes 32 items; lane (c = lane%32, half) loads its item's row chunks once and walks the hidden tiles.
 template <int KS, bool F16>  // d_gx / 16; 16-bit type of the inputs and of Xi
@@ -257,6 +264,10 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   ALLOC(c->w1u, (n3 ? n3 : 1) * 2)
   ALLOC(w1x, (n4 ? n4 : 1) * 2)
   ALLOC(c->b2, n5 * 4)
+  if (!decomposed && !c->f16) {
+    ALLOC(c->w1c_frag_h, n1 * 2)
+    ALLOC(c->w2_frag_h, n2 * 2)
+  }
   if (decomposed) {
     ALLOC(c->xw, (size_t)c->N * P * 4)
     ALLOC(c->wu1, (size_t)cfg->d_hu * c->d_gu * 2)
@@ -291,6 +302,19 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
                        static_cast<uint16_t *>(c->w1u), static_cast<uint16_t *>(w1x), c->b2);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "k_pack_weights: %s", hipGetErrorString(e));
+  }
+  if (rc == MOL_OK && !decomposed) {
+    if (c->f16) {
+      c->w1c_frag_h = c->w1c_frag;
+      c->w2_frag_h = c->w2_frag;
+    } else {
+      hipLaunchKernelGGL(k_bf16_to_f16, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st,
+                         static_cast<const uint16_t *>(c->w1c_frag), static_cast<uint16_t *>(c->w1c_frag_h), (int)n1);
+      hipLaunchKernelGGL(k_bf16_to_f16, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
+                         static_cast<const uint16_t *>(c->w2_frag), static_cast<uint16_t *>(c->w2_frag_h), (int)n2);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "k_bf16_to_f16: %s", hipGetErrorString(e));
+    }
   }
   if (rc == MOL_OK && !decomposed) rc = launch_item_gate_cache(c, item_gate, w1x, cfg->b1, st);
   if (rc == MOL_OK && decomposed) {
@@ -388,6 +412,8 @@ extern "C" mol_status_t mol_quantize_int8(const void *src, int src_dtype, int64_
 extern "C" mol_status_t mol_corpus_free(mol_corpus_t *c) {
   if (!c) return MOL_OK;
   (void)hipDeviceSynchronize();
+  if (c->w1c_frag_h && c->w1c_frag_h != c->w1c_frag) (void)hipFree(c->w1c_frag_h);
+  if (c->w2_frag_h && c->w2_frag_h != c->w2_frag) (void)hipFree(c->w2_frag_h);
   if (c->w1c_frag) (void)hipFree(c->w1c_frag);
   if (c->w2_frag) (void)hipFree(c->w2_frag);
   if (c->w1u) (void)hipFree(c->w1u);

@@ -13,8 +13,12 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 SHAPES = {
+    "C1": dict(k_u=4, k_x=4, d_p=32, H=32, d_gu=32, d_gx=32),
     "C2": dict(k_u=4, k_x=4, d_p=64, H=64, d_gu=64, d_gx=64),
+    "C3": dict(k_u=8, k_x=4, d_p=64, H=128, d_gu=128, d_gx=128),
     "C4": dict(k_u=8, k_x=8, d_p=64, H=128, d_gu=128, d_gx=128),
+    "odd-kx1": dict(k_u=16, k_x=1, d_p=32, H=32, d_gu=32, d_gx=32),
+    "odd-h96": dict(k_u=8, k_x=2, d_p=128, H=96, d_gu=20, d_gx=96),
 }
 
 
@@ -55,17 +59,24 @@ def checked_queries(B, every):
     return sorted(x for x in edge if 0 <= x < B)
 
 
-@pytest.mark.parametrize("shape,gate,B,every", [
-    ("C2", "concat", 300, True),        # every one of the 300 x 20003 scores
-    ("C2", "concat", 1024, False),      # the largest batch: four query chunks
-    ("C4", "concat", 300, False),
-    ("C4", "concat", 1024, False),
-    ("C2", "decomposed", 300, False),
-    ("C4", "decomposed", 1024, False),
+@pytest.mark.parametrize("shape,gate,B,every,act,scale", [
+    ("C2", "concat", 300, True, "relu", 1.0),        # every one of the 300 x 20003 scores
+    ("C2", "concat", 1024, False, "relu", 1.0),      # the largest batch: four query chunks
+    ("C2", "concat", 1023, False, "relu", 20.0),     # sharp gates; the last group of queries is incomplete
+    ("C2", "concat", 301, False, "silu", 0.05),      # SiLU takes the general exhaustive kernel
+    ("C3", "concat", 258, False, "relu", 1.0),       # two queries per logit product
+    ("C1", "concat", 515, False, "relu", 20.0),
+    ("odd-kx1", "concat", 300, False, "relu", 1.0),  # one query per logit product
+    ("odd-h96", "concat", 270, False, "relu", 1.0),
+    ("C4", "concat", 300, False, "relu", 1.0),
+    ("C4", "concat", 1024, False, "relu", 1.0),
+    ("C2", "decomposed", 300, False, "relu", 1.0),
+    ("C4", "decomposed", 1024, False, "relu", 1.0),
 ])
-def test_exhaustive_scores_and_topk_beyond_one_query_chunk(shape, gate, B, every):
+def test_exhaustive_scores_and_topk_beyond_one_query_chunk(shape, gate, B, every, act, scale):
     N, k = 20_003, 100                              # ragged: the last item block holds 3 items
-    wl = synth.CONFIGS["C5"].replace(N=N, B=B, k=k, n_clusters=64, bias_scale=0.1, **SHAPES[shape])
+    wl = synth.CONFIGS["C5"].replace(N=N, B=B, k=k, n_clusters=64, bias_scale=0.1, act=act, logit_scale=scale,
+                                     **SHAPES[shape])
     items, q, corpus, model = build(wl, gate)
     got = m().mol_score(corpus, q["F"], q["gu"], None)
     idx, sc = m().mol_topk(corpus, q["F"], q["gu"], None, k)
@@ -78,7 +89,7 @@ def test_exhaustive_scores_and_topk_beyond_one_query_chunk(shape, gate, B, every
         ref = orc.mol_scores_for(model, orc.as_f64(Fb[b]), orc.as_f64(gub[b]), ids)
         assert_scores_close(got[b], ref, wl.logit_scale, f"{shape}/{gate} B={B} query {b}")
         kth = np.sort(ref)[::-1][k - 1]
-        assert_topk_set(idx[b], ref, k, 2e-3 * abs(kth) + 1e-4, f"query {b}")
+        assert_topk_set(idx[b], ref, k, 2e-3 * abs(kth) + 1e-4 * wl.logit_scale, f"query {b}")
     # every query: mol_topk is the exact selection (score desc, index asc) over mol_score's own values
     for b in range(B):
         want = np.lexsort((ids, -got[b].astype(np.float64)))[:k]
