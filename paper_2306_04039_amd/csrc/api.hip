@@ -116,9 +116,9 @@ extern "C" size_t hindexer_workspace_bytes(const mol_corpus_t *c, int B, int Kp,
   return p0.total > p1.total ? p0.total : p1.total;
 }
 
-// U [B, H], UW [B, P], UP [B, H] (the per-query inputs of the scoring kernels)
+// U [B, H], UW [B, P], UP [B, H/32, 64] (the per-query inputs of the scoring kernels)
 static size_t mol_user_bytes(const mol_corpus_t *c, int B) {
-  return 2 * align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256);
+  return 3 * align_up((size_t)B * c->H * 4, 256) + align_up((size_t)B * c->P * 4, 256);
 }
 static void mol_user_ptrs(const mol_corpus_t *c, int B, char *ws, float **U, float **UW, uint32_t **UP) {
   *U = reinterpret_cast<float *>(ws);

@@ -35,7 +35,8 @@ struct MolArgs {
   const float *UW;       // decomposed gate: f32 [B, P] user weights
   const char *w1c_frag_h;   // the layer-1 / layer-2 fragments as IEEE half (exhaustive fast path)
   const char *w2_frag_h;
-  const uint32_t *UP;       // [B, H] U[b, h] as a half head | half remainder << 16 (exhaustive fast path)
+  const uint32_t *UP;       // [B][H/32][64]: U[b, 32 mt + l] as a half head | half remainder << 16 at [b][mt][l], l < 32,
+                            // zeros at l >= 32 (the A operand of the extra k-step, one word per lane; exhaustive fast path)
   const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
   const int32_t *cand_count;  // [B] or nullptr: only the first cand_count[b] slots of row b are candidates
   float *scores;         // [B, Kp]
@@ -352,6 +353,17 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   }
 }
 
+// Reductions over the two halves of a wavefront (lane and lane ^ 32) without a trip through LDS: the row swap leaves the
+// lower half's value in one register and the upper half's in the other, in every lane.
+__device__ __forceinline__ float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Exhaustive scoring, fast form (cand_idx = NULL, concatenated gate, ReLU, shapes whose item tile fits registers).
 // Every (query, item) pair costs the same arithmetic, so what bounds this kernel is instruction issue -- matrix-core
 // and vector -- not memory (Section 4.2: the non-GEMM operators dominate once the GEMMs are on the matrix cores).
@@ -365,26 +377,44 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 //   * lets the matrix cores add what is constant over a tile: the cached item half Xi[n] and b2 enter as the MFMA's
 //     initial accumulators, the user half U[b] as one more k-step (a half head + remainder against a column of ones);
 //   * applies ReLU on packed halves (it commutes with the rounding).
+// registers one lane holds for a whole item block (decoded gate halves, layer-1 accumulators, rows, layer-2 accumulators
+// and bias): shapes beyond 170 of them get the whole register file (one wavefront per SIMD), the others share it in two
+template <int K_U, int K_X, int D_P, int H>
+constexpr int exh_min_waves() {
+  using S = MolShape<K_U, K_X, D_P, H>;
+  return (S::MT * 32 + S::RT * S::SA * 4 + S::PT * 32 > 170) ? 1 : 2;
+}
+
 template <int K_U, int K_X, int D_P, int H, bool F16>
-__global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
+__global__ __launch_bounds__(256, (exh_min_waves<K_U, K_X, D_P, H>())) void k_mol_exh(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
   constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
                 CLS = S::CLS;
   constexpr int QPM = 16 / K_U;  // queries per component-logit MFMA
   static_assert(RT <= 8, "the item tile must fit the register file");
+  // small gates keep their weight fragments in registers for the whole kernel (each is read once per query otherwise,
+  // and LDS bandwidth is a co-limit of this kernel); larger ones stage them in LDS
+  constexpr bool WREG = MT * S1 + PT * S2 <= 8;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char *w1s = smem;
   char *w2s = smem + S::W1B;
   const int wv = threadIdx.x >> 6;
-  float *cl = reinterpret_cast<float *>(smem + S::W1B + S::W2B) + wv * (QPM * 32 * CLS);  // [QPM][32][CLS]
-
-  for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
-    reinterpret_cast<uint4 *>(w1s)[i] = reinterpret_cast<const uint4 *>(a.w1c_frag_h)[i];
-  for (int i = threadIdx.x; i < S::W2B / 16; i += 256)
-    reinterpret_cast<uint4 *>(w2s)[i] = reinterpret_cast<const uint4 *>(a.w2_frag_h)[i];
-  __syncthreads();
-
   const int lane = threadIdx.x & 63;
+  float *cl = reinterpret_cast<float *>(smem + (WREG ? 0 : S::W1B + S::W2B)) + wv * (QPM * 32 * CLS);  // [QPM][32][CLS]
+  uint4 w1r[WREG ? MT * S1 : 1], w2r[WREG ? PT * S2 : 1];
+  if constexpr (WREG) {
+#pragma unroll
+    for (int i = 0; i < MT * S1; ++i) w1r[i] = reinterpret_cast<const uint4 *>(a.w1c_frag_h)[i * 64 + lane];
+#pragma unroll
+    for (int i = 0; i < PT * S2; ++i) w2r[i] = reinterpret_cast<const uint4 *>(a.w2_frag_h)[i * 64 + lane];
+  } else {
+    for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
+      reinterpret_cast<uint4 *>(w1s)[i] = reinterpret_cast<const uint4 *>(a.w1c_frag_h)[i];
+    for (int i = threadIdx.x; i < S::W2B / 16; i += 256)
+      reinterpret_cast<uint4 *>(w2s)[i] = reinterpret_cast<const uint4 *>(a.w2_frag_h)[i];
+    __syncthreads();
+  }
+
   const int c = lane & 31, h = lane >> 5;
   const int r16 = lane & 15, g = lane >> 4;
   const int64_t n_tiles = (a.N + 31) >> 5;
@@ -437,6 +467,15 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
 
     for (int b0 = b_lo; b0 < b_hi; b0 += QPM) {
       // ---- A: component logits of QPM queries -> LDS tiles (column r16 = (query b0 + r16 / K_U, ku = r16 % K_U)) ----
+      // U of the group's queries, in operand form: issued first, needed only after the logits
+      uint32_t upk[QPM][MT];
+#pragma unroll
+      for (int qi = 0; qi < QPM; ++qi) {
+        const int bc = b0 + qi < b_hi ? b0 + qi : b_hi - 1;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) upk[qi][mt] = a.UP[((size_t)bc * MT + mt) * 64 + lane];
+      }
+      float res[QPM];
       uint4 Ff[SA];
       const bool qvalid = b0 * K_U + r16 < b_hi * K_U;
 #pragma unroll
@@ -463,15 +502,13 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-#pragma unroll 1
+      // The QPM queries of the group are independent chains of dependent steps (LDS read -> MFMA -> convert -> MFMA ->
+      // softmax): unrolled into one block with no branches so that the scheduler can overlap them.  A query past the
+      // end of the chunk (incomplete last group) is computed on zero logits and not stored.
+#pragma unroll
       for (int qi = 0; qi < QPM; ++qi) {
-        const int b = b0 + qi;
-        if (b >= b_hi) break;
         const float *clq = cl + qi * (32 * CLS);
         // ---- B: layer 1 (transposed), accumulators start at the cached item half; one more k-step adds U[b] ----
-        uint32_t upk[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) upk[mt] = a.UP[(size_t)b * H + 32 * mt + c];
         f32x16 acc1[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc1[mt] = xif[mt];
@@ -483,13 +520,15 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
                                       pack16x2<true>(hi.z, hi.w));
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
-            const uint4 af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
+            uint4 af;
+            if constexpr (WREG) af = w1r[mt * S1 + s];
+            else af = *reinterpret_cast<const uint4 *>(w1s + ((mt * S1 + s) * 64 + lane) * 16);
             acc1[mt] = mfma16_32x32x16<true>(af, bf, acc1[mt]);
           }
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-          acc1[mt] = mfma16_32x32x16<true>(make_uint4(h == 0 ? upk[mt] : 0u, 0u, 0u, 0u), ones, acc1[mt]);
+          acc1[mt] = mfma16_32x32x16<true>(make_uint4(upk[qi][mt], 0u, 0u, 0u), ones, acc1[mt]);
 
         // ---- C: ReLU on packed halves, layer 2 (transposed), accumulators start at b2 ----
         f32x16 acc2[PT];
@@ -511,7 +550,9 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
             }
 #pragma unroll
             for (int pt = 0; pt < PT; ++pt) {
-              const uint4 af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
+              uint4 af;
+              if constexpr (WREG) af = w2r[pt * S2 + mt * 2 + qq];
+              else af = *reinterpret_cast<const uint4 *>(w2s + ((pt * S2 + mt * 2 + qq) * 64 + lane) * 16);
               acc2[pt] = mfma16_32x32x16<true>(af, bf, acc2[pt]);
             }
           }
@@ -524,7 +565,7 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
 #pragma unroll
           for (int j = 0; j < 16; ++j)
             if (32 * pt + 8 * (j >> 2) < P) m = fmaxf(m, acc2[pt][j]);
-        m = fmaxf(m, __shfl_xor(m, 32));
+        m = half_swap_max(m);
         constexpr float L2E = 1.4426950408889634f;
         const float mm = m * L2E;
         float den = 0.f, num = 0.f;
@@ -542,9 +583,14 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
               num += (e0 * c4.x + e1 * c4.y) + (e2 * c4.z + e3 * c4.w);
             }
           }
-        den += __shfl_xor(den, 32);
-        num += __shfl_xor(num, 32);
-        if (h == 0 && ok) a.scores[(size_t)b * a.Kp + cpos] = num * __builtin_amdgcn_rcpf(den);
+        den = half_swap_sum(den);
+        num = half_swap_sum(num);
+        res[qi] = num * __builtin_amdgcn_rcpf(den);
+      }
+      if (h == 0 && ok) {
+#pragma unroll
+        for (int qi = 0; qi < QPM; ++qi)
+          if (b0 + qi < b_hi) a.scores[(size_t)(b0 + qi) * a.Kp + cpos] = res[qi];
       }
       // the next group overwrites the LDS logit tiles: all lanes must be done reading them
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -555,7 +601,8 @@ __global__ __launch_bounds__(256, 2) void k_mol_exh(MolArgs a) {
 
 // U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
 // One thread per output, 8 bf16 of each operand per load when the rows allow it.
-// UP (optional): the same value as a half head and half remainder, head | remainder << 16 (exhaustive fast path).
+// UP (optional): the same value as a half head and half remainder, head | remainder << 16, laid out [B][H/32][64] with
+// U[b, 32 mt + l] at [b][mt][l] and zeros at l >= 32 (exhaustive fast path).
 __device__ __forceinline__ uint32_t half_head_and_rest(float v) {
   const _Float16 hd = (_Float16)v;
   const _Float16 rs = (_Float16)(v - (float)hd);
@@ -574,7 +621,10 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, u
     for (int j = 0; j < d_gu; ++j)
       acc = fmaf(dec16(w1u[(size_t)hh * d_gu + j], f16), dec16(gu[(size_t)b * d_gu + j], f16), acc);
     U[i] = acc;
-    if (UP) UP[i] = half_head_and_rest(acc);
+    if (UP) {
+      UP[((size_t)b * (H / 32) + hh / 32) * 64 + (hh & 31)] = half_head_and_rest(acc);
+      UP[((size_t)b * (H / 32) + hh / 32) * 64 + 32 + (hh & 31)] = 0u;
+    }
     return;
   }
   for (int j = 0; j < d_gu / 8; ++j) {
@@ -587,7 +637,10 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, u
     }
   }
   U[i] = acc;
-  if (UP) UP[i] = half_head_and_rest(acc);
+  if (UP) {
+    UP[((size_t)b * (H / 32) + hh / 32) * 64 + (hh & 31)] = half_head_and_rest(acc);
+    UP[((size_t)b * (H / 32) + hh / 32) * 64 + 32 + (hh & 31)] = 0u;
+  }
 }
 
 // Decomposed gate, per query (userWeightFn of Algorithm 1): UW[b, :] = Wu2 * act(Wu1 * gu[b] + bu1) + bu2, and the
@@ -650,7 +703,8 @@ template <int K_U, int K_X, int D_P, int H, bool F16>
 mol_status_t launch_exh(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
   constexpr int QPM = 16 / K_U;
-  constexpr size_t LDS = S::W1B + S::W2B + (size_t)4 * QPM * 32 * S::CLS * 4;
+  constexpr bool WREG = S::MT * S::S1 + S::PT * S::S2 <= 8;  // as in the kernel: weight fragments in registers
+  constexpr size_t LDS = (WREG ? 0 : S::W1B + S::W2B) + (size_t)4 * QPM * 32 * S::CLS * 4;
   auto kern = k_mol_exh<K_U, K_X, D_P, H, F16>;
   static std::mutex mu;
   static bool configured = false;
