@@ -37,6 +37,9 @@ product" from "round the exact product" (the rule itself is the library's contra
 paper, which gives no scheme), INT8 scores against Python integers;
 Algorithm 1's decomposed gate: distribution / convexity, P = 1, all-zero heads give the mean logit, constant heads in
 the two SiLU limits (softmax of the product; uniform), one-hot selection, scalar-loop re-derivation.
+Generated item embeddings (Section 3.1): with a zero first layer every item gets the normalised bias, an identity MLP on
+non-negative seeds returns the normalised seed chunks (both then equal the cached path on hand-built embeddings), unit
+norm, invariance to a positive rescaling of the output layer, scalar-loop re-derivation.
 The recall level of the approximate (sampled) mode is "parity unpinned": the paper's recall figure
 carries no numbers.
 """
@@ -238,6 +241,21 @@ def decomposed_gating(cl: np.ndarray, gu_b: np.ndarray, gx_rows: np.ndarray, use
     return e / e.sum(axis=1, keepdims=True)
 
 
+def generated_item_embeddings(seed_rows: np.ndarray, gen_mlp, k_g: int, d: int, act: str = "relu") -> np.ndarray:
+    """Item-side embeddings produced at query time instead of being cached (Section 3.1, item-side bullet: some of the
+    item-side embeddings are generated on the fly by learned MLPs, trading compute for accelerator memory).
+
+    The paper fixes neither the MLP's input nor its depth; the reading taken: each item caches a small seed vector
+    seed_rows[c] (d_s numbers); one 2-layer MLP (Wa [d_h, d_s], ba, Wb [k_g * d, d_h], bb) maps it to k_g vectors of
+    length d, and each of them is L2-normalised like every other component embedding (Eq. 9; Algorithm 1's l2Norm):
+        e = Wb * act(Wa * seed + ba) + bb,   g_j = e[j*d : (j+1)*d] / max(||e[j*d : (j+1)*d]||_2, 1e-12).
+    Returns [n, k_g, d] (fp64)."""
+    Wa, ba, Wb, bb = gen_mlp
+    e = _mlp2(seed_rows, Wa, ba, Wb, bb, act).reshape(seed_rows.shape[0], k_g, d)
+    norm = np.sqrt((e * e).sum(axis=2, keepdims=True))
+    return e / np.maximum(norm, 1e-12)
+
+
 class MolModelDecomposed:
     """Algorithm 1's gate (three 2-layer MLPs, multiplicative combination), decoded to fp64 once."""
 
@@ -253,8 +271,12 @@ class MolModelDecomposed:
 class MolModel:
     """Weights and item-side tensors, decoded to fp64 once."""
 
-    def __init__(self, G, gx, W1, b1, W2, b2, logit_scale: float = 1.0, act: str = "relu"):
-        self.G = as_f64(G)            # [N, k_x, d]
+    def __init__(self, G, gx, W1, b1, W2, b2, logit_scale: float = 1.0, act: str = "relu", seed=None, gen_mlp=None):
+        """seed [N, d_s] and gen_mlp (Wa, ba, Wb, bb): the last k_g = Wb.shape[0] / d item-side embeddings are generated
+        from the seed (generated_item_embeddings) and follow the cached ones of G in the component order."""
+        self.seed = None if seed is None else as_f64(seed)
+        self.gen_mlp = None if gen_mlp is None else tuple(as_f64(t) for t in gen_mlp)
+        self.G = as_f64(G)            # [N, k_x (cached), d]
         self.gx = as_f64(gx)          # [N, d_gx]
         self.W1 = as_f64(W1)          # [H, P + d_gu + d_gx]
         self.b1 = np.zeros(self.W1.shape[0]) if b1 is None else as_f64(b1)
@@ -271,7 +293,13 @@ def mol_scores_for(model: MolModel, F_b: np.ndarray, gu_b: np.ndarray, ids: np.n
     out = np.empty(ids.shape[0], dtype=np.float64)
     for lo in range(0, ids.shape[0], chunk):
         sel = ids[lo: lo + chunk]
-        cl = component_logits(F_b, model.G[sel], model.logit_scale)
+        G_rows = model.G[sel]
+        if getattr(model, "gen_mlp", None) is not None:   # cached embeddings first, generated ones after them
+            d = G_rows.shape[2]
+            k_g = model.gen_mlp[2].shape[0] // d
+            G_rows = np.concatenate([G_rows, generated_item_embeddings(model.seed[sel], model.gen_mlp, k_g, d, model.act)],
+                                    axis=1)
+        cl = component_logits(F_b, G_rows, model.logit_scale)
         if isinstance(model, MolModelDecomposed):
             pi = decomposed_gating(cl, gu_b, model.gx[sel], model.user_mlp, model.item_mlp, model.cross_mlp, model.act)
         else:

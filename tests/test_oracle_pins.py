@@ -635,3 +635,111 @@ def test_half_precision_inputs_decode_exactly():
     v = orc.bf16_bits_to_f64(b)
     v = v[(np.abs(v) > 2.0 ** -14) & (np.abs(v) < 60000)]
     assert np.array_equal(v.astype(np.float16).astype(np.float64), v)
+
+
+# --------------------------------------------------------------------------- item embeddings generated on the fly (Section 3.1)
+def small_generated(rng, N=25, k_u=2, k_c=2, k_g=2, d=8, d_s=5, d_h=6, H=5, d_gu=4, d_gx=3, scale=1.0, act="relu"):
+    k_x = k_c + k_g
+    P = k_u * k_x
+    G = rand_bf16_bits(rng, (N, k_c, d), 0.5)
+    gx = rand_bf16_bits(rng, (N, d_gx), 0.5)
+    seed = rand_bf16_bits(rng, (N, d_s), 0.7)
+    gen = (rand_bf16_bits(rng, (d_h, d_s), 0.7), (rng.standard_normal(d_h) * 0.3).astype(np.float32),
+           rand_bf16_bits(rng, (k_g * d, d_h), 0.7), (rng.standard_normal(k_g * d) * 0.3).astype(np.float32))
+    W1 = rand_bf16_bits(rng, (H, P + d_gu + d_gx), 0.7)
+    W2 = rand_bf16_bits(rng, (P, H), 0.7)
+    b1 = (rng.standard_normal(H) * 0.3).astype(np.float32)
+    b2 = (rng.standard_normal(P) * 0.3).astype(np.float32)
+    F = rand_bf16_bits(rng, (3, k_u, d), 0.5)
+    gu = rand_bf16_bits(rng, (3, d_gu), 0.5)
+    return dict(G=G, gx=gx, seed=seed, gen=gen, W1=W1, b1=b1, W2=W2, b2=b2, F=F, gu=gu, scale=scale, act=act, k_g=k_g, d=d)
+
+
+def model_with_explicit_embeddings(m, extra):
+    """The cached-path model whose item tensor is m's cached embeddings followed by `extra` [N, k_g, d] (fp64)."""
+    G_full = np.concatenate([orc.as_f64(m["G"]), extra], axis=1)
+    return orc.MolModel(G_full, m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], m["scale"], m["act"])
+
+
+def test_generated_embeddings_zero_first_layer_gives_the_normalised_bias():
+    """Wa = 0, ba = 0: the hidden layer is act(0) = 0, so every item's generated embeddings are the normalised chunks of
+    bb -- the scores must equal the cached path on an item tensor extended by those constant vectors."""
+    rng = np.random.default_rng(41)
+    m = small_generated(rng)
+    Wa, ba, Wb, bb = m["gen"]
+    gen = (np.zeros_like(Wa), np.zeros_like(ba), Wb, bb)
+    model = orc.MolModel(m["G"], m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], m["scale"], m["act"], seed=m["seed"], gen_mlp=gen)
+    const = unit_rows(bb.astype(np.float64).reshape(m["k_g"], m["d"]))
+    ref = model_with_explicit_embeddings(m, np.broadcast_to(const, (25, m["k_g"], m["d"])))
+    np.testing.assert_allclose(orc.mol_scores(model, m["F"], m["gu"]), orc.mol_scores(ref, m["F"], m["gu"]), rtol=0, atol=1e-12)
+
+
+def test_generated_embeddings_identity_mlp_returns_the_normalised_seed():
+    """d_s = d_h = k_g * d, Wa = Wb = I, zero biases, non-negative seeds, ReLU: e = seed, so the generated embeddings are
+    the L2-normalised chunks of the seed."""
+    rng = np.random.default_rng(42)
+    k_g, d = 2, 8
+    m = small_generated(rng, k_g=k_g, d=d, d_s=k_g * d, d_h=k_g * d)
+    seed = (np.abs(orc.as_f64(m["seed"])) + 0.125).astype(np.float32)          # non-negative, exactly representable path
+    eye = np.eye(k_g * d, dtype=np.float32)
+    zero = np.zeros(k_g * d, dtype=np.float32)
+    model = orc.MolModel(m["G"], m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], m["scale"], "relu", seed=seed,
+                         gen_mlp=(eye, zero, eye, zero))
+    extra = unit_rows(seed.astype(np.float64).reshape(25, k_g, d))
+    m["act"] = "relu"
+    ref = model_with_explicit_embeddings(m, extra)
+    np.testing.assert_allclose(orc.mol_scores(model, m["F"], m["gu"]), orc.mol_scores(ref, m["F"], m["gu"]), rtol=0, atol=1e-12)
+
+
+def test_generated_embeddings_are_unit_vectors_and_ignore_the_output_scale():
+    """Eq. 9's normalisation: unit L2 norm per generated embedding; multiplying the output layer (Wb, bb) by a positive
+    constant changes nothing (a missing normalisation would scale the logits)."""
+    rng = np.random.default_rng(43)
+    m = small_generated(rng, act="silu", scale=3.0)
+    Wa, ba, Wb, bb = (orc.as_f64(t) for t in m["gen"])
+    e = orc.generated_item_embeddings(orc.as_f64(m["seed"]), (Wa, ba, Wb, bb), m["k_g"], m["d"], "silu")
+    assert e.shape == (25, m["k_g"], m["d"])
+    np.testing.assert_allclose(np.linalg.norm(e, axis=2), 1.0, rtol=0, atol=1e-12)
+    e4 = orc.generated_item_embeddings(orc.as_f64(m["seed"]), (Wa, ba, 4.0 * Wb, 4.0 * bb), m["k_g"], m["d"], "silu")
+    np.testing.assert_allclose(e4, e, rtol=0, atol=1e-12)
+    a = orc.MolModel(m["G"], m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], 3.0, "silu", seed=m["seed"], gen_mlp=(Wa, ba, Wb, bb))
+    b = orc.MolModel(m["G"], m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], 3.0, "silu", seed=m["seed"], gen_mlp=(Wa, ba, 4.0 * Wb, 4.0 * bb))
+    np.testing.assert_allclose(orc.mol_scores(a, m["F"], m["gu"]), orc.mol_scores(b, m["F"], m["gu"]), rtol=0, atol=1e-12)
+    # the generated embeddings take the LAST k_g places of the item-side component order
+    cl = orc.component_logits(orc.as_f64(m["F"])[0], np.concatenate([orc.as_f64(m["G"]), e], axis=1), 3.0)
+    k_x = 2 + m["k_g"]
+    for ku in range(2):
+        for j in range(m["k_g"]):
+            want = 3.0 * (e[:, j, :] @ orc.as_f64(m["F"])[0, ku])
+            np.testing.assert_allclose(cl[:, ku * k_x + 2 + j], want, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("act", ["relu", "silu"])
+def test_generated_embeddings_loop_by_loop(act):
+    import math
+    rng = np.random.default_rng(44)
+    m = small_generated(rng, N=5, act=act, scale=1.7)
+    Wa, ba, Wb, bb = (orc.as_f64(t) for t in m["gen"])
+    model = orc.MolModel(m["G"], m["gx"], m["W1"], m["b1"], m["W2"], m["b2"], 1.7, act, seed=m["seed"], gen_mlp=m["gen"])
+    got = orc.mol_scores(model, m["F"], m["gu"])
+    Ff, guf, Gc, sd = orc.as_f64(m["F"]), orc.as_f64(m["gu"]), orc.as_f64(m["G"]), orc.as_f64(m["seed"])
+    k_u, d, k_c, k_g = 2, m["d"], 2, m["k_g"]
+    k_x = k_c + k_g
+    f_act = (lambda v: max(v, 0.0)) if act == "relu" else (lambda v: v / (1.0 + math.exp(-v)))
+    for b in range(3):
+        for n in range(5):
+            hid = [f_act(ba[u] + sum(Wa[u, i] * sd[n, i] for i in range(sd.shape[1]))) for u in range(Wa.shape[0])]
+            e = [bb[f] + sum(Wb[f, u] * hid[u] for u in range(len(hid))) for f in range(k_g * d)]
+            rows = [[Gc[n, kx, j] for j in range(d)] for kx in range(k_c)]
+            for j in range(k_g):
+                chunk = e[j * d:(j + 1) * d]
+                nrm = math.sqrt(sum(v * v for v in chunk))
+                rows.append([v / nrm for v in chunk])
+            cl = [1.7 * sum(Ff[b, p // k_x, j] * rows[p % k_x][j] for j in range(d)) for p in range(k_u * k_x)]
+            x = cl + guf[b].tolist() + model.gx[n].tolist()
+            h1 = [f_act(model.b1[h] + sum(model.W1[h, i] * x[i] for i in range(len(x)))) for h in range(model.W1.shape[0])]
+            z = [model.b2[p] + sum(model.W2[p, h] * h1[h] for h in range(len(h1))) for p in range(len(cl))]
+            mz = max(z)
+            w = [math.exp(v - mz) for v in z]
+            phi = sum(wi * ci for wi, ci in zip(w, cl)) / sum(w)
+            assert abs(got[b, n] - phi) < 1e-12
