@@ -403,6 +403,9 @@ def main():
     ap.add_argument("--gate", default="config", choices=["config", "decomposed"],
                     help="decomposed: Algorithm 1's gate (user / item / cross MLPs, uw*xw + cw, SiLU) instead of the workload's "
                          "concatenated MLP; a different model, reported as such")
+    ap.add_argument("--gen-items", action="store_true",
+                    help="generate the last 2 of the k_x item-side embeddings on the fly from a cached 32-d seed (Section 3.1) instead "
+                         "of caching them; a different model (fewer bytes gathered per candidate, more matrix-core work), reported as such")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true", help="skip the comparison of the returned results with the CPU oracle")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the bare read / bare gather ceiling measurements")
@@ -426,7 +429,16 @@ def main():
 
     if wl.Kp == 0:
         return exhaustive(args, m, wl, dev)
-    items, q, gw = generate(wl, dev)
+    gen = None
+    if args.gen_items:
+        import synth
+        K_G, D_S, D_HG = 2, 32, 64
+        items, _, _ = generate(wl.replace(k_x=wl.k_x - K_G), dev)       # the cache holds k_x - 2 embeddings per item
+        cen = synth.make_centres(wl, dev)
+        q, gw = synth.make_queries(wl, cen), synth.make_gate_weights(wl, dev)
+        gen = {"k_g": K_G, "d_s": D_S, "seed": synth.make_item_seeds(wl, cen, D_S), "mlp": synth.make_gen_mlp(wl, dev, K_G, D_S, D_HG)}
+    else:
+        items, q, gw = generate(wl, dev)
     t0 = time.time()
     int8 = args.stage1 == "int8"
     x1, q1 = items["x1"], q["q1"]
@@ -441,7 +453,8 @@ def main():
                                    act=wl.act, borrow=True, user_mlp=user_mlp, item_mlp=item_mlp)
     else:
         corpus = m.mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u,
-                                   logit_scale=wl.logit_scale, act=wl.act, borrow=True)
+                                   logit_scale=wl.logit_scale, act=wl.act, borrow=True,
+                                   item_seed=gen["seed"] if gen else None, gen_mlp=gen["mlp"] if gen else None)
     log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
 
     B, Kp, k = wl.B, wl.Kp, wl.k
@@ -489,13 +502,15 @@ def main():
     scan_bytes = wl.N * wl.d1 * (1 if int8 else (4 if wl.stage1_dtype == "f32" else 2))
     achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
     mol_ms, mol_n = prof["mol_score"]
-    gather_bytes = B * Kp * (wl.k_x * wl.d_p * 2 + (wl.P * 4 if decomposed else wl.H * 2) + 4 + 4)
+    k_cached = wl.k_x - (gen["k_g"] if gen else 0)
+    bytes_per_cand = k_cached * wl.d_p * 2 + (gen["d_s"] * 2 if gen else 0) + (wl.P * 4 if decomposed else wl.H * 2) + 4 + 4
+    gather_bytes = B * Kp * bytes_per_cand
     mol_flops = B * Kp * (2 * wl.P * wl.d_p + 4 * wl.P * wl.H)
 
     # hardware-counter readings: only those taken on exactly the sources compiled now (profiles/pmc_table.md)
     variant = wl.name + ("/int8" if int8 else "")
     scan_ctr = counters_for("k_stage1_scan", variant) if (not args.n_items and args.mode == 0) else None
-    mol_ctr = counters_for("k_mol_score", wl.name) if (not args.n_items and not decomposed) else None
+    mol_ctr = counters_for("k_mol_score", wl.name) if (not args.n_items and not decomposed and not gen) else None
     traffic = None
     if scan_ctr and "FETCH_SIZE KiB" in scan_ctr:
         traffic = (scan_ctr["FETCH_SIZE KiB"] * scan_ctr.get("fetch scale", 1.0)
@@ -519,7 +534,8 @@ def main():
         "dtype": "int8 stage 1 (int32 scores) + bf16 MoL" if int8 else ("bf16" if wl.stage1_dtype != "f32" else "f32"),
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: N={wl.N}, B={B}, K'={Kp}, P={wl.k_u}x{wl.k_x}, d_P={wl.d_p}, H={wl.H}, k={k}, "
-                               f"h-indexer mode {args.mode}, lambda={lam}" + (", INT8 stage 1" if int8 else "") + (", decomposed gate (Algorithm 1)" if decomposed else "")},
+                               f"h-indexer mode {args.mode}, lambda={lam}" + (", INT8 stage 1" if int8 else "") + (", decomposed gate (Algorithm 1)" if decomposed else "")
+                               + (f", {gen['k_g']} of {wl.k_x} item-side embeddings generated on the fly from a {gen['d_s']}-d seed (Section 3.1)" if gen else "")},
         "roofline": {"kernel": "k_stage1_scan (corpus scan + threshold filter)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "traffic_unit": "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, calibrated; null unless measured on the sources compiled now)",
@@ -527,7 +543,7 @@ def main():
                      "avg_launch_ms": scan_ms / max(1, scan_n), "launches": scan_n},
         "kernels_ms_per_step": {name: v[0] / args.steps for name, v in prof.items() if v[1]},
         "kernels_note": "from a second, untimed set of steps with every kernel group bracketed by events",
-        "mol_stage": {"gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,
+        "mol_stage": {"bytes_gathered_per_candidate": bytes_per_cand, "gather_GBps": gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 if mol_n else 0.0,
                       "gather_frac_of_hbm_peak": (gather_bytes / (mol_ms / max(1, mol_n) * 1e-3) / 1e9 / HBM_PEAK_GBS) if mol_n else 0.0,
                       "model_TFLOPs": mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 if mol_n else 0.0,
                       "model_frac_of_bf16_mfma_peak": (mol_flops / (mol_ms / max(1, mol_n) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS) if mol_n else 0.0,
@@ -537,7 +553,7 @@ def main():
     final_idx, final_score, final_cand = out2[0].clone(), out2[1].clone(), out1[0].clone()
 
     if not args.no_ceiling and not decomposed:
-        ceil = measured_ceilings(m, corpus, x1, final_cand, dev, gather_bytes)
+        ceil = measured_ceilings(m, corpus, x1, None if gen else final_cand, dev, gather_bytes)
         result["measured_ceiling"] = ceil
         if "stream_read" in ceil and scan_n:
             result["roofline"]["frac_of_measured_stream_read"] = ceil["stream_read"]["ms"] / (scan_ms / scan_n)
@@ -549,8 +565,9 @@ def main():
         log("comparing the returned results with the CPU oracle ...")
 
         def model_of(rows):
+            extra = dict(seed=bits(gen["seed"][rows]), gen_mlp=tuple(bits(t) for t in gen["mlp"])) if gen else {}
             return orc.MolModel(bits(items["G"][rows]), bits(items["gx"][rows]), bits(gw.W1), bits(gw.b1), bits(gw.W2),
-                                bits(gw.b2), wl.logit_scale, wl.act)
+                                bits(gw.b2), wl.logit_scale, wl.act, **extra)
 
         nq = min(4, B)
         result["accuracy"] = accuracy_report(wl, items, q, model_of, final_idx, final_score, final_cand, nq)
@@ -570,7 +587,7 @@ def main():
             torch.cuda.synchronize()
             result["int8_stage1_recall_vs_unquantised_topKp"] = recall_vs(real_sets, out1[0], out1[2].cpu().numpy(), Kp)
 
-    if wl.N <= 1_000_000 and not decomposed and not args.no_ceiling:
+    if wl.N <= 1_000_000 and not decomposed and not gen and not args.no_ceiling:
         result["cold_cache"] = cold_cache_ms(args, m, wl, items, q, gw, q1, x1, args.steps)
 
     if args.calibrate_copy:
@@ -580,7 +597,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_cpu_baseline and not decomposed:
+    if not args.no_cpu_baseline and not decomposed and not gen:
         log("timing the CPU oracle on a slice of the workload ...")
         result["cpu_baseline"] = cpu_baseline(wl, items, q, gw, min(wl.N, 4_000_000), 16384)
     print(json.dumps(result), flush=True)

@@ -103,6 +103,25 @@ typedef struct {
    * serves in FP16; a model trained in BF16 converts to it without rounding.  0 or MOL_BF16 = bfloat16.
    */
   int32_t mol_dtype;
+  /*
+   * Item-side embeddings generated on the fly (Section 3.1, item-side bullet: accelerator memory limits how many item
+   * embeddings can be cached, so some are produced at query time by a learned MLP, trading compute for memory).
+   * k_x_gen > 0: of the k_x item-side embeddings of an item only the first k_x - k_x_gen are cached (item_embs is then
+   * bf16 [N, k_x - k_x_gen, d_p]); the last k_x_gen are computed inside the scoring kernel for every candidate:
+   *   e   = Wg2 * act(Wg1 * item_seed[n] + bg1) + bg2            (k_x_gen * d_p numbers)
+   *   g_j = e[j*d_p : (j+1)*d_p] / max(||.||_2, 1e-12)            (Eq. 9: every component embedding is L2-normalised)
+   * and take the places k_x - k_x_gen .. k_x - 1 in the item-side component order.  The seed, both weight matrices and the
+   * hidden units enter the matrix cores as IEEE half (bf16 inputs convert exactly), the generated embeddings are rounded
+   * once to half.  Concatenated gate only; (k_u, k_x, d_p, H, k_x_gen, d_s, d_hg) must be one of
+   * (4,4,64,64,2,32,64), (8,8,64,128,2,32,64), else MOL_EUNSUPPORTED.  mol_gather_items returns the cached embeddings.
+   */
+  int32_t k_x_gen;       /* 0 = every item-side embedding is cached */
+  int32_t d_s, d_hg;     /* seed width, hidden width of the generator */
+  const void *item_seed; /* device, bf16 [N, d_s]; copied (as half) by mol_corpus_pack */
+  const void *Wg1;       /* device, bf16 [d_hg, d_s] */
+  const float *bg1;      /* device, f32 [d_hg] or NULL */
+  const void *Wg2;       /* device, bf16 [k_x_gen * d_p, d_hg] */
+  const float *bg2;      /* device, f32 [k_x_gen * d_p] or NULL */
 } mol_config_t;
 
 /*
@@ -111,7 +130,8 @@ typedef struct {
  * L2-normalised by the caller, Eq. 9), and precomputes the item half of the first gating layer,
  * Xi[n] = W1[:, P+d_gu:] * item_gate[n] + b1, stored as bf16 [N, H] (decomposed gate: the item weights xw, f32 [N, P]).
  *   stage1_items : [N, d1] of stage1_dtype (fp32, bf16 or int8), or NULL when cfg->d1 == 0 (MoL-only use, Section 5.2.1 K' = X).
- *   item_embs    : bf16 [N, k_x, d_p].      item_gate : bf16 [N, d_gx]; not referenced after the call returns.
+ *   item_embs    : bf16 [N, k_x, d_p] ([N, k_x - k_x_gen, d_p] with generated embeddings).
+ *   item_gate    : bf16 [N, d_gx]; not referenced after the call returns.
  * Allocates device memory with hipMalloc; synchronises `stream` before returning.  *out is set on MOL_OK only.
  */
 mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *stage1_items, const void *item_embs,

@@ -46,6 +46,8 @@ class _Config(C.Structure):
         ("Wu1", C.c_void_p), ("bu1", C.c_void_p), ("Wu2", C.c_void_p), ("bu2", C.c_void_p),
         ("Wx1", C.c_void_p), ("bx1", C.c_void_p), ("Wx2", C.c_void_p), ("bx2", C.c_void_p),
         ("mol_dtype", C.c_int32),
+        ("k_x_gen", C.c_int32), ("d_s", C.c_int32), ("d_hg", C.c_int32),
+        ("item_seed", C.c_void_p), ("Wg1", C.c_void_p), ("bg1", C.c_void_p), ("Wg2", C.c_void_p), ("bg2", C.c_void_p),
     ]
 
 
@@ -152,14 +154,22 @@ class Corpus:
 def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tensor, item_gate: torch.Tensor,
                     W1: torch.Tensor, b1: Optional[torch.Tensor], W2: torch.Tensor, b2: Optional[torch.Tensor],
                     k_u: int, logit_scale: float = 1.0, act: str = "relu", borrow: bool = False,
-                    user_mlp=None, item_mlp=None) -> Corpus:
+                    user_mlp=None, item_mlp=None, item_seed: Optional[torch.Tensor] = None, gen_mlp=None) -> Corpus:
     """user_mlp / item_mlp = (Wa bf16 [d_h, d_in], ba f32 [d_h] or None, Wb bf16 [P, d_h], bb f32 [P] or None) select
-    Algorithm 1's decomposed gate; W1 [H, P], b1, W2 [P, H], b2 are then the cross MLP."""
+    Algorithm 1's decomposed gate; W1 [H, P], b1, W2 [P, H], b2 are then the cross MLP.
+    item_seed bf16 [N, d_s] and gen_mlp = (Wg1 [d_hg, d_s], bg1, Wg2 [k_g * d_p, d_hg], bg2): the last k_g item-side
+    embeddings are generated on the fly (Section 3.1); item_embs then holds the cached k_x - k_g."""
     lib = load_library()
     decomposed = user_mlp is not None or item_mlp is not None
     if decomposed and (user_mlp is None or item_mlp is None):
         raise ValueError("the decomposed gate needs both user_mlp and item_mlp")
     N, k_x, d_p = item_embs.shape
+    k_g = 0
+    if gen_mlp is not None:
+        if item_seed is None:
+            raise ValueError("gen_mlp needs item_seed")
+        k_g = gen_mlp[2].shape[0] // d_p
+        k_x += k_g                     # item_embs holds the cached embeddings only
     t16 = item_embs.dtype
     if t16 not in (torch.bfloat16, torch.float16):
         raise ValueError("item_embs must be bfloat16 or float16")
@@ -192,6 +202,18 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
         raise ValueError("inconsistent model shapes")
     cfg = _Config()
     cfg.mol_dtype = 3 if t16 == torch.float16 else 1
+    if k_g:
+        Wg1, bg1, Wg2, bg2 = gen_mlp
+        _dev(item_seed, t16, "item_seed")
+        _dev(Wg1, t16, "Wg1")
+        _dev(Wg2, t16, "Wg2")
+        for bias in (bg1, bg2):
+            if bias is not None:
+                _dev(bias, torch.float32, "generator bias")
+        if item_seed.shape[0] != N or Wg1.shape[1] != item_seed.shape[1] or Wg2.shape != (k_g * d_p, Wg1.shape[0]):
+            raise ValueError("inconsistent generator shapes")
+        cfg.k_x_gen, cfg.d_s, cfg.d_hg = k_g, item_seed.shape[1], Wg1.shape[0]
+        cfg.item_seed, cfg.Wg1, cfg.bg1, cfg.Wg2, cfg.bg2 = _ptr(item_seed), _ptr(Wg1), _ptr(bg1), _ptr(Wg2), _ptr(bg2)
     if decomposed:
         cfg.gate_form = 1
         cfg.d_hu, cfg.d_hx = user_mlp[0].shape[0], item_mlp[0].shape[0]
@@ -219,8 +241,10 @@ def mol_corpus_pack(stage1_items: Optional[torch.Tensor], item_embs: torch.Tenso
     _check(lib.mol_corpus_pack(C.byref(cfg), _ptr(stage1_items), _ptr(item_embs), _ptr(item_gate), _stream(),
                                C.byref(out)))
     keep = (stage1_items, item_embs) if borrow else None
-    return Corpus(out.value, N, cfg.d1, None if stage1_items is None else stage1_items.dtype, k_u, k_x, d_p, H, d_gu,
-                  keep, t16)
+    corpus = Corpus(out.value, N, cfg.d1, None if stage1_items is None else stage1_items.dtype, k_u, k_x, d_p, H, d_gu,
+                    keep, t16)
+    corpus.k_g = k_g
+    return corpus
 
 
 def quantize_int8(src: torch.Tensor, scale: float, out: Optional[torch.Tensor] = None) -> torch.Tensor:
@@ -283,7 +307,8 @@ def gather_items(corpus: Corpus, cand_idx: torch.Tensor, out: Optional[torch.Ten
     _dev(cand_idx, torch.int32, "cand_idx")
     B, Kp = cand_idx.shape
     if out is None:
-        out = torch.empty(B, Kp, corpus.k_x, corpus.d_p, dtype=corpus.mol_dtype, device=cand_idx.device)
+        out = torch.empty(B, Kp, corpus.k_x - getattr(corpus, "k_g", 0), corpus.d_p, dtype=corpus.mol_dtype,
+                          device=cand_idx.device)
     _dev(out, corpus.mol_dtype, "out")
     _check(load_library().mol_gather_items(corpus.handle, _ptr(cand_idx), B, Kp, _ptr(out), _stream()))
     return out

@@ -99,6 +99,7 @@ extern "C" mol_status_t mol_bench_gather(const mol_corpus_t *c, const int32_t *c
                                          void *sink, void *stream) {
   if (!c || !cand_idx || !sink || B < 1 || Kp < 1 || blocks < 1)
     return mol_fail(MOL_EINVAL, "mol_bench_gather: corpus, cand_idx, sink, B, Kp, blocks >= 1 are required");
+  if (c->k_g > 0) return mol_fail(MOL_EUNSUPPORTED, "mol_bench_gather: not built for corpora with generated embeddings");
   const char *embs = static_cast<const char *>(c->embs), *xi = static_cast<const char *>(c->xi);
   hipStream_t st = static_cast<hipStream_t>(stream);
   uint32_t *sk = static_cast<uint32_t *>(sink);

@@ -133,6 +133,12 @@ struct mol_corpus {
   float *xw;            // f32 [N, P]
   void *wu1, *wu2;      // bf16 [d_hu, d_gu], bf16 [P, d_hu]
   float *bu1, *bu2, *b1c;  // f32 [d_hu], f32 [P], f32 [H] (zeros when the caller gave none)
+  // item embeddings generated on the fly (Section 3.1): the last k_g of the k_x item-side embeddings come from a 2-layer
+  // MLP on a cached seed; embs then holds k_x - k_g embeddings per item
+  int32_t k_g, d_s, d_hg;
+  void *seed;              // half [N, d_s]
+  void *wg1_frag, *wg2_frag;  // half, MFMA fragment order
+  float *bg1, *bg2;        // f32 [d_hg], f32 [k_g * d_p]
 };
 
 // error plumbing (api.hip)
@@ -184,6 +190,7 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
                               const uint32_t *UP, int B, const int32_t *cand_idx, const int32_t *cand_count, int64_t Kp,
                               float *scores, hipStream_t st);
 bool mol_exh_fast_form(const mol_corpus *c);
+bool mol_gen_shape_supported(int k_u, int k_x, int d_p, int H, int k_g, int d_s, int d_hg);
 mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, int B, int64_t Kp, void *out, hipStream_t st);
 // select.hip
 size_t final_topk_workspace_bytes(int B, int64_t Kp, int k);

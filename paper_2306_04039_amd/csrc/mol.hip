@@ -35,6 +35,11 @@ struct MolArgs {
   const float *UW;       // decomposed gate: f32 [B, P] user weights
   const char *w1c_frag_h;   // the layer-1 / layer-2 fragments as IEEE half (exhaustive fast path)
   const char *w2_frag_h;
+  // item embeddings generated on the fly (Section 3.1): seed vectors and the generator MLP, all IEEE half
+  const char *seed;         // half [N, D_S]
+  const char *wg1_frag;     // half, MFMA fragment order [D_HG/16][D_S/32][64][8]
+  const char *wg2_frag;     // half, MFMA fragment order [K_G*D_P/16][D_HG/32][64][8] (k-slots permuted, see pack)
+  const float *bg1, *bg2;   // f32 [D_HG], f32 [K_G*D_P]
   const uint32_t *UP;       // [B][H/32][64]: U[b, 32 mt + l] as a half head | half remainder << 16 at [b][mt][l], l < 32,
                             // zeros at l >= 32 (the A operand of the extra k-step, one word per lane; exhaustive fast path)
   const int32_t *cand;   // [B, Kp] or nullptr (exhaustive: candidate c is item c)
@@ -64,6 +69,20 @@ struct MolShape {
   static constexpr size_t LDS = W1B + W2B + PT * 32 * 4 + 4 * WAVE_FLOATS * 4;
 };
 
+// Generator of on-the-fly item embeddings (Section 3.1): K_G of the K_X item-side embeddings come from a 2-layer MLP on a
+// cached seed of D_S numbers (hidden width D_HG) instead of the cache.  K_G = 0: none.
+template <int K_G, int D_P, int D_S, int D_HG>
+struct GenShape {
+  static constexpr int UT = D_HG / 16;            // 16-row tiles of layer 1 (hidden units)
+  static constexpr int SG1 = D_S / 32;            // k-steps of layer 1
+  static constexpr int FT = K_G * D_P / 16;       // 16-row tiles of layer 2 (output features)
+  static constexpr int SG2 = D_HG / 32;           // k-steps of layer 2
+  static constexpr int W1B = K_G ? UT * SG1 * 1024 : 0;  // bytes of the fragment buffers
+  static constexpr int W2B = K_G ? FT * SG2 * 1024 : 0;
+  static constexpr int BIAS_FLOATS = K_G ? D_HG + K_G * D_P : 0;
+  static constexpr size_t LDS = W1B + W2B + BIAS_FLOATS * 4;
+};
+
 __device__ __forceinline__ float act_fn(float x, int act) {
   return act == MOL_ACT_RELU ? fmaxf(x, 0.f) : x / (1.f + __expf(-x));
 }
@@ -84,26 +103,45 @@ __device__ __forceinline__ float act_fn(float x, int act) {
 //           matrix cores, U[b] and the cached Xi[n]).
 // FORM = 1: Algorithm 1's decomposedGating: z = SiLU(uw[b] * xw[n] + crossMLP(cl)), uw per query, xw cached per item.
 // F16: the 16-bit inputs are IEEE half instead of bfloat16 (same layouts, the half-precision MFMA forms).
-template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16>
-__global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
+// K_G > 0: the last K_G of the K_X item-side embeddings are generated per candidate inside the kernel (GenShape), the
+// item cache then holds K_X - K_G embeddings per item; such instances run 8 wavefronts per workgroup so that the
+// larger set of weights in LDS is shared by as many wavefronts per compute unit as before.
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16, int K_G = 0, int D_S = 32, int D_HG = 64>
+__global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
   using S = MolShape<K_U, K_X, D_P, H>;
+  using GS = GenShape<K_G, D_P, D_S, D_HG>;
   constexpr int P = S::P, MT = S::MT, S1 = S::S1, PT = S::PT, S2 = S::S2, SA = S::SA, CPR = S::CPR, RT = S::RT,
                 CLS = S::CLS;
+  constexpr int NW = K_G ? 8 : 4;     // wavefronts per workgroup
+  constexpr int NT = NW * 64;
+  constexpr int K_C = K_X - K_G;      // cached item-side embeddings per item
+  static_assert(!(EXH && K_G), "generated embeddings use the per-candidate form");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char *w1s = smem;
   char *w2s = smem + S::W1B;
-  float *b2s = reinterpret_cast<float *>(smem + S::W1B + S::W2B);
+  char *wg1s = smem + S::W1B + S::W2B;
+  char *wg2s = wg1s + GS::W1B;
+  float *bgs = reinterpret_cast<float *>(wg2s + GS::W2B);   // [D_HG] then [K_G * D_P]
+  float *b2s = bgs + GS::BIAS_FLOATS;
   const int wv = threadIdx.x >> 6;
   float *cl = b2s + PT * 32 + wv * S::WAVE_FLOATS;  // [32][CLS]
   float *Us = cl + 32 * CLS;                        // [H]
   float *UWs = Us + H;                              // [32 * PT] (FORM 1)
 
   // stage the weight fragments once per workgroup
-  for (int i = threadIdx.x; i < S::W1B / 16; i += 256)
+  for (int i = threadIdx.x; i < S::W1B / 16; i += NT)
     reinterpret_cast<uint4 *>(w1s)[i] = reinterpret_cast<const uint4 *>(a.w1c_frag)[i];
-  for (int i = threadIdx.x; i < S::W2B / 16; i += 256)
+  for (int i = threadIdx.x; i < S::W2B / 16; i += NT)
     reinterpret_cast<uint4 *>(w2s)[i] = reinterpret_cast<const uint4 *>(a.w2_frag)[i];
-  for (int i = threadIdx.x; i < PT * 32; i += 256) b2s[i] = a.b2[i];
+  for (int i = threadIdx.x; i < PT * 32; i += NT) b2s[i] = a.b2[i];
+  if constexpr (K_G > 0) {
+    for (int i = threadIdx.x; i < GS::W1B / 16; i += NT)
+      reinterpret_cast<uint4 *>(wg1s)[i] = reinterpret_cast<const uint4 *>(a.wg1_frag)[i];
+    for (int i = threadIdx.x; i < GS::W2B / 16; i += NT)
+      reinterpret_cast<uint4 *>(wg2s)[i] = reinterpret_cast<const uint4 *>(a.wg2_frag)[i];
+    for (int i = threadIdx.x; i < D_HG; i += NT) bgs[i] = a.bg1[i];
+    for (int i = threadIdx.x; i < K_G * D_P; i += NT) bgs[D_HG + i] = a.bg2[i];
+  }
   __syncthreads();
 
   const int lane = threadIdx.x & 63;
@@ -111,11 +149,12 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
   const int r16 = lane & 15, g = lane >> 4;   // 16x16 tiles: row (or ku column) / k-group
   const int64_t tpq = (a.Kp + 31) >> 5;       // tiles per query
   const int64_t ntiles = tpq * a.B;
-  const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
-  const int64_t nwaves = (int64_t)gridDim.x * 4;
+  const int64_t wave = (int64_t)blockIdx.x * NW + wv;
+  const int64_t nwaves = (int64_t)gridDim.x * NW;
 
   int cur_b = -1;
   uint4 Ff[SA];
+  uint4 Ffp[K_G ? SA : 1];  // K_G > 0: the user embeddings as halves in the k order of the generated rows
   constexpr int PD = RT < 8 ? RT : 8;
   uint4 A[PD][SA];
   uint2 xi[MT][4];      // FORM 0: cached item half of layer 1 (bf16 x 4)
@@ -169,6 +208,27 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
 #pragma unroll
       for (int s = 0; s < SA; ++s)
         Ff[s] = (r16 < K_U) ? ld16(a.F + ((size_t)(b * K_U + r16) * D_P + 32 * s + 8 * g) * 2) : make_uint4(0, 0, 0, 0);
+      if constexpr (K_G > 0) {
+        // k-slots e < 4 of group g hold d = 32 s + 4 g + e, slots e >= 4 hold d = 32 s + 16 + 4 g + (e - 4): the order in
+        // which the generator leaves its output in registers (two 16-row result tiles side by side)
+#pragma unroll
+        for (int s = 0; s < SA; ++s) {
+          uint2 lo = make_uint2(0, 0), hi = make_uint2(0, 0);
+          if (r16 < K_U) {
+            const char *fp = a.F + ((size_t)(b * K_U + r16) * D_P + 32 * s + 4 * g) * 2;
+            lo = *reinterpret_cast<const uint2 *>(fp);
+            hi = *reinterpret_cast<const uint2 *>(fp + 32);
+          }
+          if constexpr (F16) {
+            Ffp[s] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+          } else {  // bfloat16 -> half (exact for normal halves)
+            Ffp[s] = make_uint4(pack16x2<true>(dec16<false>(lo.x & 0xffffu), dec16<false>(lo.x >> 16)),
+                                pack16x2<true>(dec16<false>(lo.y & 0xffffu), dec16<false>(lo.y >> 16)),
+                                pack16x2<true>(dec16<false>(hi.x & 0xffffu), dec16<false>(hi.x >> 16)),
+                                pack16x2<true>(dec16<false>(hi.y & 0xffffu), dec16<false>(hi.y >> 16)));
+          }
+        }
+      }
       for (int i = lane; i < H; i += 64) Us[i] = a.U[(size_t)b * H + i];
       if constexpr (FORM == 1)
         for (int i = lane; i < 32 * PT; i += 64) UWs[i] = i < P ? a.UW[(size_t)b * P + i] : 0.f;
@@ -198,10 +258,65 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
     auto load_rows = [&](uint4(&dst)[SA], int rt, int item = -1) {
       const int ci = rt * CPR + r16 / K_X;
       const int nidx = __shfl(item < 0 ? idxc : item, ci);
-      const char *rowp = a.embs + (((size_t)nidx * K_X + (r16 % K_X)) * D_P + 8 * g) * 2;
+      const int kx = r16 % K_X;
+      const char *rowp = a.embs + (((size_t)nidx * K_C + (kx < K_C ? kx : 0)) * D_P + 8 * g) * 2;
 #pragma unroll
-      for (int s = 0; s < SA; ++s) dst[s] = ld16(rowp + 64 * s);
+      for (int s = 0; s < SA; ++s) dst[s] = (K_G == 0 || kx < K_C) ? ld16(rowp + 64 * s) : make_uint4(0, 0, 0, 0);
     };
+    // ---- G: the generated item embeddings of the tile's 32 candidates, 16 at a time, all in registers -------------------
+    // 16x16x32 half MFMAs with the weights as the row operand and the candidates as columns: lane (r16, g) ends up with
+    // rows 4 g + j of every 16-row result tile for candidate r16, which -- two tiles side by side -- is an 8-value k
+    // group of the next product's column operand, in the k order the weight fragments / Ffp were laid out for.
+    uint4 Agen[K_G ? 2 : 1][K_G ? K_G : 1][SA];
+    if constexpr (K_G > 0) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int gidx = __shfl(idxc, 16 * hf + r16);
+        uint4 sd[GS::SG1];
+#pragma unroll
+        for (int s = 0; s < GS::SG1; ++s) sd[s] = ld16(a.seed + ((size_t)gidx * D_S + 32 * s + 8 * g) * 2);
+        uint4 hb[GS::SG2];   // hidden units as halves: the column operand of layer 2
+        uint32_t *hw = reinterpret_cast<uint32_t *>(hb);
+#pragma unroll
+        for (int ut = 0; ut < GS::UT; ++ut) {
+          const float4 bi = *reinterpret_cast<const float4 *>(&bgs[16 * ut + 4 * g]);
+          f32x4 acc = {bi.x, bi.y, bi.z, bi.w};
+#pragma unroll
+          for (int s = 0; s < GS::SG1; ++s)
+            acc = mfma16_16x16x32<true>(*reinterpret_cast<const uint4 *>(wg1s + ((ut * GS::SG1 + s) * 64 + lane) * 16), sd[s], acc);
+          // tile ut -> words 2 (ut % 2), 2 (ut % 2) + 1 of k-step ut / 2
+          hw[4 * (ut >> 1) + 2 * (ut & 1)] = pack16x2<true>(act_fn(acc[0], a.act), act_fn(acc[1], a.act));
+          hw[4 * (ut >> 1) + 2 * (ut & 1) + 1] = pack16x2<true>(act_fn(acc[2], a.act), act_fn(acc[3], a.act));
+        }
+#pragma unroll
+        for (int kg = 0; kg < K_G; ++kg) {
+          f32x4 ev[D_P / 16];
+          float ss = 0.f;
+#pragma unroll
+          for (int dt = 0; dt < D_P / 16; ++dt) {
+            const int ft = kg * (D_P / 16) + dt;
+            const float4 bi = *reinterpret_cast<const float4 *>(&bgs[D_HG + 16 * ft + 4 * g]);
+            f32x4 acc = {bi.x, bi.y, bi.z, bi.w};
+#pragma unroll
+            for (int s = 0; s < GS::SG2; ++s)
+              acc = mfma16_16x16x32<true>(*reinterpret_cast<const uint4 *>(wg2s + ((ft * GS::SG2 + s) * 64 + lane) * 16), hb[s], acc);
+            ev[dt] = acc;
+            ss += (acc[0] * acc[0] + acc[1] * acc[1]) + (acc[2] * acc[2] + acc[3] * acc[3]);
+          }
+          // L2 norm over the D_P values of (candidate, kg): they sit in the four lanes r16 + 16 g
+          ss += __shfl_xor(ss, 16);
+          ss += __shfl_xor(ss, 32);
+          const float inv = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+#pragma unroll
+          for (int sa = 0; sa < SA; ++sa)
+            Agen[hf][kg][sa] = make_uint4(pack16x2<true>(ev[2 * sa][0] * inv, ev[2 * sa][1] * inv),
+                                          pack16x2<true>(ev[2 * sa][2] * inv, ev[2 * sa][3] * inv),
+                                          pack16x2<true>(ev[2 * sa + 1][0] * inv, ev[2 * sa + 1][1] * inv),
+                                          pack16x2<true>(ev[2 * sa + 1][2] * inv, ev[2 * sa + 1][3] * inv));
+        }
+      }
+    }
+
     constexpr int PFR = MOL_PF_ROWS < PD ? MOL_PF_ROWS : PD;
     if (EXH ? (new_items || RT > PD) : true) {
 #pragma unroll
@@ -227,6 +342,27 @@ __global__ __launch_bounds__(256) void k_mol_score(MolArgs a) {
             cl[(rt * CPR + (4 * g + j) / K_X) * CLS + r16 * K_X + (4 * g + j) % K_X] = acc[j] * a.logit_scale;
         }
       }
+    }
+    if constexpr (K_G > 0) {
+      // logits of the generated embeddings: rows = 16 candidates, columns = ku; they take places K_C .. K_X - 1 of each
+      // user's group of K_X components (after the cached tiles above have written those places with zeros)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+        for (int kg = 0; kg < K_G; ++kg) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int sa = 0; sa < SA; ++sa) acc = mfma16_16x16x32<true>(Agen[hf][kg][sa], Ffp[sa], acc);
+          const float v0 = acc[0] * a.logit_scale, v1 = acc[1] * a.logit_scale, v2 = acc[2] * a.logit_scale,
+                      v3 = acc[3] * a.logit_scale;  // read before the branch
+          if (r16 < K_U) {
+            float *dst = &cl[(16 * hf + 4 * g) * CLS + r16 * K_X + K_C + kg];
+            dst[0] = v0;
+            dst[CLS] = v1;
+            dst[2 * CLS] = v2;
+            dst[3 * CLS] = v3;
+          }
+        }
     }
     if (have_next) {  // the row registers are free: start the next tile's first rows
       idxc_n = (idx_n >= 0 && idx_n < a.N) ? idx_n : 0;
@@ -666,10 +802,13 @@ __global__ __launch_bounds__(256) void k_user_weights(const uint16_t *wu1, const
   for (int h = threadIdx.x; h < H; h += 256) U[(size_t)b * H + h] = b1c[h];
 }
 
-template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16>
+template <int K_U, int K_X, int D_P, int H, bool EXH, int FORM, bool F16, int K_G = 0, int D_S = 32, int D_HG = 64>
 mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
   using S = MolShape<K_U, K_X, D_P, H>;
-  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM, F16>;
+  using GS = GenShape<K_G, D_P, D_S, D_HG>;
+  constexpr int NW = K_G ? 8 : 4;  // wavefronts per workgroup, as in the kernel
+  constexpr size_t LDS = S::W1B + S::W2B + GS::LDS + S::PT * 32 * 4 + (size_t)NW * S::WAVE_FLOATS * 4;
+  auto kern = k_mol_score<K_U, K_X, D_P, H, EXH, FORM, F16, K_G, D_S, D_HG>;
   // launch shape of this instantiation, found once per process (one GPU; concurrent first calls are serialised)
   static std::mutex mu;
   static bool configured = false;
@@ -681,19 +820,19 @@ mol_status_t launch_shape(const MolArgs &a, hipStream_t st) {
       HIP_TRY(hipGetDevice(&dev));
       HIP_TRY(hipDeviceGetAttribute(&sm_count, hipDeviceAttributeMultiprocessorCount, dev));
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)S::LDS));
-      HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, S::LDS));
+                                  (int)LDS));
+      HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, NW * 64, LDS));
       if (per_sm < 1) per_sm = 1;
       configured = true;
     }
   }
   const int64_t ntiles = EXH ? ((a.Kp + 31) / 32) * ((a.B + MOL_QCHUNK - 1) / MOL_QCHUNK) : ((a.Kp + 31) / 32) * a.B;
   int64_t grid = (int64_t)sm_count * per_sm;
-  const int64_t need = (ntiles + 3) / 4;
+  const int64_t need = (ntiles + NW - 1) / NW;
   if (grid > need) grid = need;
   if (grid < 1) grid = 1;
   ProfScope ps(MOL_PROF_MOL_SCORE, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), S::LDS, st, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * 64), LDS, st, a);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
 }
@@ -761,7 +900,21 @@ bool mol_shape_supported(int k_u, int k_x, int d_p, int H);
   X(16, 1, 32, 32)        \
   X(8, 2, 128, 96)
 
+// (k_u, k_x, d_p, H, k_x_gen, d_s, d_hg) the kernel with generated item embeddings is built for (concatenated gate only)
+#define MOL_GEN_SHAPES(X)     \
+  X(4, 4, 64, 64, 2, 32, 64)  \
+  X(8, 8, 64, 128, 2, 32, 64)
+
+bool mol_gen_shape_supported(int k_u, int k_x, int d_p, int H, int k_g, int d_s, int d_hg) {
+#define X(KU, KX, DP, HH, KG, DS, DHG) \
+  if (k_u == KU && k_x == KX && d_p == DP && H == HH && k_g == KG && d_s == DS && d_hg == DHG) return true;
+  MOL_GEN_SHAPES(X)
+#undef X
+  return false;
+}
+
 bool mol_exh_fast_form(const mol_corpus *c) {
+  if (c->k_g > 0) return false;
   if (c->gate_form != MOL_GATE_CONCAT || c->act != MOL_ACT_RELU || !c->w1c_frag_h || !c->w2_frag_h) return false;
 #define X(KU, KX, DP, HH) \
   if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH) return true;
@@ -816,7 +969,7 @@ __global__ __launch_bounds__(256) void k_gather_items(const char *embs, const in
 }
 
 mol_status_t launch_gather_items(const mol_corpus *c, const int32_t *cand_idx, int B, int64_t Kp, void *out, hipStream_t st) {
-  const int row_bytes = c->k_x * c->d_p * 2;
+  const int row_bytes = (c->k_x - c->k_g) * c->d_p * 2;  // the cached embeddings of an item
   const int64_t npairs = (int64_t)B * Kp;
   const int64_t total = npairs * (row_bytes / 16);
   int64_t grid = (total + 1023) / 1024;
@@ -864,6 +1017,20 @@ mol_status_t launch_mol_score(const mol_corpus *c, const void *user_embs, const 
   a.w1c_frag_h = static_cast<const char *>(c->w1c_frag_h);
   a.w2_frag_h = static_cast<const char *>(c->w2_frag_h);
   a.UP = UP;
+  a.seed = static_cast<const char *>(c->seed);
+  a.wg1_frag = static_cast<const char *>(c->wg1_frag);
+  a.wg2_frag = static_cast<const char *>(c->wg2_frag);
+  a.bg1 = c->bg1;
+  a.bg2 = c->bg2;
+  if (c->k_g > 0) {  // generated item embeddings: the per-candidate form also serves cand_idx = NULL (candidate c = item c)
+#define XG(KU, KX, DP, HH, KG, DS, DHG)                                                                               \
+  if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH && c->k_g == KG && c->d_s == DS && c->d_hg == DHG)   \
+    return c->f16 ? launch_shape<KU, KX, DP, HH, false, 0, true, KG, DS, DHG>(a, st)                                  \
+                  : launch_shape<KU, KX, DP, HH, false, 0, false, KG, DS, DHG>(a, st);
+    MOL_GEN_SHAPES(XG)
+#undef XG
+    return mol_fail(MOL_EUNSUPPORTED, "no generator instance for this shape");
+  }
   if (mol_exh_fast_form(c) && cand_idx == nullptr && UP != nullptr) {
 #define XF(KU, KX, DP, HH)                                                \
   if (c->k_u == KU && c->k_x == KX && c->d_p == DP && c->H == HH)         \

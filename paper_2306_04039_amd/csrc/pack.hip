@@ -58,6 +58,39 @@ __global__ void k_bf16_to_f16(const uint16_t *src, uint16_t *dst, int n) {
   if (i < n) dst[i] = __builtin_bit_cast(uint16_t, (_Float16)bf16_bits_to_f32(src[i]));
 }
 
+// 16-bit (bf16 or half) -> IEEE half over a large tensor (the seed table of generated item embeddings).
+__global__ void k_to_f16_big(const uint16_t *src, uint16_t *dst, int64_t n, bool src_f16) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src_f16 ? src[i] : __builtin_bit_cast(uint16_t, (_Float16)bf16_bits_to_f32(src[i]));
+}
+
+// Generator weights (Section 3.1, on-the-fly item embeddings) as the row operands of 16x16x32 half MFMAs: lane l holds row
+// l % 16 of a 16-row tile and the 8 k values of group l / 16.
+//   layer 1, tile ut, k-step s : Wg1[16 ut + l % 16][32 s + 8 (l / 16) + e]
+//   layer 2, tile ft, k-step s : Wg2[16 ft + l % 16][u(e)],  u(e) = 32 s + 4 (l / 16) + e for e < 4,
+//                                                                   32 s + 16 + 4 (l / 16) + (e - 4) otherwise
+// (the hidden units reach layer 2 as two 16-row result tiles side by side: lane group g holds rows 4 g .. 4 g + 3 of each).
+__global__ void k_pack_gen_weights(const uint16_t *Wg1, const uint16_t *Wg2, int d_s, int d_hg, int n_out, bool src_f16,
+                                   uint16_t *wg1_frag, uint16_t *wg2_frag) {
+  const int SG1 = d_s / 32, SG2 = d_hg / 32;
+  const int n1 = (d_hg / 16) * SG1 * 512, n2 = (n_out / 16) * SG2 * 512;
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  auto cv = [&](uint16_t v) -> uint16_t { return src_f16 ? v : __builtin_bit_cast(uint16_t, (_Float16)bf16_bits_to_f32(v)); };
+  if (i < n1) {
+    const int e = i & 7, l = (i >> 3) & 63, f = i >> 9;
+    const int ut = f / SG1, s = f % SG1;
+    wg1_frag[i] = cv(Wg1[(size_t)(16 * ut + (l & 15)) * d_s + 32 * s + 8 * (l >> 4) + e]);
+    return;
+  }
+  i -= n1;
+  if (i < n2) {
+    const int e = i & 7, l = (i >> 3) & 63, f = i >> 9;
+    const int ft = f / SG2, s = f % SG2, g = l >> 4;
+    const int u = e < 4 ? 32 * s + 4 * g + e : 32 * s + 16 + 4 * g + (e - 4);
+    wg2_frag[i] = cv(Wg2[(size_t)(16 * ft + (l & 15)) * d_hg + u]);
+  }
+}
+
 // Xi^T[h, n] = W1x[h, :] . gx[n, :] + b1[h] on 32x32x16 MFMA: A = W1x rows (hidden units), B = item rows.
 // A wavefront takes 32 items; lane (c = lane%32, half) loads its item's row chunks once and walks the hidden tiles.
 template <int KS, bool F16>  // d_gx / 16; 16-bit type of the inputs and of Xi
@@ -218,6 +251,15 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     return mol_fail(MOL_EINVAL, "mol_dtype must be 0, MOL_BF16 or MOL_F16");
   const bool decomposed = cfg->gate_form == MOL_GATE_DECOMPOSED;
   if (cfg->gate_form != MOL_GATE_CONCAT && !decomposed) return mol_fail(MOL_EINVAL, "bad gate_form");
+  const int k_g = cfg->k_x_gen;
+  if (k_g < 0) return mol_fail(MOL_EINVAL, "k_x_gen must be >= 0");
+  if (k_g > 0) {
+    if (!cfg->item_seed || !cfg->Wg1 || !cfg->Wg2) return mol_fail(MOL_EINVAL, "generated embeddings need item_seed, Wg1 and Wg2");
+    if (decomposed) return mol_fail(MOL_EUNSUPPORTED, "generated embeddings are built for the concatenated gate only");
+    if (!mol_gen_shape_supported(cfg->k_u, cfg->k_x, cfg->d_p, cfg->H, k_g, cfg->d_s, cfg->d_hg))
+      return mol_fail(MOL_EUNSUPPORTED, "no kernel with generated embeddings for k_u=%d k_x=%d d_p=%d H=%d k_x_gen=%d d_s=%d d_hg=%d",
+                      cfg->k_u, cfg->k_x, cfg->d_p, cfg->H, k_g, cfg->d_s, cfg->d_hg);
+  }
   if (decomposed) {
     if (!cfg->Wu1 || !cfg->Wu2 || !cfg->Wx1 || !cfg->Wx2)
       return mol_fail(MOL_EINVAL, "the decomposed gate needs Wu1, Wu2, Wx1 and Wx2");
@@ -244,6 +286,9 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   c->gate_form = cfg->gate_form;
   c->f16 = cfg->mol_dtype == MOL_F16;
   c->d_hu = decomposed ? cfg->d_hu : 0;
+  c->k_g = k_g;
+  c->d_s = k_g ? cfg->d_s : 0;
+  c->d_hg = k_g ? cfg->d_hg : 0;
   (void)hipGetDevice(&c->device);
 
   const int P = c->P, H = c->H;
@@ -278,9 +323,18 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
   } else {
     ALLOC(c->xi, (size_t)c->N * H * 2)
   }
+  const size_t ng1 = k_g ? (size_t)(cfg->d_hg / 16) * (cfg->d_s / 32) * 512 : 0;
+  const size_t ng2 = k_g ? (size_t)(k_g * cfg->d_p / 16) * (cfg->d_hg / 32) * 512 : 0;
+  if (k_g) {
+    ALLOC(c->seed, (size_t)c->N * cfg->d_s * 2)
+    ALLOC(c->wg1_frag, ng1 * 2)
+    ALLOC(c->wg2_frag, ng2 * 2)
+    ALLOC(c->bg1, (size_t)cfg->d_hg * 4)
+    ALLOC(c->bg2, (size_t)k_g * cfg->d_p * 4)
+  }
   void *s1copy = nullptr, *embcopy = nullptr;
   const size_t s1_bytes = (size_t)c->N * c->d1 * (c->stage1_dtype == MOL_F32 ? 4 : (c->stage1_dtype == MOL_BF16 ? 2 : 1));
-  const size_t emb_bytes = (size_t)c->N * c->k_x * c->d_p * 2;
+  const size_t emb_bytes = (size_t)c->N * (c->k_x - k_g) * c->d_p * 2;  // the cached embeddings
   if (c->d1 && !(cfg->flags & MOL_PACK_BORROW_STAGE1)) { ALLOC(s1copy, s1_bytes) }
   if (!(cfg->flags & MOL_PACK_BORROW_EMBS)) { ALLOC(embcopy, emb_bytes) }
 #undef ALLOC
@@ -328,6 +382,21 @@ extern "C" mol_status_t mol_corpus_pack(const mol_config_t *cfg, const void *sta
     if (e == hipSuccess) e = copy_or_zero(c->b1c, cfg->b1, (size_t)H * 4);
     if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "copy of the user-side gate weights failed: %s", hipGetErrorString(e));
     if (rc == MOL_OK) rc = launch_item_weights(c, cfg, item_gate, st);
+  }
+  if (rc == MOL_OK && k_g) {
+    const int64_t ns = c->N * cfg->d_s;
+    hipLaunchKernelGGL(k_to_f16_big, dim3((unsigned)((ns + 255) / 256 < 65536 ? (ns + 255) / 256 : 65536)), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(cfg->item_seed), static_cast<uint16_t *>(c->seed), ns, c->f16);
+    hipLaunchKernelGGL(k_pack_gen_weights, dim3((unsigned)((ng1 + ng2 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uint16_t *>(cfg->Wg1), static_cast<const uint16_t *>(cfg->Wg2), cfg->d_s, cfg->d_hg,
+                       k_g * cfg->d_p, c->f16, static_cast<uint16_t *>(c->wg1_frag), static_cast<uint16_t *>(c->wg2_frag));
+    hipError_t e = hipGetLastError();
+    auto copy_or_zero = [&](void *dst, const void *src, size_t bytes) -> hipError_t {
+      return src ? hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, st) : hipMemsetAsync(dst, 0, bytes, st);
+    };
+    if (e == hipSuccess) e = copy_or_zero(c->bg1, cfg->bg1, (size_t)cfg->d_hg * 4);
+    if (e == hipSuccess) e = copy_or_zero(c->bg2, cfg->bg2, (size_t)k_g * cfg->d_p * 4);
+    if (e != hipSuccess) rc = mol_fail(MOL_EHIP, "packing the generator failed: %s", hipGetErrorString(e));
   }
   if (rc == MOL_OK) {
     hipError_t e = hipStreamSynchronize(st);
@@ -425,6 +494,11 @@ extern "C" mol_status_t mol_corpus_free(mol_corpus_t *c) {
   if (c->bu1) (void)hipFree(c->bu1);
   if (c->bu2) (void)hipFree(c->bu2);
   if (c->b1c) (void)hipFree(c->b1c);
+  if (c->seed) (void)hipFree(c->seed);
+  if (c->wg1_frag) (void)hipFree(c->wg1_frag);
+  if (c->wg2_frag) (void)hipFree(c->wg2_frag);
+  if (c->bg1) (void)hipFree(c->bg1);
+  if (c->bg2) (void)hipFree(c->bg2);
   if (c->own_stage1 && c->stage1) (void)hipFree(const_cast<void *>(c->stage1));
   if (c->own_embs && c->embs) (void)hipFree(const_cast<void *>(c->embs));
   free(c);

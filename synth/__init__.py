@@ -9,5 +9,7 @@ from .generator import (  # noqa: F401
     item_chunk,
     make_items,
     make_queries,
+    make_item_seeds,
+    make_gen_mlp,
     ITEM_CHUNK,
 )

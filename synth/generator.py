@@ -39,6 +39,7 @@ _T_CENTRE_S, _T_CENTRE_M, _T_CENTRE_T = 11, 12, 13
 _T_W1, _T_W2, _T_B1, _T_B2 = 21, 22, 23, 24
 _T_DEC = 50  # decomposed gate: tags 50..61
 _T_ITEM, _T_QUERY = 31, 41
+_T_SEED, _T_CENTRE_Z, _T_GEN = 35, 14, 70  # seeds of on-the-fly item embeddings, their centre table, the generator MLP
 
 
 @dataclasses.dataclass(frozen=True)
@@ -226,3 +227,33 @@ def make_queries(w: Workload, centres: Dict[str, torch.Tensor], B: Optional[int]
     F = _noisy_unit(centres["M"][z], w.k_u, w.sigma, _gen(w.seed, _T_QUERY, 2, dev)).to(torch.bfloat16)
     gu = _noisy_unit(centres["T"][z][:, : w.d_gu], 1, w.sigma, _gen(w.seed, _T_QUERY, 3, dev))[:, 0].to(torch.bfloat16)
     return {"z": z, "q1": q1 if w.stage1_dtype == "f32" else q1.to(torch.bfloat16), "F": F, "gu": gu}
+
+
+def make_item_seeds(w: Workload, centres: Dict[str, torch.Tensor], d_s: int) -> torch.Tensor:
+    """Seed vectors of the items (the cached input of the MLP that generates item-side embeddings on the fly): bf16
+    [N, d_s], noisy unit vectors around a fourth centre table, by the items' cluster ids (re-drawn from the same stream)."""
+    dev = centres["S"].device
+    Z = _unit_rows(torch.randn(w.n_clusters, d_s, generator=_gen(w.seed, _T_CENTRE_Z, 0, dev), device=dev, dtype=torch.float32))
+    out = torch.empty(w.N, d_s, device=dev, dtype=torch.bfloat16)
+    n_chunks = (w.N + ITEM_CHUNK - 1) // ITEM_CHUNK
+    for c in range(n_chunks):
+        lo = c * ITEM_CHUNK
+        n = min(w.N, lo + ITEM_CHUNK) - lo
+        z = _draw_clusters(n, centres["cdf"], _gen(w.seed, _T_ITEM, 4 * c + 0, dev))
+        out[lo: lo + n] = _noisy_unit(Z[z], 1, w.sigma, _gen(w.seed, _T_SEED, c, dev))[:, 0].to(torch.bfloat16)
+    return out
+
+
+def make_gen_mlp(w: Workload, device, k_g: int, d_s: int, d_hg: int, bias_scale: float = 0.1):
+    """Weights of the generator MLP (Xavier-uniform -> bf16, small uniform biases): (Wg1 [d_hg, d_s], bg1 [d_hg],
+    Wg2 [k_g * d_p, d_hg], bg2 [k_g * d_p])."""
+    def xavier(rows, cols, t):
+        a = math.sqrt(6.0 / (rows + cols))
+        g = _gen(w.seed, t, 0, device)
+        return ((torch.rand(rows, cols, generator=g, device=device, dtype=torch.float32) * 2 - 1) * a).to(torch.bfloat16)
+
+    def bias(n, t):
+        g = _gen(w.seed, t, 0, device)
+        return (torch.rand(n, generator=g, device=device, dtype=torch.float32) * 2 - 1) * bias_scale
+
+    return (xavier(d_hg, d_s, _T_GEN), bias(d_hg, _T_GEN + 1), xavier(k_g * w.d_p, d_hg, _T_GEN + 2), bias(k_g * w.d_p, _T_GEN + 3))
