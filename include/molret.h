@@ -151,8 +151,9 @@ mol_status_t mol_quantize_int8(const void *src, int src_dtype, int64_t n, float 
 /* Frees what pack allocated (device synchronising).  NULL is accepted. */
 mol_status_t mol_corpus_free(mol_corpus_t *corpus);
 
-/* Size queries (no device work; hindexer_workspace_bytes asks the HIP runtime for the device's occupancy figures, so the
- * device the corpus lives on must be current); return 0 on invalid arguments.  lambda <= 0 selects the default sample size. */
+/* Size queries (no device work); return 0 on invalid arguments.  lambda <= 0 selects the default sample size.  The first
+ * hindexer_workspace_bytes / hindexer_topk call of a process asks the HIP runtime for the occupancy of the scan kernels
+ * (once per kernel variant; later calls make no runtime queries), so the device the corpus lives on must be current. */
 size_t hindexer_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int64_t lambda);
 size_t mol_workspace_bytes(const mol_corpus_t *corpus, int B, int Kp, int k);
 

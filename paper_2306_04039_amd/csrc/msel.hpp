@@ -180,4 +180,4 @@ __device__ inline void msel_take_lowest_ties(const uint32_t *ties, uint32_t nt, 
 }
 
 __global__ void k_zero_u32(uint32_t *p, size_t n);
-#define MCNT_STRIDE 64  // uint32 per query in the counter block: [0] emitted, [1] ties parked, [2] "too many ties" flag
+#define MCNT_STRIDE 64  // uint32 per query in the counter block: [0] emitted, [1] ties parked

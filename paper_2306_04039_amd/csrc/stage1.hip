@@ -20,7 +20,6 @@
 
 #include "common.hpp"
 #include "msel.hpp"
-#include "select.hpp"
 
 // Tuning constants of the corpus scan (measured on MI355X at N = 1e8, B = 32).
 #ifndef MOL_SCAN_DEPTH
@@ -424,8 +423,10 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
 }
 
 // i-th sampled row: floor(N * hi32(SplitMix64 output i) / 2^32), stream state = seed + (i+1) * golden gamma.
-__global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64_t N) {
+// The same launch clears `nz` words at `zero` (the histograms and counters of the two radix selections of the call).
+__global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64_t N, uint32_t *zero, size_t nz) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (size_t z = (size_t)i; z < nz; z += (size_t)gridDim.x * blockDim.x) zero[z] = 0u;
   if (i >= lambda) return;
   uint64_t z = seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull;
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
@@ -486,13 +487,12 @@ __global__ void k_init_all_pass(float *thr, uint32_t *flags, uint32_t *gate, int
 
 // ---- survivors -> at most K' candidates (Section 4.1.2) ----------------------------------------------------------
 // sstat[b] = {survivors of query b, 1 if its lists cannot give the answer}: a list overflowed, or (exact mode) fewer
-// than K' survived, or the caller asked for the redo.  Such a query is left to the exact redo.
-__global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_t L, int64_t cap, int Kp, int mode,
-                                                     bool force, uint2 *sstat) {
-  __shared__ uint32_t s_tot[4], s_ovf[4];
-  const int b = blockIdx.x;
+// than K' survived, or the caller asked for the redo.  Such a query is left to the exact redo.  Workgroup-cooperative;
+// every thread returns the value.
+__device__ inline uint2 surv_status(const uint32_t *cnt, int64_t L, int64_t cap, int Kp, int mode, bool force, int b) {
+  __shared__ uint32_t s_tot[MSEL_THREADS / 64], s_ovf[MSEL_THREADS / 64];
   uint32_t tot = 0, ovf = 0;
-  for (int64_t i = threadIdx.x; i < L; i += 256) {
+  for (int64_t i = threadIdx.x; i < L; i += MSEL_THREADS) {
     const uint32_t c = cnt[(size_t)b * L + i];
     tot += c;
     ovf |= ((int64_t)c > cap) ? 1u : 0u;
@@ -506,12 +506,14 @@ __global__ __launch_bounds__(256) void k_surv_reduce(const uint32_t *cnt, int64_
     s_ovf[threadIdx.x >> 6] = ovf;
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    tot = s_tot[0] + s_tot[1] + s_tot[2] + s_tot[3];
-    ovf = s_ovf[0] | s_ovf[1] | s_ovf[2] | s_ovf[3];
-    const bool bad = ovf || force || (mode == MOL_HINDEXER_EXACT && tot < (uint32_t)Kp);
-    sstat[b] = make_uint2(tot, bad ? 1u : 0u);
+  tot = 0;
+  ovf = 0;
+  for (int i = 0; i < MSEL_THREADS / 64; ++i) {
+    tot += s_tot[i];
+    ovf |= s_ovf[i];
   }
+  const bool bad = ovf || force || (mode == MOL_HINDEXER_EXACT && tot < (uint32_t)Kp);
+  return make_uint2(tot, bad ? 1u : 0u);
 }
 
 // Walks lists [lo, hi) of query b.  A wavefront takes 32 lists at a time: the lanes fetch the counts with one load, then
@@ -561,12 +563,20 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
   }
 }
 
+// Pass 0 also works out the query's status from the list counts (every workgroup for itself; the first one records it
+// for the passes and kernels that follow).
 __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, const uint32_t *cnt, int64_t L,
-                                                            int64_t cap, const uint2 *sstat, int Kp, uint32_t *mhist,
-                                                            int B, int pass) {
+                                                            int64_t cap, uint2 *sstat, int Kp, uint32_t *mhist,
+                                                            int B, int pass, int mode, bool force) {
   __shared__ MselShared sh;
   const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
-  const uint2 stt = sstat[b];
+  uint2 stt;
+  if (pass == 0) {
+    stt = surv_status(cnt, L, cap, Kp, mode, force, b);
+    if (blk == 0 && threadIdx.x == 0) sstat[b] = stt;
+  } else {
+    stt = sstat[b];
+  }
   if (stt.y || stt.x <= (uint32_t)Kp) return;
   uint32_t prefix = 0;
   if (pass > 0) prefix = msel_cut(mhist, B, b, (uint32_t)Kp, pass, sh).prefix;
@@ -675,8 +685,17 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat
     const MselCut c = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
     nout = (uint32_t)Kp;
     if (c.krem != c.cnt) {  // only the krem lowest indices of the cnt items tied at the K'-th key are taken
-      if (c.cnt > MSEL_TIE_CAP) {
-        if (tid == 0) mcnt[(size_t)b * MCNT_STRIDE + 2] = 1u;  // left to the single-workgroup selection
+      if (c.cnt > MSEL_TIE_CAP) {  // more ties at the K'-th key than the tie buffer holds: left to the exact redo
+        if (tid == 0) {
+          ExactState s = {};
+          s.active = 1;
+          s.krem = (uint32_t)Kp;
+          s.idx_limit = 0xffffffffu;
+          state[b] = s;
+          flags[b] = 1u;
+          gate[0] = 1u;
+          cand_count[b] = -1;
+        }
         return;
       }
       const uint32_t base = (uint32_t)Kp - c.krem;
@@ -692,47 +711,6 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat
     oi[i] = -1;
     if (os) os[i] = -INFINITY;
   }
-}
-
-// Single-workgroup form of the same selection.  It runs for queries the multi-workgroup kernels hand over (more than
-// MSEL_TIE_CAP items tied at the K'-th key: `enable`).
-__global__ __launch_bounds__(SELECT_THREADS) void k_select_survivors(const uint2 *surv, const uint32_t *cnt, int64_t L,
-                                                                     int64_t cap, const uint2 *sstat, int Kp,
-                                                                     const uint32_t *enable,
-                                                                     int32_t *cand_idx, float *cand_score,
-                                                                     int32_t *cand_count) {
-  __shared__ SelectShared sh;
-  const int b = blockIdx.x, B = gridDim.x;
-  const int tid = threadIdx.x;
-  if (enable[(size_t)b * MCNT_STRIDE] == 0u) return;
-  const uint2 stt = sstat[b];
-  int32_t *oi = cand_idx + (size_t)b * Kp;
-  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
-  auto each = [&](auto f) {
-    for_each_survivor(surv, cnt, L, cap, B, b, 0, L, SELECT_THREADS / 64, [&](uint2 e, bool valid) {
-      if (valid) f(e.x, e.y);
-    });
-  };
-  const bool take_all = stt.x <= (uint32_t)Kp;
-  if (!take_all) block_select_kth<true>(each, (uint32_t)Kp, sh);
-  if (tid == 0) sh.out_count = 0;
-  __syncthreads();
-  each([&](uint32_t key, uint32_t idx) {
-    if (take_all || select_accept(key, idx, sh)) {
-      uint32_t slot = atomicAdd(&sh.out_count, 1u);
-      if (slot < (uint32_t)Kp) {
-        oi[slot] = (int32_t)idx;
-        if (os) os[slot] = key_to_f32(key);
-      }
-    }
-  });
-  __syncthreads();
-  const uint32_t nout = take_all ? stt.x : (uint32_t)Kp;
-  for (int64_t i = nout + tid; i < Kp; i += SELECT_THREADS) {
-    oi[i] = -1;
-    if (os) os[i] = -INFINITY;
-  }
-  if (tid == 0) cand_count[b] = (int32_t)nout;
 }
 
 // ---- launch helpers ----------------------------------------------------------------------------------------------
@@ -768,15 +746,30 @@ int device_cus() {
 
 // Workgroups (of 4 wavefronts) a scan over `ntiles` tiles is launched with: resident blocks, at most one tile each.
 // fixed_grid > 0 forces the grid (the survivor lists are laid out for a given number of wavefronts).
+// Resident workgroups per compute unit of one scan variant: asked of the runtime once per process and variant (the
+// answer, and the raised LDS limit that goes with it, do not change afterwards), so that a call makes no HIP queries.
+template <int DT, int EPI, bool GATHER>
+mol_status_t scan_occupancy(int nqg, int *per_sm_out) {
+  static std::atomic<int> cached[5] = {};  // by nqg (1, 2, 4); 0 = not asked yet
+  int v = cached[nqg].load(std::memory_order_acquire);
+  if (v == 0) {
+    auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
+    const size_t lds = scan_lds_bytes(EPI, nqg);
+    if (lds > 48 * 1024)
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, kern, 256, lds));
+    if (v < 1) v = 1;
+    cached[nqg].store(v, std::memory_order_release);
+  }
+  *per_sm_out = v;
+  return MOL_OK;
+}
+
 template <int DT, int EPI, bool GATHER>
 mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
-  auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
-  const size_t lds = scan_lds_bytes(EPI, nqg);
-  if (lds > 48 * 1024)
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   int per_sm = 0;
-  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_sm, kern, 256, lds));
-  if (per_sm < 1) per_sm = 1;
+  mol_status_t rc = scan_occupancy<DT, EPI, GATHER>(nqg, &per_sm);
+  if (rc != MOL_OK) return rc;
   constexpr int PER_CU = DT == MOL_INT8 ? MOL_SCAN_PER_CU_I8 : MOL_SCAN_PER_CU;
   if (per_sm > PER_CU) per_sm = PER_CU;
   const int cus = device_cus();
@@ -930,8 +923,10 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   uint32_t *mhist2 = mhist + (size_t)MSEL_PASSES * B * MSEL_BINS;
   uint32_t *mcnt = reinterpret_cast<uint32_t *>(ws + p.off_mcnt);
   uint32_t *tiebuf = reinterpret_cast<uint32_t *>(ws + p.off_tie);
-  {  // histograms and counters of both selections start at zero (they are contiguous in the workspace)
-    const size_t nz = (p.off_tie - p.off_mhist) / 4;
+  // histograms and counters of both selections start at zero (they are contiguous in the workspace); the kernel that
+  // draws the sample clears them on the side, otherwise a launch of its own does
+  const size_t nz = (p.off_tie - p.off_mhist) / 4;
+  if (!(p.sampling && !sample_idx)) {
     hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((nz + 1023) / 1024)), dim3(256), 0, st, mhist, nz);
     HIP_TRY(hipGetLastError());
   }
@@ -953,7 +948,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     const int32_t *rows = sample_idx;
     if (!rows) {
       hipLaunchKernelGGL(k_gen_sample, dim3((unsigned)((p.lambda + 255) / 256)), dim3(256), 0, st, samp, p.lambda,
-                         seed, (uint64_t)c->N);
+                         seed, (uint64_t)c->N, mhist, nz);
       HIP_TRY(hipGetLastError());
       rows = samp;
     }
@@ -999,8 +994,6 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
 
   ProfScope ps(MOL_PROF_SELECT, st);
   {
-    hipLaunchKernelGGL(k_surv_reduce, dim3(B), dim3(256), 0, st, cnt, p.L, p.cap, Kp, mode, force_redo, sstat);
-    HIP_TRY(hipGetLastError());
 #ifndef MOL_SURV_BLOCKS
 #define MOL_SURV_BLOCKS 1024
 #endif
@@ -1008,7 +1001,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     G = G < 1 ? 1 : (G > MOL_SURV_BLOCKS / 32 ? MOL_SURV_BLOCKS / 32 : G);
     for (int pass = 0; pass < MSEL_PASSES; ++pass) {
       hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
-                         pass);
+                         pass, mode, force_redo);
       HIP_TRY(hipGetLastError());
     }
     hipLaunchKernelGGL(k_surv_emit, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
@@ -1016,9 +1009,6 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, B, mcnt, tiebuf, flags, gate,
                        state, hist, cand_idx, cand_score, cand_count);
-    HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(k_select_survivors, dim3(B), dim3(SELECT_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp,
-                       mcnt + 2, cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
   }
 
