@@ -406,6 +406,7 @@ def main():
     ap.add_argument("--gen-items", action="store_true",
                     help="generate the last 2 of the k_x item-side embeddings on the fly from a cached 32-d seed (Section 3.1) instead "
                          "of caching them; a different model (fewer bytes gathered per candidate, more matrix-core work), reported as such")
+    ap.add_argument("--lam", type=int, default=0, help="h-indexer sample size (default: the library's, max(1 %% of N, 256 N / K'))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true", help="skip the comparison of the returned results with the CPU oracle")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the bare read / bare gather ceiling measurements")
@@ -458,7 +459,7 @@ def main():
     log(f"mol_corpus_pack: {time.time() - t0:.1f}s")
 
     B, Kp, k = wl.B, wl.Kp, wl.k
-    lam = m.hindexer_default_lambda(corpus, Kp)
+    lam = args.lam if args.lam > 0 else m.hindexer_default_lambda(corpus, Kp)
     ws1 = torch.empty(m.hindexer_workspace_bytes(corpus, B, Kp, lam), dtype=torch.uint8, device=dev)
     ws2 = torch.empty(m.mol_workspace_bytes(corpus, B, Kp, k), dtype=torch.uint8, device=dev)
     out1 = (torch.empty(B, Kp, dtype=torch.int32, device=dev), torch.empty(B, Kp, dtype=torch.float32, device=dev),

@@ -99,6 +99,9 @@ __device__ __forceinline__ float act_fn(float x, int act) {
 #ifndef MOL_PF_XI
 #define MOL_PF_XI 0    // also start the next tile's cached item-gate loads early
 #endif
+// With MOL_PF_XI = 1 a conditional load would sit between the layer-2 MFMA chain and the first read of its accumulators
+// (the branch pattern after which matrix-core results were once read too early in the corpus scan): not supported.
+static_assert(MOL_PF_XI == 0, "MOL_PF_XI = 1 needs mfma_settle() after the prefetch");
 // FORM = 0: the gate is one 2-layer MLP on [cl | user feature | item feature] (first layer split into a cross part on the
 //           matrix cores, U[b] and the cached Xi[n]).
 // FORM = 1: Algorithm 1's decomposedGating: z = SiLU(uw[b] * xw[n] + crossMLP(cl)), uw per query, xw cached per item.

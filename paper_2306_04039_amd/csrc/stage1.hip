@@ -325,9 +325,13 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
             if ((cnt[g] & (RING - 1)) == 0) flush_ring(g, RING);
           };
           if (tile != ntiles - 1) {
+            // the wavefront-wide test first: when no lane passes (all but ~2 % of the compares) the cost is the compare
+            // and one scalar branch on its mask, with no save / restore of the execution mask
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-              if (acc[g][j] > thr[g]) [[unlikely]] append(j);
+              if (__builtin_amdgcn_ballot_w64(acc[g][j] > thr[g]) != 0) [[unlikely]] {
+                if (acc[g][j] > thr[g]) append(j);
+              }
           } else {
 #pragma unroll
             for (int j = 0; j < 16; ++j)
