@@ -120,15 +120,20 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
 #ifndef MOL_TOPK_MAXG
 #define MOL_TOPK_MAXG 32
 #endif
-static int topk_slices(int64_t Kp, int k) {
+// A level-1 workgroup pays a fixed price per radix pass (histogram, scans, barriers), so large batches take fewer,
+// longer slices: at most about 8192 level-1 workgroups per call, never fewer than 8 slices per query.
+static int topk_slices(int B, int64_t Kp, int k) {
   int64_t G = Kp / MOL_TOPK_SLICE;
   if (G > MOL_TOPK_MAXG) G = MOL_TOPK_MAXG;
+  int64_t by_batch = 8192 / (B > 0 ? B : 1);
+  if (by_batch < 8) by_batch = 8;
+  if (G > by_batch) G = by_batch;
   if (G < 2 || G * (int64_t)k * 2 > Kp) G = 1;
   return (int)G;
 }
 
 size_t final_topk_workspace_bytes(int B, int64_t Kp, int k) {
-  const int G = topk_slices(Kp, k);
+  const int G = topk_slices(B, Kp, k);
   return G > 1 ? 2 * align_up((size_t)B * G * k * 4, 256) : 0;
 }
 
@@ -138,7 +143,7 @@ mol_status_t launch_final_topk(const float *scores, const int32_t *cand_idx, con
   ProfScope ps(MOL_PROF_FINAL_TOPK, st);
   int nsort = 64;
   while (nsort < k) nsort <<= 1;
-  const int G = topk_slices(Kp, k);
+  const int G = topk_slices(B, Kp, k);
   if (G > 1) {
     float *st_score = reinterpret_cast<float *>(ws);
     int32_t *st_idx = reinterpret_cast<int32_t *>(ws + align_up((size_t)B * G * k * 4, 256));
