@@ -13,10 +13,19 @@ namespace {
 // With k much smaller than the row (k = 100 of K' = 1e5) the k best of the row are among the k best of each of G slices,
 // so G workgroups per query cut the row to G*k staged candidates in one pass over it, and one workgroup per query
 // finishes.  Staged rows are (score, item index) pairs, unordered, padded with (-inf, -1).
+// Long slices are cut first with a bound that cannot lose anything: the k-th best key of ANY subset of the slice is a
+// lower bound of the slice's k-th best key, so after the k-th best of the slice's first eighth is known (the multi-pass
+// radix selection, on an eighth of the data), ONE pass over the slice collects every entry that reaches it -- about 8 k
+// of them when the slice is in no particular order -- into an LDS buffer, and the exact k best are selected there.
+// When the buffer overflows (a slice sorted by score, masses of ties) the multi-pass selection runs on the whole slice.
+#define SEG_PREFIX_MIN 16384  // shortest slice that takes the prefix-bound path
+#define SEG_CAP 4096          // entries of the LDS buffer
 __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores, const int32_t *cand,
                                                              const int32_t *cand_count, int64_t Kp, int k,
                                                              float *st_score, int32_t *st_idx) {
   __shared__ SelectShared sh;
+  __shared__ uint2 s_buf[SEG_CAP];
+  __shared__ uint32_t s_cnt;
   const int g = blockIdx.x, G = gridDim.x, b = blockIdx.y;
   const int tid = threadIdx.x;
   const int64_t per = (Kp + G - 1) / G;
@@ -27,29 +36,67 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
   const int32_t *ci = cand ? cand + (size_t)b * Kp + lo : nullptr;
   float *os = st_score + ((size_t)b * G + g) * k;
   int32_t *oi = st_idx + ((size_t)b * G + g) * k;
-  auto each = [&](auto f) {
-    block_for_each<4>(sc, n, [&](int64_t i, float v) {
-      const int32_t id = ci ? ci[i] : (int32_t)(lo + i);
-      if (id >= 0) f(f32_to_key(v), (uint32_t)id);
-    });
+  auto each_of = [&](int64_t len) {
+    return [&, len](auto f) {
+      block_for_each<4>(sc, len, [&](int64_t i, float v) {
+        const int32_t id = ci ? ci[i] : (int32_t)(lo + i);
+        if (id >= 0) f(f32_to_key(v), (uint32_t)id);
+      });
+    };
   };
-  if (tid == 0) sh.out_count = 0;
-  const uint32_t kk = block_select_kth<true>(each, (uint32_t)k, sh);  // min(k, valid entries of the slice)
-  if (kk > 0) {
-    each([&](uint32_t key, uint32_t idx) {
-      if (select_accept(key, idx, sh)) {
-        const uint32_t slot = atomicAdd(&sh.out_count, 1u);
-        if (slot < kk) {
-          os[slot] = key_to_f32(key);
-          oi[slot] = (int32_t)idx;
+  auto each = each_of(n);
+  // writes the accepted entries of `from` (exactly kk of them, up to entries listed twice) and pads the rest
+  auto emit = [&](auto from, uint32_t kk) {
+    if (tid == 0) sh.out_count = 0;
+    __syncthreads();
+    if (kk > 0) {
+      from([&](uint32_t key, uint32_t idx) {
+        if (select_accept(key, idx, sh)) {
+          const uint32_t slot = atomicAdd(&sh.out_count, 1u);
+          if (slot < kk) {
+            os[slot] = key_to_f32(key);
+            oi[slot] = (int32_t)idx;
+          }
         }
+      });
+    }
+    for (uint32_t i = kk + tid; i < (uint32_t)k; i += SELECT_THREADS) {
+      os[i] = -INFINITY;
+      oi[i] = -1;
+    }
+  };
+
+  if (n >= SEG_PREFIX_MIN) {
+    auto each_prefix = each_of(n / 8);
+    const uint32_t kp = block_select_kth<false>(each_prefix, (uint32_t)k, sh);  // k-th best key of the first eighth
+    const uint32_t bound = (kp == (uint32_t)k) ? sh.kth_key : 0u;               // fewer than k valid entries there: no bound
+    __syncthreads();
+    if (tid == 0) s_cnt = 0;
+    __syncthreads();
+    each([&](uint32_t key, uint32_t idx) {
+      if (key >= bound) {
+        const uint32_t slot = atomicAdd(&s_cnt, 1u);
+        if (slot < SEG_CAP) s_buf[slot] = make_uint2(key, idx);
       }
     });
+    __syncthreads();
+    const uint32_t cnt = s_cnt;
+    if (cnt <= SEG_CAP) {  // the buffer holds every entry that can be among the k best (at least k of them, if k exist)
+      auto each_buf = [&](auto f) {
+        for (uint32_t e = tid; e < cnt; e += SELECT_THREADS) {
+          const uint2 v = s_buf[e];
+          f(v.x, v.y);
+        }
+      };
+      const uint32_t kk = block_select_kth<true>(each_buf, (uint32_t)k, sh);
+      emit(each_buf, kk);
+      return;
+    }
+    __syncthreads();
   }
-  for (uint32_t i = kk + tid; i < (uint32_t)k; i += SELECT_THREADS) {
-    os[i] = -INFINITY;
-    oi[i] = -1;
-  }
+
+  const uint32_t kk = block_select_kth<true>(each, (uint32_t)k, sh);  // min(k, valid entries of the slice)
+  emit(each, kk);
 }
 
 // ---- one workgroup per query: radix select of the k-th element, then a sort of the k winners -----------------------
