@@ -87,6 +87,23 @@ __device__ __forceinline__ float act_fn(float x, int act) {
   return act == MOL_ACT_RELU ? fmaxf(x, 0.f) : x / (1.f + __expf(-x));
 }
 
+// Reductions over the two halves of a wavefront (lane and lane ^ 32) without a trip through LDS: the row swap leaves the
+// lower half's value in one register and the upper half's in the other, in every lane.
+__device__ __forceinline__ float half_swap_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// x + the value of lane ^ 16, in every lane (rows of 16 lanes swapped in pairs)
+__device__ __forceinline__ float quarter_swap_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // EXH = false: tiles of 32 candidates of one query (cand list or not), every tile gathers its own rows.
 // EXH = true : exhaustive scoring (every item for every query).  A wavefront takes a block of 32 consecutive items,
 //              loads their rows and cached gate halves into registers ONCE and walks a chunk of queries over them, so
@@ -158,6 +175,7 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
   int cur_b = -1;
   uint4 Ff[SA];
   uint4 Ffp[K_G ? SA : 1];  // K_G > 0: the user embeddings as halves in the k order of the generated rows
+  uint4 sd[K_G ? 2 : 1][K_G ? GenShape<K_G, D_P, D_S, D_HG>::SG1 : 1];  // K_G > 0: the candidates' seeds (16 per half-tile)
   constexpr int PD = RT < 8 ? RT : 8;
   uint4 A[PD][SA];
   uint2 xi[MT][4];      // FORM 0: cached item half of layer 1 (bf16 x 4)
@@ -266,6 +284,24 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
 #pragma unroll
       for (int s = 0; s < SA; ++s) dst[s] = (K_G == 0 || kx < K_C) ? ld16(rowp + 64 * s) : make_uint4(0, 0, 0, 0);
     };
+    constexpr int PFR = MOL_PF_ROWS < PD ? MOL_PF_ROWS : PD;
+    // seeds of the tile's candidates (generated embeddings): fetched with the previous tile's prefetch when there was one
+    auto load_seeds = [&](int item) {
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int gidx = __shfl(item, 16 * hf + r16);
+#pragma unroll
+        for (int s = 0; s < GS::SG1; ++s) sd[hf][s] = ld16(a.seed + ((size_t)gidx * D_S + 32 * s + 8 * g) * 2);
+      }
+    };
+    if constexpr (K_G > 0) {
+      if (!primed) load_seeds(idxc);
+    }
+    if (EXH ? (new_items || RT > PD) : true) {
+#pragma unroll
+      for (int i = 0; i < PD; ++i)
+        if (EXH || i >= PFR || !primed) load_rows(A[i], i);
+    }
     // ---- G: the generated item embeddings of the tile's 32 candidates, 16 at a time, all in registers -------------------
     // 16x16x32 half MFMAs with the weights as the row operand and the candidates as columns: lane (r16, g) ends up with
     // rows 4 g + j of every 16-row result tile for candidate r16, which -- two tiles side by side -- is an 8-value k
@@ -274,10 +310,6 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
     if constexpr (K_G > 0) {
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
-        const int gidx = __shfl(idxc, 16 * hf + r16);
-        uint4 sd[GS::SG1];
-#pragma unroll
-        for (int s = 0; s < GS::SG1; ++s) sd[s] = ld16(a.seed + ((size_t)gidx * D_S + 32 * s + 8 * g) * 2);
         uint4 hb[GS::SG2];   // hidden units as halves: the column operand of layer 2
         uint32_t *hw = reinterpret_cast<uint32_t *>(hb);
 #pragma unroll
@@ -286,7 +318,7 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
           f32x4 acc = {bi.x, bi.y, bi.z, bi.w};
 #pragma unroll
           for (int s = 0; s < GS::SG1; ++s)
-            acc = mfma16_16x16x32<true>(*reinterpret_cast<const uint4 *>(wg1s + ((ut * GS::SG1 + s) * 64 + lane) * 16), sd[s], acc);
+            acc = mfma16_16x16x32<true>(*reinterpret_cast<const uint4 *>(wg1s + ((ut * GS::SG1 + s) * 64 + lane) * 16), sd[hf][s], acc);
           // tile ut -> words 2 (ut % 2), 2 (ut % 2) + 1 of k-step ut / 2
           hw[4 * (ut >> 1) + 2 * (ut & 1)] = pack16x2<true>(act_fn(acc[0], a.act), act_fn(acc[1], a.act));
           hw[4 * (ut >> 1) + 2 * (ut & 1) + 1] = pack16x2<true>(act_fn(acc[2], a.act), act_fn(acc[3], a.act));
@@ -307,8 +339,8 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
             ss += (acc[0] * acc[0] + acc[1] * acc[1]) + (acc[2] * acc[2] + acc[3] * acc[3]);
           }
           // L2 norm over the D_P values of (candidate, kg): they sit in the four lanes r16 + 16 g
-          ss += __shfl_xor(ss, 16);
-          ss += __shfl_xor(ss, 32);
+          ss = quarter_swap_sum(ss);
+          ss = half_swap_sum(ss);
           const float inv = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
 #pragma unroll
           for (int sa = 0; sa < SA; ++sa)
@@ -320,12 +352,6 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
       }
     }
 
-    constexpr int PFR = MOL_PF_ROWS < PD ? MOL_PF_ROWS : PD;
-    if (EXH ? (new_items || RT > PD) : true) {
-#pragma unroll
-      for (int i = 0; i < PD; ++i)
-        if (EXH || i >= PFR || !primed) load_rows(A[i], i);
-    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -371,6 +397,7 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
       idxc_n = (idx_n >= 0 && idx_n < a.N) ? idx_n : 0;
 #pragma unroll
       for (int i = 0; i < PFR; ++i) load_rows(A[i], i, idxc_n);
+      if constexpr (K_G > 0) load_seeds(idxc_n);  // the generator has consumed this tile's seeds
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -490,17 +517,6 @@ __global__ __launch_bounds__(K_G ? 512 : 256) void k_mol_score(MolArgs a) {
     __builtin_amdgcn_wave_barrier();
    }
   }
-}
-
-// Reductions over the two halves of a wavefront (lane and lane ^ 32) without a trip through LDS: the row swap leaves the
-// lower half's value in one register and the upper half's in the other, in every lane.
-__device__ __forceinline__ float half_swap_max(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float half_swap_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // Exhaustive scoring, fast form (cand_idx = NULL, concatenated gate, ReLU, shapes whose item tile fits registers).

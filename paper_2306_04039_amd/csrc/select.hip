@@ -18,7 +18,7 @@ namespace {
 // radix selection, on an eighth of the data), ONE pass over the slice collects every entry that reaches it -- about 8 k
 // of them when the slice is in no particular order -- into an LDS buffer, and the exact k best are selected there.
 // When the buffer overflows (a slice sorted by score, masses of ties) the multi-pass selection runs on the whole slice.
-#define SEG_PREFIX_MIN 16384  // shortest slice that takes the prefix-bound path
+#define SEG_PREFIX_MIN 4096  // shortest slice that takes the prefix-bound path
 #define SEG_CAP 4096          // entries of the LDS buffer
 __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores, const int32_t *cand,
                                                              const int32_t *cand_count, int64_t Kp, int k,
@@ -172,8 +172,8 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
 static int topk_slices(int B, int64_t Kp, int k) {
   int64_t G = Kp / MOL_TOPK_SLICE;
   if (G > MOL_TOPK_MAXG) G = MOL_TOPK_MAXG;
-  int64_t by_batch = 8192 / (B > 0 ? B : 1);
-  if (by_batch < 8) by_batch = 8;
+  int64_t by_batch = 4096 / (B > 0 ? B : 1);
+  if (by_batch < 4) by_batch = 4;
   if (G > by_batch) G = by_batch;
   if (G < 2 || G * (int64_t)k * 2 > Kp) G = 1;
   return (int)G;
