@@ -42,7 +42,12 @@ namespace {
 
 // Survivor records a lane stages in LDS before it writes them out (per query group); the rings of a workgroup take
 // 4 wavefronts * 64 lanes * NQG * entries * 8 bytes.
-constexpr uint32_t scan_ring_entries(int nqg) { return nqg == 4 ? 8u : 16u; }
+constexpr uint32_t scan_ring_entries(int nqg) { return nqg == 4 ? 4u : 16u; }
+// The filtering scan with four query groups keeps the queries in LDS instead of 64 registers (every wavefront of a
+// workgroup uses the same ones) and runs three wavefronts per SIMD: its 64 threshold compares per lane and tile are
+// dependent compare / branch pairs, and a third wavefront hides more of them than the registers were worth.
+constexpr bool scan_queries_in_lds(int epi, int nqg) { return epi == 0 /* EPI_FILTER */ && nqg == 4; }
+constexpr int scan_chunks(int dt) { return dt == MOL_F32 ? 8 : (dt == MOL_BF16 ? 4 : 2); }
 
 enum { EPI_FILTER = 0, EPI_KEYS = 1, EPI_HIST_KEY = 2, EPI_HIST_IDX = 3, EPI_FILTER_EXACT = 4 };
 
@@ -171,7 +176,7 @@ __device__ inline bool last_workgroup(uint32_t *ticket) {
 #define MOL_SCAN_MIN_WAVES 2  // keeps the 4-query-group variants at two wavefronts per SIMD (they need 260 registers otherwise)
 #endif
 template <int DT, int NQG, int EPI, bool GATHER, int DEPTH>
-__global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArgs a) {
+__global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArgs a) {
   constexpr int NCH = DT == MOL_F32 ? 8 : (DT == MOL_BF16 ? 4 : 2);
   constexpr int ROWB = DT == MOL_F32 ? 256 : (DT == MOL_BF16 ? 128 : 64);
   constexpr bool REDO = EPI >= EPI_HIST_KEY;
@@ -195,7 +200,10 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
     __syncthreads();
   }
 
-  uint4 q[NQG][NCH];
+  constexpr bool QLDS = scan_queries_in_lds(EPI, NQG);
+  uint4 q[QLDS ? 1 : NQG][QLDS ? 1 : NCH];
+  // QLDS: [NQG][NCH][64 lanes] behind the survivor rings
+  uint4 *q_lds = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(lds_hist) + (size_t)4 * 64 * NQG * RING * 8);
   float thr[NQG];
   uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
   uint32_t cnt[NQG];
@@ -207,8 +215,14 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
     const int b = a.qbase + 32 * g + r;
     ring[g] = reinterpret_cast<uint2 *>(lds_hist) + ((size_t)((threadIdx.x >> 6) * NQG + g) * 64 + lane) * RING;
 #pragma unroll
-    for (int ci = 0; ci < NCH; ++ci)
-      q[g][ci] = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
+    for (int ci = 0; ci < NCH; ++ci) {
+      const uint4 qv = (b < a.B) ? ld16(a.Q + (size_t)b * ROWB + (2 * ci + h) * 16) : make_uint4(0, 0, 0, 0);
+      if constexpr (QLDS) {
+        if (threadIdx.x < 64) q_lds[(g * NCH + ci) * 64 + lane] = qv;  // the same for every wavefront: the first one stores
+      } else {
+        q[g][ci] = qv;
+      }
+    }
     thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
     if constexpr (EPI == EPI_FILTER_EXACT) thr[g] = (a.paper && b < a.B) ? a.thr[b] : -INFINITY;
     st_active[g] = 0;
@@ -227,6 +241,12 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
       }
     }
   }
+
+  if constexpr (QLDS) __syncthreads();  // the queries are in LDS
+  auto qop = [&](int g, int ci) -> uint4 {
+    if constexpr (QLDS) return q_lds[(g * NCH + ci) * 64 + lane];
+    else return q[g][ci];
+  };
 
   auto load_tile = [&](uint4(&dst)[NCH], int64_t tile) {
     int64_t row = tile * 32 + r;
@@ -279,16 +299,16 @@ __global__ __launch_bounds__(256, MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArg
 #pragma unroll
         for (int g = 0; g < NQG; ++g) {
           if constexpr (DT == MOL_INT8) {
-            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(buf[i][ci]), as_i32x4(q[g][ci]), iacc[g], 0, 0, 0);
+            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(buf[i][ci]), as_i32x4(qop(g, ci)), iacc[g], 0, 0, 0);
           } else if constexpr (DT == MOL_F32) {
             const float av[4] = {__uint_as_float(buf[i][ci].x), __uint_as_float(buf[i][ci].y),
                                  __uint_as_float(buf[i][ci].z), __uint_as_float(buf[i][ci].w)};
-            const float qv[4] = {__uint_as_float(q[g][ci].x), __uint_as_float(q[g][ci].y),
-                                 __uint_as_float(q[g][ci].z), __uint_as_float(q[g][ci].w)};
+            const uint4 qq = qop(g, ci);
+            const float qv[4] = {__uint_as_float(qq.x), __uint_as_float(qq.y), __uint_as_float(qq.z), __uint_as_float(qq.w)};
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], qv[e], acc[g], 0, 0, 0);
           } else {
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(buf[i][ci]), as_bf16x8(q[g][ci]), acc[g], 0,
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(buf[i][ci]), as_bf16x8(qop(g, ci)), acc[g], 0,
                                                              0, 0);
           }
         }
@@ -730,9 +750,11 @@ void (*scan_kernel(int nqg))(ScanArgs) {
 constexpr int scan_query_span(int dt) { return dt == MOL_F32 ? 64 : 128; }
 
 // dynamic LDS of one scan workgroup
-size_t scan_lds_bytes(int epi, int nqg) {
+size_t scan_lds_bytes(int epi, int nqg, int dt) {
   if (epi == EPI_HIST_KEY || epi == EPI_HIST_IDX) return (size_t)32 * nqg * EXACT_BINS * 4;
-  if (epi == EPI_FILTER) return (size_t)4 * 64 * nqg * scan_ring_entries(nqg) * 8;
+  if (epi == EPI_FILTER)
+    return (size_t)4 * 64 * nqg * scan_ring_entries(nqg) * 8 +
+           (scan_queries_in_lds(epi, nqg) ? (size_t)nqg * scan_chunks(dt) * 64 * 16 : 0);
   return 0;
 }
 
@@ -758,7 +780,7 @@ mol_status_t scan_occupancy(int nqg, int *per_sm_out) {
   int v = cached[nqg].load(std::memory_order_acquire);
   if (v == 0) {
     auto kern = scan_kernel<DT, EPI, GATHER>(nqg);
-    const size_t lds = scan_lds_bytes(EPI, nqg);
+    const size_t lds = scan_lds_bytes(EPI, nqg, DT);
     if (lds > 48 * 1024)
       HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, kern, 256, lds));
@@ -775,7 +797,8 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   mol_status_t rc = scan_occupancy<DT, EPI, GATHER>(nqg, &per_sm);
   if (rc != MOL_OK) return rc;
   constexpr int PER_CU = DT == MOL_INT8 ? MOL_SCAN_PER_CU_I8 : MOL_SCAN_PER_CU;
-  if (per_sm > PER_CU) per_sm = PER_CU;
+  const int per_cu = (scan_queries_in_lds(EPI, nqg) && PER_CU < 3) ? 3 : PER_CU;
+  if (per_sm > per_cu) per_sm = per_cu;
   const int cus = device_cus();
   if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
   int64_t grid = (int64_t)cus * per_sm;
@@ -800,7 +823,7 @@ mol_status_t launch_scan(const ScanArgs &a0, int B, int64_t fixed_grid, hipStrea
     mol_status_t rc = scan_grid<DT, EPI, GATHER>(nqg, ntiles, &grid);
     if (rc != MOL_OK) return rc;
     if (fixed_grid > 0) grid = fixed_grid;
-    const size_t lds = scan_lds_bytes(EPI, nqg);
+    const size_t lds = scan_lds_bytes(EPI, nqg, DT);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), lds, st, a);
     HIP_TRY(hipGetLastError());
   }
