@@ -170,9 +170,17 @@ struct HindexerPlan {
   int64_t grid;        // workgroups of the list-writing scans
   int64_t L;           // survivor lists per query (8 per workgroup)
   int64_t cap;         // capacity of one survivor list
+  // how the threshold is taken from the sample: 0 no sampling, 1 the sampled scores fit one workgroup's LDS,
+  // 2 large sample, bracket from its first lambda0 rows then a filtering scan over all of it (the threshold may then lie
+  // below the rank-th sampled score, never above: exact-on-success mode only), 3 large sample, digit passes over the
+  // B x lambda score matrix (exact rank)
+  int thr_path;
+  int64_t lambda0;     // path 2: rows of the bracketing part of the sample
+  int64_t rank0;       // path 2: rank of the bracket inside that part
+  int64_t rank_u;      // rank of the upper end of the key window inside the sample (0: none)
   // workspace offsets (bytes)
-  size_t off_sample, off_skeys, off_thr, off_count, off_flags, off_sstat, off_surv, off_mhist, off_mcnt, off_tie,
-      off_hist, off_state, total;
+  size_t off_sample, off_skeys, off_thr, off_thr0, off_win, off_count, off_flags, off_sstat, off_surv, off_mhist, off_mcnt,
+      off_tie, off_hist, off_state, total;
 };
 mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, int mode, HindexerPlan *p);
 mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, const int32_t *sample_idx,

@@ -782,13 +782,25 @@ __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, u
     }
     return;
   }
-  for (int j = 0; j < d_gu / 8; ++j) {
-    const uint4 w = wr[j], g = gr[j];
-    const uint32_t wv[4] = {w.x, w.y, w.z, w.w}, gv[4] = {g.x, g.y, g.z, g.w};
+  // eight 16-byte pieces of both rows in flight at a time (the sum itself stays in element order)
+  constexpr int PF = 8;
+  for (int j0 = 0; j0 < d_gu / 8; j0 += PF) {
+    uint4 wq[PF], gq[PF];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc = fmaf(dec16(wv[e] & 0xffffu, f16), dec16(gv[e] & 0xffffu, f16), acc);
-      acc = fmaf(dec16(wv[e] >> 16, f16), dec16(gv[e] >> 16, f16), acc);
+    for (int u = 0; u < PF; ++u) {
+      const int j = j0 + u < d_gu / 8 ? j0 + u : j0;
+      wq[u] = wr[j];
+      gq[u] = gr[j];
+    }
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      if (j0 + u >= d_gu / 8) break;
+      const uint32_t wv[4] = {wq[u].x, wq[u].y, wq[u].z, wq[u].w}, gv[4] = {gq[u].x, gq[u].y, gq[u].z, gq[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = fmaf(dec16(wv[e] & 0xffffu, f16), dec16(gv[e] & 0xffffu, f16), acc);
+        acc = fmaf(dec16(wv[e] >> 16, f16), dec16(gv[e] >> 16, f16), acc);
+      }
     }
   }
   U[i] = acc;

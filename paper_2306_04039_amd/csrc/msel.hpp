@@ -5,6 +5,9 @@
 // a grid of (slices x queries) workgroups.  Three histogram passes over fixed digits of the 32-bit key
 // (bits 31..21, 20..10, 9..0) find the exact K-th key; an emit pass writes everything above it, and the few items tied
 // at the K-th key are parked in a small buffer from which a finishing workgroup takes the lowest indices.
+// Where the caller knows a narrow key window that holds the K-th element (stage 1 does, from its sample), the
+// histogram is one pass over 2048 equal slices of that window, made by whoever produces the elements, and the members
+// of the slice that holds the K-th element are parked and ranked by the finishing workgroup.
 // No per-query state is carried between the kernels except the three histograms: every workgroup re-derives the
 // digits found so far from them (a 2048-bin scan, microseconds), which saves a launch per pass.
 #pragma once
@@ -163,18 +166,22 @@ __device__ __forceinline__ void msel_slice_for_each(const T *p, int64_t n, int b
   }
 }
 
-// Finishing helper: of the nt ties parked in `ties` (all with the same key), the `need` lowest indices are appended to
-// the output through `put(slot_offset, idx)`; slot offsets run from 0 to need-1 in ascending index order.
-// One workgroup; nt <= MSEL_TIE_CAP.  sh.hist is used as scratch for the indices.
+// Finishing helper: of the nt entries (key, idx) parked in `parked`, the `need` first ones under the order (key
+// descending, idx ascending) are handed to `put(rank, key, idx)`, rank = 0 .. need-1 in that order.
+// One workgroup; nt <= MSEL_TIE_CAP.  `scratch` is LDS for MSEL_TIE_CAP entries.
 template <class Put>
-__device__ inline void msel_take_lowest_ties(const uint32_t *ties, uint32_t nt, uint32_t need, MselShared &sh, Put put) {
-  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) sh.hist[i] = ties[i];
+__device__ inline void msel_take_best(const uint2 *parked, uint32_t nt, uint32_t need, uint2 *scratch, Put put) {
+  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) scratch[i] = parked[i];
   __syncthreads();
   for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
-    const uint32_t me = sh.hist[i];
+    const uint2 me = scratch[i];
     uint32_t rank = 0;
-    for (uint32_t j = 0; j < nt; ++j) rank += (sh.hist[j] < me || (sh.hist[j] == me && j < i)) ? 1u : 0u;
-    if (rank < need) put(rank, me);
+    for (uint32_t j = 0; j < nt; ++j) {
+      const uint2 o = scratch[j];
+      const bool before = o.x > me.x || (o.x == me.x && (o.y < me.y || (o.y == me.y && j < i)));
+      rank += before ? 1u : 0u;
+    }
+    if (rank < need) put(rank, me.x, me.y);
   }
   __syncthreads();
 }

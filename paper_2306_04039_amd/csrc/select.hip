@@ -162,7 +162,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
 
 // slices per query of the two-level form (1 = single level)
 #ifndef MOL_TOPK_SLICE
-#define MOL_TOPK_SLICE 8192  // entries of a row one level-1 workgroup reduces
+#define MOL_TOPK_SLICE 6144  // entries of a row one level-1 workgroup reduces (16 slices of a 1e5-candidate row)
 #endif
 #ifndef MOL_TOPK_MAXG
 #define MOL_TOPK_MAXG 32

@@ -10,7 +10,7 @@
 #define SELECT_BINS (1 << SELECT_BITS)
 
 struct SelectShared {
-  uint32_t hist[SELECT_BINS];
+  alignas(16) uint32_t hist[SELECT_BINS];
   uint32_t chunk[64];
   uint32_t red_min[SELECT_THREADS / WAVE];
   uint32_t red_max[SELECT_THREADS / WAVE];
@@ -47,13 +47,14 @@ __device__ __forceinline__ void block_for_each(const T *p, int64_t n, F f) {
 //
 // One radix pass.  ON_IDX = false: digit of the key, among elements agreeing with sh.prefix above bit `hi`.
 // ON_IDX = true: digit of ~idx among the elements whose key equals sh.kth_key.
+// sh.hist must be all zero on entry and is all zero again on return.
 template <bool ON_IDX, class Each>
 __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
+  static_assert(SELECT_BINS == 2 * SELECT_THREADS, "the digit search gives every thread two bins");
   const int tid = threadIdx.x;
-  for (int i = tid; i < SELECT_BINS; i += SELECT_THREADS) sh.hist[i] = 0;
-  __syncthreads();
   const uint32_t prefix = sh.prefix;
   const uint32_t kth_key = sh.kth_key;
+  const uint32_t krem = sh.krem;
   const int w = hi - lo + 1;
   const uint32_t dmask = (1u << w) - 1u;
   each([&](uint32_t key, uint32_t idx) {
@@ -67,48 +68,37 @@ __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
     if (valid && match) atomicAdd(&sh.hist[(k >> lo) & dmask], 1u);
   });
   __syncthreads();
-  // locate the digit that holds rank krem counting from the largest digit: the first wavefront alone, with lane scans
-  // (chunk t covers `per` consecutive digits from the top; then the lanes take one digit each of the chunk that holds it)
+  // locate the digit that holds rank krem counting from the largest digit: thread t owns digits top-2t and top-2t-1
+  // (read as one aligned pair and cleared for the next pass); inclusive sums run over the lanes of a wavefront, then
+  // over the wavefronts through sh.chunk
   const int nb = 1 << w;
-  const int per = (nb + 63) / 64;  // digits per chunk (<= 32)
-  if (tid < 64) {
-    const uint32_t krem = sh.krem;
-    uint32_t s = 0;
-    const int top = nb - 1 - tid * per;
-    for (int j = 0; j < per; ++j) {
-      const int d = top - j;
-      if (d >= 0) s += sh.hist[d];
-    }
-    uint32_t incl = s;  // inclusive sum over chunks 0..tid
+  const int p2 = SELECT_BINS / 2 - 1 - tid;  // pair index: bins 2*p2 (lower digit) and 2*p2+1 (higher digit)
+  const uint2 pr = reinterpret_cast<uint2 *>(sh.hist)[p2];
+  reinterpret_cast<uint2 *>(sh.hist)[p2] = make_uint2(0u, 0u);
+  // digits at or above nb are never filled; thread t sees them as zero, so counting from the top of the table is the
+  // same as counting from digit nb-1
+  const uint32_t h_hi = pr.y, h_lo = pr.x;
+  const uint32_t s = h_hi + h_lo;
+  uint32_t incl = s;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t up = (uint32_t)__shfl_up((int)incl, o);
-      if (tid >= o) incl += up;
-    }
-    // first chunk whose inclusive sum reaches krem (the last chunk if none does: krem never exceeds the total)
-    const uint64_t reach = __ballot(incl >= krem);
-    const int c = reach ? __ffsll((unsigned long long)reach) - 1 : 63;
-    const uint32_t before = (uint32_t)__shfl((int)(incl - s), c);  // elements in the chunks above chunk c
-    // inside chunk c: lane j takes digit dtop - j
-    const int dtop = nb - 1 - c * per;
-    const int d_mine = dtop - tid;
-    const uint32_t h = (tid < per && d_mine >= 0) ? sh.hist[d_mine] : 0u;
-    uint32_t hin = h;
-#pragma unroll
-    for (int o = 1; o < 32; o <<= 1) {
-      const uint32_t up = (uint32_t)__shfl_up((int)hin, o);
-      if (tid >= o) hin += up;
-    }
-    const uint64_t hit = __ballot(tid < per && d_mine >= 0 && before + hin >= krem);
-    int j = hit ? __ffsll((unsigned long long)hit) - 1 : (dtop < per ? dtop : per - 1);  // fall back to the chunk's last digit
-    const uint32_t above = before + (uint32_t)__shfl((int)(hin - h), j);
-    if (tid == 0) {
-      const int d = dtop - j;
-      sh.krem = krem - above;  // rank inside digit d
-      sh.prefix = prefix | ((uint32_t)d << lo);
-      sh.ties = sh.hist[d];
-    }
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl, o);
+    if ((tid & 63) >= o) incl += up;
   }
+  if ((tid & 63) == 63) sh.chunk[tid >> 6] = incl;
+  __syncthreads();
+  uint32_t before = 0;
+  for (int i = 0; i < (tid >> 6); ++i) before += sh.chunk[i];
+  incl += before;
+  const uint32_t above = incl - s;  // elements in digits larger than this thread's pair
+  if (above < krem && krem <= incl) {  // exactly one thread (1 <= krem <= number of matching elements)
+    const bool in_hi = krem <= above + h_hi;
+    const int d = 2 * p2 + (in_hi ? 1 : 0);
+    sh.krem = krem - above - (in_hi ? 0u : h_hi);
+    sh.prefix = prefix | ((uint32_t)d << lo);
+    sh.ties = in_hi ? h_hi : h_lo;
+  }
+  (void)nb;
   __syncthreads();
 }
 
@@ -137,6 +127,7 @@ __device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
     sh.red_max[tid >> 6] = mx;
     sh.red_cnt[tid >> 6] = n_mine;
   }
+  for (int i = tid; i < SELECT_BINS; i += SELECT_THREADS) sh.hist[i] = 0;  // the passes keep it zero between them
   __syncthreads();
   if (tid == 0) {
     for (int i = 1; i < SELECT_THREADS / WAVE; ++i) {

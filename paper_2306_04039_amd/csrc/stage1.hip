@@ -20,6 +20,7 @@
 
 #include "common.hpp"
 #include "msel.hpp"
+#include "select.hpp"
 
 // Tuning constants of the corpus scan (measured on MI355X at N = 1e8, B = 32).
 #ifndef MOL_SCAN_DEPTH
@@ -97,6 +98,31 @@ struct ScanArgs {
   int shift;                // exact redo: bit position of the digit
   int paper;                // FILTER_EXACT: Algorithm 2 as written -- of the K' best only those above the sampled threshold are kept
 };
+
+// Key window of one query, known from the sample before the corpus scan: the K'-th best score of the corpus lies in
+// (t_key, u_key] unless the sample misleads (then the query is redone exactly).  One pass over the survivors counts
+// them per slice of the window (2048 equal slices), which is enough to cut the K' best out of them: the members of the
+// slice that holds the K'-th are ranked by a finishing workgroup.  (Counting in the scan itself, one global atomic
+// per survivor, cost 120 us at N = 1e8: the atomics sit in the same in-order queue as the prefetched tiles.)
+// Stored as uint2 {t_key, u_key} (the two ends are found by different workgroups); make_window() adds the shift:
+// slice of a key = (key - t_key) >> shift, keys above u_key are not counted.
+__device__ __forceinline__ uint32_t win_slice(uint32_t key, const uint4 w) {
+  const uint32_t s = (key > w.x ? key - w.x : 0u) >> w.z;
+  return s < (uint32_t)MSEL_BINS ? s : (uint32_t)MSEL_BINS - 1u;
+}
+__device__ __forceinline__ uint4 make_window(const uint2 tu) {
+  const uint32_t t_key = tu.x, u_key = tu.y < tu.x ? tu.x : tu.y;
+  const uint32_t w = u_key - t_key;
+  const int bits = w ? 32 - __clz(w) : 0;
+  return make_uint4(t_key, u_key, bits > 11 ? (uint32_t)(bits - 11) : 0u, 0u);
+}
+// upper end of the window when the sample is too small to bracket the K'-th score from above: as far above the largest
+// sampled key as that key lies above the threshold
+__device__ __forceinline__ uint32_t window_top_from_max(uint32_t t_key, uint32_t max_key) {
+  if (max_key < t_key) max_key = t_key;
+  const uint64_t u = (uint64_t)max_key + (uint64_t)(max_key - t_key) + 1024u;
+  return u > 0xffffffffull ? 0xffffffffu : (uint32_t)u;
+}
 
 // One step of the exact redo, run for query b by the 256 threads of the last workgroup of a histogram scan to finish:
 //   stage 1..4 : digit of the key found from the histogram of the scan just done; after the fourth the K'-th key is
@@ -192,6 +218,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
   // when it is full, so that the lists are written in whole 64/128-byte pieces.  (Appending each 8-byte record straight
   // to HBM cost a quarter of the scan's time: 4.6 M scattered partial-line writes at N = 1e8, K' = 1e5.)
   constexpr uint32_t RING = scan_ring_entries(NQG);
+  constexpr bool QLDS = scan_queries_in_lds(EPI, NQG);
   if constexpr (REDO) {
     if (*a.gate == 0) return;
   }
@@ -200,7 +227,6 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
     __syncthreads();
   }
 
-  constexpr bool QLDS = scan_queries_in_lds(EPI, NQG);
   uint4 q[QLDS ? 1 : NQG][QLDS ? 1 : NCH];
   // QLDS: [NQG][NCH][64 lanes] behind the survivor rings
   uint4 *q_lds = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(lds_hist) + (size_t)4 * 64 * NQG * RING * 8);
@@ -261,7 +287,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
   };
 
   // copies the first n (even up to RING) staged records of query group g to the lane's list; cnt[g] already counts them
-  auto flush_ring = [&](int g, uint32_t n) {
+  auto flush_ring = [&](int g, uint32_t n) __attribute__((always_inline)) {
     if (lst[g] == nullptr || cnt[g] > cap32) return;  // a list that overflowed is redone anyway
     uint2 *dst = lst[g] + (cnt[g] - n);
     for (uint32_t e = 0; e + 2 <= n; e += 2)
@@ -279,12 +305,12 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
   for (int i = 0; i < DEPTH; ++i)
     if (i < n_it && tile_of(i) < ntiles) load_tile(buf[i], tile_of(i));
 
-  for (int64_t it0 = 0; it0 < n_it; it0 += DEPTH) {
-#pragma unroll
-    for (int i = 0; i < DEPTH; ++i) {
-      if (it0 + i >= n_it) break;
-      const int64_t tile = tile_of(it0 + i);
-      if (tile >= ntiles) break;  // tile_of grows with its argument: nothing valid follows
+  // one tile out of ring slot tb (iteration `it` of this wavefront); false when the wavefront has no more tiles
+  auto do_tile = [&](uint4(&tb)[NCH], int64_t it) __attribute__((always_inline)) -> bool {
+    {
+      if (it >= n_it) return false;
+      const int64_t tile = tile_of(it);
+      if (tile >= ntiles) return false;  // tile_of grows with its argument: nothing valid follows
       f32x16 acc[NQG];
       i32x16 iacc[NQG];  // DT = MOL_INT8 only
 #pragma unroll
@@ -299,23 +325,23 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
 #pragma unroll
         for (int g = 0; g < NQG; ++g) {
           if constexpr (DT == MOL_INT8) {
-            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(buf[i][ci]), as_i32x4(qop(g, ci)), iacc[g], 0, 0, 0);
+            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(tb[ci]), as_i32x4(qop(g, ci)), iacc[g], 0, 0, 0);
           } else if constexpr (DT == MOL_F32) {
-            const float av[4] = {__uint_as_float(buf[i][ci].x), __uint_as_float(buf[i][ci].y),
-                                 __uint_as_float(buf[i][ci].z), __uint_as_float(buf[i][ci].w)};
+            const float av[4] = {__uint_as_float(tb[ci].x), __uint_as_float(tb[ci].y), __uint_as_float(tb[ci].z),
+                                 __uint_as_float(tb[ci].w)};
             const uint4 qq = qop(g, ci);
             const float qv[4] = {__uint_as_float(qq.x), __uint_as_float(qq.y), __uint_as_float(qq.z), __uint_as_float(qq.w)};
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], qv[e], acc[g], 0, 0, 0);
           } else {
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(buf[i][ci]), as_bf16x8(qop(g, ci)), acc[g], 0,
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(tb[ci]), as_bf16x8(qop(g, ci)), acc[g], 0,
                                                              0, 0);
           }
         }
       }
-      if (it0 + i + DEPTH < n_it) {
-        const int64_t tnext = tile_of(it0 + i + DEPTH);
-        if (tnext < ntiles) load_tile(buf[i], tnext);
+      if (it + DEPTH < n_it) {
+        const int64_t tnext = tile_of(it + DEPTH);
+        if (tnext < ntiles) load_tile(tb, tnext);
       }
       mfma_settle();
       if constexpr (DT == MOL_INT8) {
@@ -339,7 +365,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
         if constexpr (EPI == EPI_FILTER) {
           // about 1.5 of the 1024 scores of a tile pass: one compare per accumulator, and the (rare) append is a
           // branch the wavefront skips when no lane takes it
-          auto append = [&](int j) {
+          auto append = [&](int j) __attribute__((always_inline)) {
             ring[g][cnt[g] & (RING - 1)] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
             ++cnt[g];
             if ((cnt[g] & (RING - 1)) == 0) flush_ring(g, RING);
@@ -399,6 +425,17 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
         }
       }
     }
+    return true;
+  };
+  static_assert(DEPTH >= 1 && DEPTH <= 4, "ring slots are walked by hand");
+  for (int64_t it0 = 0; it0 < n_it; it0 += DEPTH) {
+    if (!do_tile(buf[0], it0)) break;
+    if constexpr (DEPTH > 1)
+      if (!do_tile(buf[1], it0 + 1)) break;
+    if constexpr (DEPTH > 2)
+      if (!do_tile(buf[2], it0 + 2)) break;
+    if constexpr (DEPTH > 3)
+      if (!do_tile(buf[3], it0 + 3)) break;
   }
   if constexpr (LISTS) {
 #pragma unroll
@@ -447,16 +484,18 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
 }
 
 // i-th sampled row: floor(N * hi32(SplitMix64 output i) / 2^32), stream state = seed + (i+1) * golden gamma.
-// The same launch clears `nz` words at `zero` (the histograms and counters of the two radix selections of the call).
-__global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64_t N, uint32_t *zero, size_t nz) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  for (size_t z = (size_t)i; z < nz; z += (size_t)gridDim.x * blockDim.x) zero[z] = 0u;
-  if (i >= lambda) return;
+__device__ __forceinline__ int32_t sample_row(uint64_t seed, int64_t i, uint64_t N) {
   uint64_t z = seed + (uint64_t)(i + 1) * 0x9E3779B97F4A7C15ull;
   z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
   z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
   z = z ^ (z >> 31);
-  out[i] = (int32_t)(((z >> 32) * N) >> 32);
+  return (int32_t)(((z >> 32) * N) >> 32);
+}
+// The same launch clears `nz` words at `zero` (the histograms and counters of the two radix selections of the call).
+__global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64_t N, uint32_t *zero, size_t nz) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (size_t z = (size_t)i; z < nz; z += (size_t)gridDim.x * blockDim.x) zero[z] = 0u;
+  if (i < lambda) out[i] = sample_row(seed, i, N);
 }
 
 // Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement), by multi-workgroup radix
@@ -488,16 +527,216 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_thr_hist(const uint32_t *skeys
 // `passes` digit passes were made: 3 give the exact rank-th sampled key (Algorithm 2 as written); with 2 the threshold is
 // the lower end of the 22-bit bucket holding it, at most 2^10 ulps below -- enough where the threshold only has to let
 // at least K' items through (the exact top-K' of the survivors is taken afterwards) and one pass over the keys cheaper.
-__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, int passes,
-                                                             float *thr, uint32_t *flags, uint32_t *gate) {
+// The upper end of the query's key window is the rank_u-th sampled key (its bucket's upper end), rank_u < rank chosen
+// by the host so that the K'-th best score of the corpus lies below it; rank_u = 0: no such rank exists in the sample.
+__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, uint32_t rank_u,
+                                                             int passes, float *thr, uint2 *win, uint32_t *flags,
+                                                             uint32_t *gate) {
   __shared__ MselShared sh;
   const int b = blockIdx.x;
   const MselCut c = msel_cut(mhist, B, b, rank, passes, sh);
+  const MselCut cu = msel_cut(mhist, B, b, rank_u ? rank_u : 1u, passes, sh);
   if (threadIdx.x == 0) {
-    thr[b] = c.K ? key_to_f32(c.prefix) : -INFINITY;
+    const uint32_t t_key = c.K ? c.prefix : f32_to_key(-INFINITY);
+    uint32_t u_key = cu.K ? (cu.prefix | (passes < MSEL_PASSES ? 0x3ffu : 0u)) : 0xffffffffu;
+    if (rank_u == 0) u_key = window_top_from_max(t_key, u_key);
+    thr[b] = key_to_f32(t_key);
+    win[b] = make_uint2(t_key, u_key);
     flags[b] = 0;
     if (b == 0) gate[0] = gate[1] = gate[2] = 0;
   }
+}
+
+// The same for a set of keys that fits the LDS of one workgroup (THR_KEYS_CAP keys), exactly: threshold = the rank-th
+// largest key, window top = the rank_u-th largest.  The keys of query b are either a dense row (dense + b * stride,
+// n_dense of them) or the survivor lists of a filtering scan over the sampled rows (lists / cnt / L / lcap as the scan
+// wrote them).  The second form serves large samples: a first, small part of the sample gives a bracket value
+// `fallback` below which the rank-th key cannot lie, the scan over the whole sample keeps only the scores above the
+// bracket, and this kernel picks the rank-th of those -- the B x lambda score matrix never exists.  Whatever the lists
+// lost (more entries than a list or the LDS holds) only lowers the rank-th key of what is left, so the threshold errs
+// to the side of more survivors; with fewer than `rank` entries the bracket itself is the threshold.
+// Grid (B, 1 or 2): workgroup (b, 0) finds the threshold, (b, 1) the window top (win != NULL), side by side.
+#define THR_KEYS_CAP 32768
+__global__ __launch_bounds__(SELECT_THREADS) void k_thr_select(const uint32_t *dense, int64_t stride, int64_t n_dense,
+                                                               const uint2 *lists, const uint32_t *cnt, int64_t L, int B,
+                                                               uint32_t lcap, uint32_t kcap, uint32_t rank,
+                                                               uint32_t rank_u, const float *fallback, float *thr,
+                                                               uint2 *win, uint32_t *flags, uint32_t *gate) {
+  extern __shared__ uint32_t s_keys[];  // kcap keys
+  __shared__ SelectShared sh;
+  __shared__ uint32_t s_n;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const bool top = blockIdx.y == 1;
+  if (tid == 0) s_n = 0;
+  __syncthreads();
+  if (dense != nullptr) {
+    const uint32_t *k = dense + (size_t)b * stride;
+    for (int64_t i = tid; i < n_dense && i < kcap; i += SELECT_THREADS) s_keys[i] = k[i];
+    if (tid == 0) s_n = (uint32_t)(n_dense < kcap ? n_dense : kcap);
+  } else {
+    // a thread takes U lists at a time and reads the first E entries of each in one go (a list of the sample scan
+    // holds about one entry); places in s_keys come from a scan of the counts over the workgroup, not from atomics
+    constexpr int U = 4, E = 4;
+    uint32_t run = 0;  // keys placed so far, the same in every thread
+    for (int64_t l0 = 0; l0 < L; l0 += (int64_t)U * SELECT_THREADS) {
+      uint32_t c[U];
+      uint2 v[U][E];
+      uint32_t tc = 0;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t l = l0 + tid + (int64_t)u * SELECT_THREADS;
+        c[u] = l < L ? cnt[(size_t)b * L + l] : 0u;
+        if (c[u] > lcap) c[u] = lcap;
+        tc += c[u];
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t l = l0 + tid + (int64_t)u * SELECT_THREADS;
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          v[u][e] = (uint32_t)e < c[u] ? lists[((size_t)l * B + b) * lcap + e] : make_uint2(0u, 0u);
+      }
+      uint32_t incl = tc;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, o);
+        if ((tid & 63) >= o) incl += up;
+      }
+      if ((tid & 63) == 63) sh.chunk[tid >> 6] = incl;
+      __syncthreads();
+      uint32_t woff = 0, total = 0;
+      for (int i = 0; i < SELECT_THREADS / 64; ++i) {
+        const uint32_t t = sh.chunk[i];
+        if (i < (tid >> 6)) woff += t;
+        total += t;
+      }
+      uint32_t pos = run + woff + incl - tc;
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int64_t l = l0 + tid + (int64_t)u * SELECT_THREADS;
+        for (uint32_t e = 0; e < c[u]; ++e, ++pos) {
+          uint32_t key;
+          if (e < (uint32_t)E) {
+            key = v[u][0].x;
+#pragma unroll
+            for (int q = 1; q < E; ++q) key = e == (uint32_t)q ? v[u][q].x : key;
+          } else {
+            key = lists[((size_t)l * B + b) * lcap + e].x;
+          }
+          if (pos < kcap) s_keys[pos] = key;
+        }
+      }
+      run += total;
+      __syncthreads();  // sh.chunk is reused by the next round
+    }
+    if (tid == 0) s_n = run;
+  }
+  __syncthreads();
+  const uint32_t n = s_n < kcap ? s_n : kcap;
+  auto each = [&](auto f) {
+    for (uint32_t i = tid; i < n; i += SELECT_THREADS) f(s_keys[i], 0u);
+  };
+  const uint32_t floor_key = fallback ? f32_to_key(fallback[b]) : f32_to_key(-INFINITY);
+  if (!top) {
+    uint32_t t_key = floor_key;
+    if (n >= rank && rank >= 1) {  // the same in every thread
+      block_select_kth<false>(each, rank, sh);
+      t_key = sh.kth_key;
+    }
+    if (tid == 0) {
+      thr[b] = key_to_f32(t_key);
+      if (win) win[b].x = t_key;
+      if (flags) flags[b] = 0;
+      if (gate && b == 0) gate[0] = gate[1] = gate[2] = 0;
+    }
+  } else {
+    uint32_t u_key = 0xffffffffu;
+    if (rank_u >= 1 && n >= rank_u) {
+      block_select_kth<false>(each, rank_u, sh);
+      u_key = sh.kth_key;
+    } else if (rank_u == 0) {
+      // no sampled rank bounds the K'-th score from above: go as far above the largest sampled key as the (rank/2)-th
+      // sampled key lies below it
+      uint32_t mid = floor_key, mx = floor_key;
+      if (n >= 1) {
+        block_select_kth<false>(each, rank / 2 > 0 ? rank / 2 : 1u, sh);
+        mid = sh.kth_key;
+        mx = sh.kmax;
+      }
+      u_key = window_top_from_max(mid, mx);
+    }
+    if (tid == 0) win[b].y = u_key;
+  }
+}
+
+// Bracket step of the large-sample threshold: workgroup b scores the first n0 sampled rows against query b with plain
+// vector arithmetic (a few thousand dot products, too few to be worth a pass of the matrix-core scan and a second
+// launch), keeps the keys in LDS and writes the rank0-th largest as thr0[b].  The value only has to lie below the
+// rank-th score of the whole sample, so the summation order (not that of the scan) does not matter.
+#define THR_BRACKET_ROWS 4096
+template <int DT>
+__global__ __launch_bounds__(SELECT_THREADS) void k_thr_bracket(const char *X, int64_t x_rows, const int32_t *rows,
+                                                                int n0, const char *Q, uint32_t rank0, float *thr0) {
+  constexpr int ROWB = DT == MOL_F32 ? 256 : (DT == MOL_BF16 ? 128 : 64);
+  __shared__ SelectShared sh;
+  __shared__ uint32_t s_keys[THR_BRACKET_ROWS];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  // LG consecutive lanes share a row, 16 bytes each (one load instruction fetches 64 / LG whole rows); a lane keeps its
+  // 16 bytes of the query decoded in registers
+  constexpr int LG = ROWB / 16;
+  constexpr int EL = DT == MOL_F32 ? 4 : (DT == MOL_BF16 ? 8 : 16);  // elements in 16 bytes
+  const int part = tid % LG;
+  auto decode = [](const uint4 v, float(&out)[EL]) {
+    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if constexpr (DT == MOL_F32) {
+        out[e] = __uint_as_float(wv[e]);
+      } else if constexpr (DT == MOL_BF16) {
+        out[2 * e] = __uint_as_float(wv[e] << 16);
+        out[2 * e + 1] = __uint_as_float(wv[e] & 0xffff0000u);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) out[4 * e + t] = (float)(int8_t)((wv[e] >> (8 * t)) & 0xffu);
+      }
+    }
+  };
+  float qv[EL];
+  decode(ld16(Q + (size_t)b * ROWB + 16 * part), qv);
+  constexpr int RPI = SELECT_THREADS / LG;  // rows per step of the workgroup
+  constexpr int UNR = 16;  // rows in flight per lane group
+  for (int i0 = tid / LG; i0 < n0; i0 += UNR * RPI) {
+    uint4 v[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int i = i0 + u * RPI < n0 ? i0 + u * RPI : i0;
+      int64_t row = rows[i];
+      row = row < 0 ? 0 : (row >= x_rows ? x_rows - 1 : row);
+      v[u] = ld16(X + (size_t)row * ROWB + 16 * part);
+    }
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      float xv[EL];
+      decode(v[u], xv);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < EL; ++e) acc = fmaf(xv[e], qv[e], acc);
+#pragma unroll
+      for (int o = LG / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+      const int i = i0 + u * RPI;
+      if (part == 0 && i < n0) s_keys[i] = f32_to_key(acc);
+    }
+  }
+  __syncthreads();
+  auto each = [&](auto f) {
+    for (int i = tid; i < n0; i += SELECT_THREADS) f(s_keys[i], 0u);
+  };
+  uint32_t key = f32_to_key(-INFINITY);
+  if ((uint32_t)n0 >= rank0 && rank0 >= 1) {
+    block_select_kth<false>(each, rank0, sh);
+    key = sh.kth_key;
+  }
+  if (tid == 0) thr0[b] = key_to_f32(key);
 }
 
 __global__ void k_init_all_pass(float *thr, uint32_t *flags, uint32_t *gate, int B) {
@@ -588,10 +827,11 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
 }
 
 // Pass 0 also works out the query's status from the list counts (every workgroup for itself; the first one records it
-// for the passes and kernels that follow).
+// for the passes and kernels that follow).  With key windows (win != NULL) there is only pass 0, over the slices of the
+// query's window instead of the first key digit.
 __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, const uint32_t *cnt, int64_t L,
                                                             int64_t cap, uint2 *sstat, int Kp, uint32_t *mhist,
-                                                            int B, int pass, int mode, bool force) {
+                                                            const uint2 *win, int B, int pass, int mode, bool force) {
   __shared__ MselShared sh;
   const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
   uint2 stt;
@@ -602,8 +842,6 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, c
     stt = sstat[b];
   }
   if (stt.y || stt.x <= (uint32_t)Kp) return;
-  uint32_t prefix = 0;
-  if (pass > 0) prefix = msel_cut(mhist, B, b, (uint32_t)Kp, pass, sh).prefix;
   const int64_t per = (L + G - 1) / G;
   const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
   auto each = [&](auto f) {
@@ -611,28 +849,148 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, c
       if (valid) f(e.x, e.y);
     });
   };
+  if (win != nullptr) {
+    const uint4 w = make_window(win[b]);
+    for (int i = threadIdx.x; i < MSEL_BINS; i += MSEL_THREADS) sh.hist[i] = 0;
+    __syncthreads();
+    each([&](uint32_t key, uint32_t) {
+      if (key <= w.y) atomicAdd(&sh.hist[win_slice(key, w)], 1u);
+    });
+    __syncthreads();
+    for (int i = threadIdx.x; i < MSEL_BINS; i += MSEL_THREADS) {
+      const uint32_t v = sh.hist[i];
+      if (v) atomicAdd(&mhist[(size_t)b * MSEL_BINS + i], v);
+    }
+    return;
+  }
+  uint32_t prefix = 0;
+  if (pass > 0) prefix = msel_cut(mhist, B, b, (uint32_t)Kp, pass, sh).prefix;
   msel_hist_pass(each, pass, prefix, mhist + ((size_t)pass * B + b) * MSEL_BINS, sh);
 }
 
-__global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, const uint32_t *cnt, int64_t L,
-                                                            int64_t cap, const uint2 *sstat, int Kp,
-                                                            const uint32_t *mhist, int B, uint32_t *mcnt,
-                                                            uint32_t *tiebuf, int32_t *cand_idx, float *cand_score) {
-  __shared__ MselShared sh;
-  const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
-  const uint2 stt = sstat[b];
-  if (stt.y) return;
-  const bool take_all = stt.x <= (uint32_t)Kp;
-  uint32_t kth = 0;
-  bool all_ties = true;
-  if (!take_all) {
-    const MselCut c = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
-    kth = c.prefix;
-    all_ties = (c.krem == c.cnt);
+// Where the K'-th best survivor of query b lies, worked out by every workgroup that needs it (256 threads).
+//   kind 0: every survivor is taken;  kind 2: the lists cannot give the answer (exact redo);
+//   kind 1: survivors of class > d are taken, of class d the `need` best of its `cbin` members (all of them when
+//           need == cbin).  The class of a key is the key itself when three digit passes were made over the survivors
+//           (win == NULL: d is the K'-th key), else its slice of the query's key window, keys above the window counting
+//           as the highest class (the scan has counted the slices; those above are the rest of the total).
+struct SurvCut {
+  uint32_t kind, d, need, cbin;
+  uint4 w;
+  bool windowed;
+  __device__ __forceinline__ uint32_t cls(uint32_t key) const {
+    if (!windowed) return key;
+    return key > w.y ? (uint32_t)MSEL_BINS : win_slice(key, w);
   }
+};
+__device__ inline SurvCut surv_cut(uint2 stt, int Kp, const uint32_t *mhist, const uint2 *win, int B, int b,
+                                   MselShared &sh) {
+  SurvCut c = {};
+  c.windowed = win != nullptr;
+  if (stt.y) {
+    c.kind = 2;
+    return c;
+  }
+  if (stt.x <= (uint32_t)Kp) return c;
+  c.kind = 1;
+  if (c.windowed) {
+    c.w = make_window(win[b]);
+    const uint32_t *g = mhist + (size_t)b * MSEL_BINS;
+    msel_find(g, MSEL_BINS, 0xffffffffu, sh);  // only the total is used
+    const uint32_t inwin = sh.res[3];
+    __syncthreads();
+    if (inwin > stt.x || stt.x - inwin >= (uint32_t)Kp) {  // the K'-th best lies above the window: the sample misled
+      c.kind = 2;
+      return c;
+    }
+    msel_find(g, MSEL_BINS, (uint32_t)Kp - (stt.x - inwin), sh);
+    c.d = sh.res[0];
+    c.need = sh.res[1];
+    c.cbin = sh.res[2];
+    __syncthreads();
+  } else {
+    const MselCut m = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
+    c.d = m.prefix;
+    c.need = m.krem;
+    c.cbin = m.cnt;
+  }
+  return c;
+}
+
+// Closes query b after the emit pass: ranks the parked members of the
+// class at the cut, pads the row, writes cand_count, and sets up the exact redo when the lists cannot give the answer
+// (or more members are parked than the buffer holds).
+__device__ inline void surv_finish(const SurvCut &c, uint2 stt, int Kp, int b, const uint2 *tiebuf, uint2 *s_tie,
+                                   uint32_t *flags, uint32_t *gate, ExactState *state, uint32_t *ehist,
+                                   int32_t *cand_idx, float *cand_score, int32_t *cand_count) {
+  const int tid = threadIdx.x;
+  const bool redo = c.kind == 2 || (c.kind == 1 && c.need != c.cbin && c.cbin > MSEL_TIE_CAP);
+  // state of the exact redo: a flagged query starts the key passes at rank K'
+  if (tid == 0) {
+    ExactState s = {};
+    if (redo) {
+      s.active = 1;
+      s.krem = (uint32_t)Kp;
+      s.idx_limit = 0xffffffffu;
+    }
+    state[b] = s;
+  }
+  for (int i = tid; i < EXACT_BINS; i += MSEL_THREADS) ehist[(size_t)b * EXACT_BINS + i] = 0;
   int32_t *oi = cand_idx + (size_t)b * Kp;
   float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
+  uint32_t nout = 0;
+  if (redo) {
+    if (tid == 0) {
+      flags[b] = 1u;  // redone by the exact path
+      gate[0] = 1u;
+      cand_count[b] = -1;
+    }
+  } else if (c.kind == 0) {
+    nout = stt.x;
+    if (tid == 0) cand_count[b] = (int32_t)nout;
+  } else {
+    nout = (uint32_t)Kp;
+    if (c.need != c.cbin) {  // only the `need` best of the cbin parked members of the class at the cut are taken
+      const uint32_t base = (uint32_t)Kp - c.need;
+      msel_take_best(tiebuf + (size_t)b * MSEL_TIE_CAP, c.cbin, c.need, s_tie, [&](uint32_t rank, uint32_t key, uint32_t idx) {
+        oi[base + rank] = (int32_t)idx;
+        if (os) os[base + rank] = key_to_f32(key);
+      });
+    }
+    if (tid == 0) cand_count[b] = Kp;
+  }
+  for (int64_t i = nout + tid; i < Kp; i += MSEL_THREADS) {
+    oi[i] = -1;
+    if (os) os[i] = -INFINITY;
+  }
+}
+
+// win == NULL: sstat and the three digit histograms come from k_surv_hist.  Otherwise this kernel works the status out
+// itself (every workgroup for itself; the first one records it for k_surv_finish) and mhist is the window histogram.
+// (Closing the query in the last of its workgroups to finish, instead of a kernel of its own, was four times slower: the
+// device-scope fence each workgroup needs before its ticket writes back the whole L2 of its XCD.)
+__global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, const uint32_t *cnt, int64_t L,
+                                                            int64_t cap, uint2 *sstat, int Kp, const uint32_t *mhist,
+                                                            const uint2 *win, int B, int mode, bool force,
+                                                            uint32_t *mcnt, uint2 *tiebuf, int32_t *cand_idx,
+                                                            float *cand_score) {
+  __shared__ MselShared sh;
+  const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
+  uint2 stt;
+  if (win != nullptr) {
+    stt = surv_status(cnt, L, cap, Kp, mode, force, b);
+    __syncthreads();
+  } else {
+    stt = sstat[b];
+  }
+  const SurvCut c = surv_cut(stt, Kp, mhist, win, B, b, sh);
+  if (win != nullptr && blk == 0 && threadIdx.x == 0) sstat[b] = make_uint2(stt.x, c.kind == 2 ? 1u : 0u);
+  if (c.kind == 2) return;
   uint32_t *mc = mcnt + (size_t)b * MCNT_STRIDE;
+  const bool take_all = c.kind == 0;
+  const bool all_ties = c.need == c.cbin;
+  int32_t *oi = cand_idx + (size_t)b * Kp;
+  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
   const int64_t per = (L + G - 1) / G;
   const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
   // Two walks over this workgroup's lists: the first counts what each wavefront will emit, one atomic reserves the
@@ -642,8 +1000,9 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   uint32_t mine = 0;
   for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
-    const bool at = valid && !take_all && e.x == kth;
-    const bool take = valid && (take_all || e.x > kth || (at && all_ties));
+    const uint32_t k = c.cls(e.x);
+    const bool at = valid && !take_all && k == c.d;
+    const bool take = valid && (take_all || k > c.d || (at && all_ties));
     mine += (uint32_t)__popcll(__ballot(take));
   });
   if (lane == 0) wave_tot[wv] = mine;
@@ -657,8 +1016,9 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   uint32_t off = block_base;
   for (int i = 0; i < wv; ++i) off += wave_tot[i];
   for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
-    const bool at = valid && !take_all && e.x == kth;
-    const bool take = valid && (take_all || e.x > kth || (at && all_ties));
+    const uint32_t k = c.cls(e.x);
+    const bool at = valid && !take_all && k == c.d;
+    const bool take = valid && (take_all || k > c.d || (at && all_ties));
     const bool tie = at && !all_ties;
     const uint64_t m = __ballot(take);
     const uint32_t slot = off + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
@@ -669,72 +1029,22 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
     }
     if (__ballot(tie)) {
       const uint32_t ts = msel_wave_slot(tie, mc + 1);
-      if (tie && ts < MSEL_TIE_CAP) tiebuf[(size_t)b * MSEL_TIE_CAP + ts] = e.y;
+      if (tie && ts < MSEL_TIE_CAP) tiebuf[(size_t)b * MSEL_TIE_CAP + ts] = e;
     }
   });
 }
 
-__global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat, int Kp, const uint32_t *mhist, int B,
-                                                              uint32_t *mcnt, const uint32_t *tiebuf, uint32_t *flags,
-                                                              uint32_t *gate, ExactState *state, uint32_t *ehist,
-                                                              int32_t *cand_idx, float *cand_score,
+__global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat, int Kp, const uint32_t *mhist,
+                                                              const uint2 *win, int B, const uint2 *tiebuf,
+                                                              uint32_t *flags, uint32_t *gate, ExactState *state,
+                                                              uint32_t *ehist, int32_t *cand_idx, float *cand_score,
                                                               int32_t *cand_count) {
   __shared__ MselShared sh;
-  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ uint2 s_tie[MSEL_TIE_CAP];
+  const int b = blockIdx.x;
   const uint2 stt = sstat[b];
-  // state of the exact redo: a flagged query starts the key passes at rank K'
-  if (tid == 0) {
-    ExactState s = {};
-    if (stt.y) {
-      s.active = 1;
-      s.krem = (uint32_t)Kp;
-      s.idx_limit = 0xffffffffu;
-    }
-    state[b] = s;
-  }
-  for (int i = tid; i < EXACT_BINS; i += MSEL_THREADS) ehist[(size_t)b * EXACT_BINS + i] = 0;
-  int32_t *oi = cand_idx + (size_t)b * Kp;
-  float *os = cand_score ? cand_score + (size_t)b * Kp : nullptr;
-  uint32_t nout = 0;
-  if (stt.y) {
-    if (tid == 0) {
-      flags[b] = 1u;  // redone by the exact path
-      gate[0] = 1u;
-      cand_count[b] = -1;
-    }
-  } else if (stt.x <= (uint32_t)Kp) {
-    nout = stt.x;
-    if (tid == 0) cand_count[b] = (int32_t)nout;
-  } else {
-    const MselCut c = msel_cut(mhist, B, b, (uint32_t)Kp, MSEL_PASSES, sh);
-    nout = (uint32_t)Kp;
-    if (c.krem != c.cnt) {  // only the krem lowest indices of the cnt items tied at the K'-th key are taken
-      if (c.cnt > MSEL_TIE_CAP) {  // more ties at the K'-th key than the tie buffer holds: left to the exact redo
-        if (tid == 0) {
-          ExactState s = {};
-          s.active = 1;
-          s.krem = (uint32_t)Kp;
-          s.idx_limit = 0xffffffffu;
-          state[b] = s;
-          flags[b] = 1u;
-          gate[0] = 1u;
-          cand_count[b] = -1;
-        }
-        return;
-      }
-      const uint32_t base = (uint32_t)Kp - c.krem;
-      const float sc = key_to_f32(c.prefix);
-      msel_take_lowest_ties(tiebuf + (size_t)b * MSEL_TIE_CAP, c.cnt, c.krem, sh, [&](uint32_t rank, uint32_t idx) {
-        oi[base + rank] = (int32_t)idx;
-        if (os) os[base + rank] = sc;
-      });
-    }
-    if (tid == 0) cand_count[b] = Kp;
-  }
-  for (int64_t i = nout + tid; i < Kp; i += MSEL_THREADS) {
-    oi[i] = -1;
-    if (os) os[i] = -INFINITY;
-  }
+  const SurvCut c = surv_cut(stt, Kp, mhist, win, B, b, sh);
+  surv_finish(c, stt, Kp, b, tiebuf, s_tie, flags, gate, state, ehist, cand_idx, cand_score, cand_count);
 }
 
 // ---- launch helpers ----------------------------------------------------------------------------------------------
@@ -881,6 +1191,10 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   if (mode == MOL_HINDEXER_EXACT) rank = r_paper + (int64_t)ceil(5.0 * sqrt((double)r_paper)) + 8;
   if (rank > lambda) rank = lambda;
   p->rank = rank;
+  // the K'-th best score of the corpus sits near sample rank K' * lambda / N: the same five standard deviations on the
+  // other side bound it from above
+  p->rank_u = r_paper - (int64_t)ceil(5.0 * sqrt((double)r_paper)) - 8;
+  if (p->rank_u < 1 || p->rank_u >= rank) p->rank_u = 0;
 
   mol_status_t rc = list_scan_grid(c->stage1_dtype, B, N, &p->grid);
   if (rc != MOL_OK) return rc;
@@ -901,14 +1215,39 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   } else {
     p->cap = list_rows;
   }
+  // how the threshold is taken (see HindexerPlan::thr_path)
+  p->thr_path = 0;
+  p->lambda0 = 0;
+  p->rank0 = 0;
+  if (p->sampling) {
+    p->thr_path = 3;
+    if (p->lambda <= THR_KEYS_CAP) {
+      p->thr_path = 1;
+    } else if (mode == MOL_HINDEXER_EXACT) {
+      const int64_t lam0 = THR_BRACKET_ROWS;
+      const double m = (double)lam0 * (double)rank / (double)p->lambda;  // expected rows of the first part above the rank-th score
+      int64_t rank0 = (int64_t)ceil(m + 6.0 * sqrt(m) + 4.0);
+      if (rank0 > lam0) rank0 = lam0;
+      const double kept = (double)p->lambda * (double)rank0 / (double)lam0;  // sampled scores expected above the bracket
+      if (kept <= 8192.0 && kept <= 2.0 * (double)p->L) {
+        p->thr_path = 2;
+        p->lambda0 = lam0;
+        p->rank0 = rank0;
+      }
+    }
+  }
   const int64_t lam_pad = (p->lambda + 31) / 32 * 32;
   size_t off = 0;
   p->off_sample = off;
   off = align_up(off + (size_t)lam_pad * 4, 256);
   p->off_skeys = off;
-  off = align_up(off + (size_t)B * lam_pad * 4, 256);
+  off = align_up(off + (size_t)B * (p->thr_path == 2 ? p->lambda0 : lam_pad) * 4, 256);
   p->off_thr = off;
   off = align_up(off + (size_t)B * 4, 256);
+  p->off_thr0 = off;
+  off = align_up(off + (size_t)B * 4, 256);
+  p->off_win = off;
+  off = align_up(off + (size_t)B * 16, 256);
   p->off_count = off;
   off = align_up(off + (size_t)B * p->L * 4, 256);
   p->off_flags = off;
@@ -922,7 +1261,7 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   p->off_mcnt = off;
   off = align_up(off + (size_t)B * MCNT_STRIDE * 4, 256);
   p->off_tie = off;
-  off = align_up(off + (size_t)B * MSEL_TIE_CAP * 4, 256);
+  off = align_up(off + (size_t)B * MSEL_TIE_CAP * 8, 256);
   p->off_hist = off;
   off = align_up(off + (size_t)B * EXACT_BINS * 4, 256);
   p->off_state = off;
@@ -949,7 +1288,8 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   uint32_t *mhist = reinterpret_cast<uint32_t *>(ws + p.off_mhist);
   uint32_t *mhist2 = mhist + (size_t)MSEL_PASSES * B * MSEL_BINS;
   uint32_t *mcnt = reinterpret_cast<uint32_t *>(ws + p.off_mcnt);
-  uint32_t *tiebuf = reinterpret_cast<uint32_t *>(ws + p.off_tie);
+  uint2 *tiebuf = reinterpret_cast<uint2 *>(ws + p.off_tie);
+  uint2 *win = reinterpret_cast<uint2 *>(ws + p.off_win);
   // histograms and counters of both selections start at zero (they are contiguous in the workspace); the kernel that
   // draws the sample clears them on the side, otherwise a launch of its own does
   const size_t nz = (p.off_tie - p.off_mhist) / 4;
@@ -977,35 +1317,77 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
       hipLaunchKernelGGL(k_gen_sample, dim3((unsigned)((p.lambda + 255) / 256)), dim3(256), 0, st, samp, p.lambda,
                          seed, (uint64_t)c->N, mhist, nz);
       HIP_TRY(hipGetLastError());
-      rows = samp;
+    }
+    if (!rows) rows = samp;
+    static std::atomic<int> lds_raised{0};  // k_thr_select may use more dynamic LDS than the default limit
+    if (p.thr_path != 3 && !lds_raised.load(std::memory_order_acquire)) {
+      HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(k_thr_select), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  THR_KEYS_CAP * 4));
+      lds_raised.store(1, std::memory_order_release);
     }
     ScanArgs s = a;
-    s.n_rows = p.lambda;
     s.rows = rows;
     s.x_rows = c->N;
-    s.skeys = skeys;
-    s.skeys_stride = lam_pad;
     mol_status_t rc;
-    {
-      ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
-      rc = launch_scan_dt<EPI_KEYS, true>(dt, s, B, 0, st);
-    }
-    if (rc != MOL_OK) return rc;
-    ProfScope ps(MOL_PROF_THRESHOLD, st);
+    if (p.thr_path == 2) {
+      // large sample, exact-on-success mode: bracket from the first lambda0 sampled rows, then the whole sample through
+      // the filtering scan (its lists share the memory of the corpus scan's lists, 16 entries each)
+      float *thr0 = reinterpret_cast<float *>(ws + p.off_thr0);
+      const uint32_t lcap = 16;
+      {
+        ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
+        auto bracket = dt == MOL_F32 ? k_thr_bracket<MOL_F32> : (dt == MOL_BF16 ? k_thr_bracket<MOL_BF16> : k_thr_bracket<MOL_INT8>);
+        hipLaunchKernelGGL(bracket, dim3(B), dim3(SELECT_THREADS), 0, st, s.X, s.x_rows, rows, (int)p.lambda0, s.Q,
+                           (uint32_t)p.rank0, thr0);
+        HIP_TRY(hipGetLastError());
+        s.n_rows = p.lambda;
+        s.thr = thr0;
+        s.cap = lcap;
+        rc = launch_scan_dt<EPI_FILTER, true>(dt, s, B, p.grid, st);
+        if (rc != MOL_OK) return rc;
+      }
+      ProfScope ps(MOL_PROF_THRESHOLD, st);
+      // room for twice the sampled scores expected above the bracket (what does not fit is dropped, see the kernel)
+      const double kept = (double)p.lambda * (double)p.rank0 / (double)p.lambda0;
+      uint32_t kcap = (uint32_t)(2.0 * kept) + 1024u;
+      kcap = kcap > THR_KEYS_CAP ? THR_KEYS_CAP : (kcap + 1023u) & ~1023u;
+      hipLaunchKernelGGL(k_thr_select, dim3(B, 2), dim3(SELECT_THREADS), (size_t)kcap * 4, st,
+                         (const uint32_t *)nullptr, (int64_t)0, (int64_t)0, surv, cnt, p.L, B, lcap, kcap,
+                         (uint32_t)p.rank, (uint32_t)p.rank_u, thr0, thr, win, flags, gate);
+      HIP_TRY(hipGetLastError());
+    } else {
+      s.n_rows = p.lambda;
+      s.skeys = skeys;
+      s.skeys_stride = lam_pad;
+      {
+        ProfScope ps(MOL_PROF_SAMPLE_SCORES, st);
+        rc = launch_scan_dt<EPI_KEYS, true>(dt, s, B, 0, st);
+      }
+      if (rc != MOL_OK) return rc;
+      ProfScope ps(MOL_PROF_THRESHOLD, st);
+      if (p.thr_path == 1) {
+        hipLaunchKernelGGL(k_thr_select, dim3(B, 2), dim3(SELECT_THREADS), (size_t)p.lambda * 4, st, skeys, lam_pad,
+                           p.lambda, (const uint2 *)nullptr, (const uint32_t *)nullptr, (int64_t)0, B, 0u,
+                           (uint32_t)p.lambda, (uint32_t)p.rank, (uint32_t)p.rank_u, (const float *)nullptr, thr, win,
+                           flags, gate);
+        HIP_TRY(hipGetLastError());
+      } else {
 #ifndef MOL_THR_BLOCKS
 #define MOL_THR_BLOCKS 1024
 #endif
-    int G = MOL_THR_BLOCKS / B;
-    G = G < 1 ? 1 : (G > MOL_THR_BLOCKS / 16 ? MOL_THR_BLOCKS / 16 : G);
-    const int passes = (mode & 0xff) == MOL_HINDEXER_EXACT ? MSEL_PASSES - 1 : MSEL_PASSES;
-    for (int pass = 0; pass < passes; ++pass) {
-      hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
-                         mhist, B, pass);
-      HIP_TRY(hipGetLastError());
+        int G = MOL_THR_BLOCKS / B;
+        G = G < 1 ? 1 : (G > MOL_THR_BLOCKS / 16 ? MOL_THR_BLOCKS / 16 : G);
+        const int passes = (mode & 0xff) == MOL_HINDEXER_EXACT ? MSEL_PASSES - 1 : MSEL_PASSES;
+        for (int pass = 0; pass < passes; ++pass) {
+          hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
+                             mhist, B, pass);
+          HIP_TRY(hipGetLastError());
+        }
+        hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank,
+                           (uint32_t)p.rank_u, passes, thr, win, flags, gate);
+        HIP_TRY(hipGetLastError());
+      }
     }
-    hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank, passes, thr, flags,
-                       gate);
-    HIP_TRY(hipGetLastError());
   } else {
     hipLaunchKernelGGL(k_init_all_pass, dim3((B + 255) / 256), dim3(256), 0, st, thr, flags, gate, B);
     HIP_TRY(hipGetLastError());
@@ -1026,15 +1408,18 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
 #endif
     int G = MOL_SURV_BLOCKS / B;
     G = G < 1 ? 1 : (G > MOL_SURV_BLOCKS / 32 ? MOL_SURV_BLOCKS / 32 : G);
-    for (int pass = 0; pass < MSEL_PASSES; ++pass) {
-      hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
+    const uint2 *w = p.sampling ? win : nullptr;
+    // no key window without a sample: three digit passes over the survivors; with windows one pass over their slices
+    const int hist_passes = p.sampling ? 1 : MSEL_PASSES;
+    for (int pass = 0; pass < hist_passes; ++pass) {
+      hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
                          pass, mode, force_redo);
       HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(k_surv_emit, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, B,
-                       mcnt, tiebuf, cand_idx, cand_score);
+    hipLaunchKernelGGL(k_surv_emit, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
+                       mode, force_redo, mcnt, tiebuf, cand_idx, cand_score);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, B, mcnt, tiebuf, flags, gate,
+    hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, w, B, tiebuf, flags, gate,
                        state, hist, cand_idx, cand_score, cand_count);
     HIP_TRY(hipGetLastError());
   }
