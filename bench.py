@@ -410,6 +410,9 @@ def main():
     ap.add_argument("--in-flight", type=int, default=2,
                     help="after the timed region, also run the steps with this many batches in flight on separate streams and report "
                          "that throughput beside the headline (1 = skip)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step into a HIP graph and time its replays (no faster than eager launches on this "
+                         "runtime: the time between dependent kernels is the device's, not the host's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true", help="skip the comparison of the returned results with the CPU oracle")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the bare read / bare gather ceiling measurements")
@@ -536,6 +539,30 @@ def main():
                      "note": "batches alternate between streams; every stream has its own workspaces and outputs"}
         del slots
 
+    # the same step recorded once into a HIP graph (both calls launch kernels only) and replayed: what a serving loop
+    # with fixed buffers would do.  Reported beside the headline, which stays eager launches; the sample seed is a
+    # kernel argument, so every replay draws the same sample (the results do not depend on it in this mode).
+    graph_replay = None
+    if args.graph:
+        gstream = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=gstream):
+            step(0)
+        torch.cuda.synchronize()
+        for _ in range(max(2, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        graph_replay = {"steps": args.steps, "ms_per_step": g_ms, "queries_per_s": B / (g_ms * 1e-3),
+                        "outputs_identical_to_the_eager_run": bool(torch.equal(out2[0], final_idx) and torch.equal(out2[1], final_score)),
+                        "note": "one captured step (hindexer_topk -> mol_topk, kernel nodes only) replayed back to back"}
+        del graph
+
     scan_ms, scan_n = prof_scan["scan_filter"]
     scan_bytes = wl.N * wl.d1 * (1 if int8 else (4 if wl.stage1_dtype == "f32" else 2))
     achieved = scan_bytes / (scan_ms / scan_n * 1e-3) / 1e9 if scan_n else 0.0
@@ -590,6 +617,8 @@ def main():
     }
     if pipelined:
         result["pipelined"] = pipelined
+    if graph_replay:
+        result["graph_replay"] = graph_replay
 
     if not args.no_ceiling and not decomposed:
         ceil = measured_ceilings(m, corpus, x1, None if gen else final_cand, dev, gather_bytes)
