@@ -780,45 +780,52 @@ __device__ inline uint2 surv_status(const uint32_t *cnt, int64_t L, int64_t cap,
 }
 
 // Walks lists [lo, hi) of query b.  A wavefront takes 32 lists at a time: the lanes fetch the counts with one load, then
-// the lists are read sixteen at a time (independent loads in flight), each half of the wavefront across the entries of
-// one list (a list holds about 30 entries at the sizes the path is tuned for).
+// the lists are read sixteen at a time (independent loads in flight), LPL lanes across the entries of one list (32 where
+// a list holds about 30 entries, N = 1e8 and 32 queries; 8 where it holds three or four, N = 1e7 and 128 queries).
 // f(entry, valid) is called the same number of times by all 64 lanes of a wavefront (wavefront collectives are safe).
-template <class F>
+template <int LPL, class F>
 __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint32_t *cnt, int64_t L, int64_t cap, int B, int b,
                                                   int64_t lo, int64_t hi, int nwaves_in_block, F f) {
+  static_assert(LPL == 32 || LPL == 16 || LPL == 8, "lanes per list");
+  constexpr int LPW = 64 / LPL;  // lists one load instruction of a wavefront covers
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int hf = lane >> 5, sub = lane & 31;
+  const int which = lane / LPL, sub = lane % LPL;
   const uint32_t cap32 = (uint32_t)cap;
-  constexpr int CHUNK = 32;  // lists a wavefront takes at a time (small, so that all wavefronts of a workgroup get lists)
-  constexpr int UNR = 8;     // list pairs in flight
+  constexpr int CHUNK = 32;        // lists a wavefront takes at a time (small, so that all wavefronts of a workgroup get lists)
+  constexpr int UNR = 16 / LPW;    // load instructions in flight: 16 lists
   for (int64_t l0 = lo + (int64_t)wv * CHUNK; l0 < hi; l0 += (int64_t)nwaves_in_block * CHUNK) {
     uint32_t mine = 0;  // lane j (and j + 32) holds the count of list l0 + j
-    if (l0 + sub < hi) mine = cnt[(size_t)b * L + l0 + sub];
+    if (l0 + (lane & 31) < hi) mine = cnt[(size_t)b * L + l0 + (lane & 31)];
     if (mine > cap32) mine = cap32;
     const int nl = (int)((hi - l0) < CHUNK ? (hi - l0) : CHUNK);
     const uint2 *base = surv + ((size_t)l0 * B + b) * cap;  // list l of query b starts at (l * B + b) * cap
     const size_t lstride = (size_t)B * cap;
-    for (int i0 = 0; i0 < nl; i0 += 2 * UNR) {
+    for (int i0 = 0; i0 < nl; i0 += LPW * UNR) {
       uint32_t n[UNR], nmax[UNR];
       uint2 v[UNR];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) {  // the lower half of the wavefront reads list i0 + 2u, the upper half the next one
-        const int l_lo = i0 + 2 * u, l_hi = l_lo + 1;
-        const uint32_t n_lo = (l_lo < nl) ? (uint32_t)__shfl((int)mine, l_lo) : 0u;
-        const uint32_t n_hi = (l_hi < nl) ? (uint32_t)__shfl((int)mine, l_hi & 31) : 0u;
-        n[u] = hf ? n_hi : n_lo;
-        nmax[u] = n_lo > n_hi ? n_lo : n_hi;
+      for (int u = 0; u < UNR; ++u) {  // lane group `which` of the wavefront reads list i0 + LPW * u + which
+        const int li = i0 + LPW * u + which;
+        const uint32_t from = (uint32_t)__shfl((int)mine, li & 31);  // by every lane: the lane read from must be active
+        n[u] = (li < nl) ? from : 0u;
+        uint32_t mx = n[u];  // the longest of the LPW lists: every lane makes that many rounds
+#pragma unroll
+        for (int o = LPL; o < 64; o <<= 1) {
+          const uint32_t other = (uint32_t)__shfl_xor((int)mx, o);
+          mx = other > mx ? other : mx;
+        }
+        nmax[u] = mx;
         v[u] = make_uint2(0u, 0u);
-        if ((uint32_t)sub < n[u]) v[u] = base[(size_t)(l_lo + hf) * lstride + sub];
+        if ((uint32_t)sub < n[u]) v[u] = base[(size_t)li * lstride + sub];
       }
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
         if (nmax[u]) f(v[u], (uint32_t)sub < n[u]);
-        for (uint32_t e0 = 32; e0 < nmax[u]; e0 += 32) {  // lists longer than half a wavefront
+        for (uint32_t e0 = LPL; e0 < nmax[u]; e0 += LPL) {  // lists longer than a lane group
           const uint32_t e = e0 + sub;
           const bool valid = e < n[u];
           uint2 w = make_uint2(0u, 0u);
-          if (valid) w = base[(size_t)(i0 + 2 * u + hf) * lstride + e];
+          if (valid) w = base[(size_t)(i0 + LPW * u + which) * lstride + e];
           f(w, valid);
         }
       }
@@ -829,6 +836,7 @@ __device__ __forceinline__ void for_each_survivor(const uint2 *surv, const uint3
 // Pass 0 also works out the query's status from the list counts (every workgroup for itself; the first one records it
 // for the passes and kernels that follow).  With key windows (win != NULL) there is only pass 0, over the slices of the
 // query's window instead of the first key digit.
+template <int LPL>
 __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, const uint32_t *cnt, int64_t L,
                                                             int64_t cap, uint2 *sstat, int Kp, uint32_t *mhist,
                                                             const uint2 *win, int B, int pass, int mode, bool force) {
@@ -845,7 +853,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_hist(const uint2 *surv, c
   const int64_t per = (L + G - 1) / G;
   const int64_t lo = blk * per, hi = lo + per < L ? lo + per : L;
   auto each = [&](auto f) {
-    for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+    for_each_survivor<LPL>(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
       if (valid) f(e.x, e.y);
     });
   };
@@ -969,6 +977,7 @@ __device__ inline void surv_finish(const SurvCut &c, uint2 stt, int Kp, int b, c
 // itself (every workgroup for itself; the first one records it for k_surv_finish) and mhist is the window histogram.
 // (Closing the query in the last of its workgroups to finish, instead of a kernel of its own, was four times slower: the
 // device-scope fence each workgroup needs before its ticket writes back the whole L2 of its XCD.)
+template <int LPL>
 __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, const uint32_t *cnt, int64_t L,
                                                             int64_t cap, uint2 *sstat, int Kp, const uint32_t *mhist,
                                                             const uint2 *win, int B, int mode, bool force,
@@ -999,7 +1008,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   __shared__ uint32_t block_base;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   uint32_t mine = 0;
-  for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+  for_each_survivor<LPL>(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
     const uint32_t k = c.cls(e.x);
     const bool at = valid && !take_all && k == c.d;
     const bool take = valid && (take_all || k > c.d || (at && all_ties));
@@ -1015,7 +1024,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_emit(const uint2 *surv, c
   __syncthreads();
   uint32_t off = block_base;
   for (int i = 0; i < wv; ++i) off += wave_tot[i];
-  for_each_survivor(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
+  for_each_survivor<LPL>(surv, cnt, L, cap, B, b, lo, hi, MSEL_THREADS / 64, [&](uint2 e, bool valid) {
     const uint32_t k = c.cls(e.x);
     const bool at = valid && !take_all && k == c.d;
     const bool take = valid && (take_all || k > c.d || (at && all_ties));
@@ -1411,12 +1420,17 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     const uint2 *w = p.sampling ? win : nullptr;
     // no key window without a sample: three digit passes over the survivors; with windows one pass over their slices
     const int hist_passes = p.sampling ? 1 : MSEL_PASSES;
+    // lanes of a wavefront per list when the lists are walked: a list holds p.cap entries at most, about a third of that
+    // on average
+    const bool short_lists = p.cap <= 32;
+    auto hist_k = short_lists ? k_surv_hist<8> : k_surv_hist<32>;
+    auto emit_k = short_lists ? k_surv_emit<8> : k_surv_emit<32>;
     for (int pass = 0; pass < hist_passes; ++pass) {
-      hipLaunchKernelGGL(k_surv_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
+      hipLaunchKernelGGL(hist_k, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
                          pass, mode, force_redo);
       HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(k_surv_emit, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
+    hipLaunchKernelGGL(emit_k, dim3(G, B), dim3(MSEL_THREADS), 0, st, surv, cnt, p.L, p.cap, sstat, Kp, mhist2, w, B,
                        mode, force_redo, mcnt, tiebuf, cand_idx, cand_score);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(k_surv_finish, dim3(B), dim3(MSEL_THREADS), 0, st, sstat, Kp, mhist2, w, B, tiebuf, flags, gate,
