@@ -38,6 +38,12 @@
 #ifndef MOL_SCAN_DEPTH_I8
 #define MOL_SCAN_DEPTH_I8 1
 #endif
+#ifndef MOL_SCAN_DEPTH_Q4
+#define MOL_SCAN_DEPTH_Q4 2  // tiles in flight per wavefront of the filtering scan with four query groups (queries in LDS)
+#endif
+#ifndef MOL_SCAN_WAVES_Q4
+#define MOL_SCAN_WAVES_Q4 3  // ... and its wavefronts per SIMD
+#endif
 
 namespace {
 
@@ -202,7 +208,7 @@ __device__ inline bool last_workgroup(uint32_t *ticket) {
 #define MOL_SCAN_MIN_WAVES 2  // keeps the 4-query-group variants at two wavefronts per SIMD (they need 260 registers otherwise)
 #endif
 template <int DT, int NQG, int EPI, bool GATHER, int DEPTH>
-__global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArgs a) {
+__global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES_Q4 : MOL_SCAN_MIN_WAVES) void k_stage1_scan(ScanArgs a) {
   constexpr int NCH = DT == MOL_F32 ? 8 : (DT == MOL_BF16 ? 4 : 2);
   constexpr int ROWB = DT == MOL_F32 ? 256 : (DT == MOL_BF16 ? 128 : 64);
   constexpr bool REDO = EPI >= EPI_HIST_KEY;
@@ -353,12 +359,6 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
 
       // acc[g][j]: item row 8*(j/4) + 4*h + j%4 of the tile, query qbase + 32*g + r
       const int64_t row0 = tile * 32 + 4 * h;
-      uint32_t vmask = 0xffffu;  // rows of this lane that exist (only the last tile can be partial)
-      if (tile == ntiles - 1) {
-        vmask = 0;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) vmask |= (row0 + 8 * (j >> 2) + (j & 3) < a.n_rows) ? (1u << j) : 0u;
-      }
 #pragma unroll
       for (int g = 0; g < NQG; ++g) {
         const int b = a.qbase + 32 * g + r;
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
           } else {
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-              if (acc[g][j] > thr[g] && ((vmask >> j) & 1u)) append(j);
+              if (acc[g][j] > thr[g] && row0 + 8 * (j >> 2) + (j & 3) < a.n_rows) append(j);  // the last tile can be partial
           }
         } else if constexpr (EPI == EPI_FILTER_EXACT) {
           if (st_active[g] == 3u) {
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
     }
     return true;
   };
-  static_assert(DEPTH >= 1 && DEPTH <= 4, "ring slots are walked by hand");
+  static_assert(DEPTH >= 1 && DEPTH <= 6, "ring slots are walked by hand");
   for (int64_t it0 = 0; it0 < n_it; it0 += DEPTH) {
     if (!do_tile(buf[0], it0)) break;
     if constexpr (DEPTH > 1)
@@ -436,6 +436,10 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? 3 : MOL_SCAN_M
       if (!do_tile(buf[2], it0 + 2)) break;
     if constexpr (DEPTH > 3)
       if (!do_tile(buf[3], it0 + 3)) break;
+    if constexpr (DEPTH > 4)
+      if (!do_tile(buf[4], it0 + 4)) break;
+    if constexpr (DEPTH > 5)
+      if (!do_tile(buf[5], it0 + 5)) break;
   }
   if constexpr (LISTS) {
 #pragma unroll
@@ -1060,7 +1064,8 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat
 template <int DT, int EPI, bool GATHER>
 void (*scan_kernel(int nqg))(ScanArgs) {
   constexpr int DEPTH = DT == MOL_INT8 ? MOL_SCAN_DEPTH_I8 : MOL_SCAN_DEPTH;
-  return nqg == 4 ? k_stage1_scan<DT, 4, EPI, GATHER, DEPTH>
+  constexpr int DEPTH4 = scan_queries_in_lds(EPI, 4) ? (DT == MOL_INT8 ? 1 : MOL_SCAN_DEPTH_Q4) : DEPTH;
+  return nqg == 4 ? k_stage1_scan<DT, 4, EPI, GATHER, DEPTH4>
                   : (nqg == 2 ? k_stage1_scan<DT, 2, EPI, GATHER, DEPTH> : k_stage1_scan<DT, 1, EPI, GATHER, DEPTH>);
 }
 
@@ -1116,7 +1121,7 @@ mol_status_t scan_grid(int nqg, int64_t ntiles, int64_t *grid_out) {
   mol_status_t rc = scan_occupancy<DT, EPI, GATHER>(nqg, &per_sm);
   if (rc != MOL_OK) return rc;
   constexpr int PER_CU = DT == MOL_INT8 ? MOL_SCAN_PER_CU_I8 : MOL_SCAN_PER_CU;
-  const int per_cu = (scan_queries_in_lds(EPI, nqg) && PER_CU < 3) ? 3 : PER_CU;
+  const int per_cu = (scan_queries_in_lds(EPI, nqg) && PER_CU < MOL_SCAN_WAVES_Q4) ? MOL_SCAN_WAVES_Q4 : PER_CU;
   if (per_sm > per_cu) per_sm = per_cu;
   const int cus = device_cus();
   if (cus <= 0) return mol_fail(MOL_EHIP, "cannot query the device");
