@@ -167,21 +167,65 @@ __device__ __forceinline__ void msel_slice_for_each(const T *p, int64_t n, int b
 }
 
 // Finishing helper: of the nt entries (key, idx) parked in `parked`, the `need` first ones under the order (key
-// descending, idx ascending) are handed to `put(rank, key, idx)`, rank = 0 .. need-1 in that order.
-// One workgroup; nt <= MSEL_TIE_CAP.  `scratch` is LDS for MSEL_TIE_CAP entries.
+// descending, idx ascending) are handed to `put(slot, key, idx)`, every slot 0 .. need-1 once, in no particular order.
+// One workgroup of MSEL_THREADS; nt <= MSEL_TIE_CAP; need <= nt.  `scratch` is LDS for MSEL_TIE_CAP entries.
+// Few entries are ranked against each other; many (integer-valued scores put hundreds of equal keys into one slice)
+// go through an 8-bit radix selection in LDS, four digits of the key and, where the cut falls inside a run of equal keys,
+// four of the index.
 template <class Put>
-__device__ inline void msel_take_best(const uint2 *parked, uint32_t nt, uint32_t need, uint2 *scratch, Put put) {
+__device__ inline void msel_take_best(const uint2 *parked, uint32_t nt, uint32_t need, uint2 *scratch, MselShared &sh,
+                                      Put put) {
   for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) scratch[i] = parked[i];
   __syncthreads();
-  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
-    const uint2 me = scratch[i];
-    uint32_t rank = 0;
-    for (uint32_t j = 0; j < nt; ++j) {
-      const uint2 o = scratch[j];
-      const bool before = o.x > me.x || (o.x == me.x && (o.y < me.y || (o.y == me.y && j < i)));
-      rank += before ? 1u : 0u;
+  if (nt <= MSEL_THREADS) {
+    for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
+      const uint2 me = scratch[i];
+      uint32_t rank = 0;
+      for (uint32_t j = 0; j < nt; ++j) {
+        const uint2 o = scratch[j];
+        const bool before = o.x > me.x || (o.x == me.x && (o.y < me.y || (o.y == me.y && j < i)));
+        rank += before ? 1u : 0u;
+      }
+      if (rank < need) put(rank, me.x, me.y);
     }
-    if (rank < need) put(rank, me.x, me.y);
+    __syncthreads();
+    return;
+  }
+  uint32_t kth_key = 0, idx_limit = 0xffffffffu, prefix = 0, krem = need;
+  bool on_idx = false;
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 24 - 8 * (pass & 3);
+    for (int i = threadIdx.x; i < 256; i += MSEL_THREADS) sh.hist[i] = 0;
+    __syncthreads();
+    for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
+      const uint2 e = scratch[i];
+      const uint32_t v = on_idx ? ~e.y : e.x;
+      bool match = !on_idx || e.x == kth_key;
+      if (shift < 24) match = match && (v >> (shift + 8)) == (prefix >> (shift + 8));
+      if (match) atomicAdd(&sh.hist[(v >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    msel_find(sh.hist, 256, krem, sh);
+    prefix |= sh.res[0] << shift;
+    const uint32_t in_digit = sh.res[2];
+    krem = sh.res[1];
+    __syncthreads();
+    if (pass == 3) {
+      kth_key = prefix;
+      if (krem == in_digit) break;  // every entry with the key at the cut is taken
+      on_idx = true;
+      prefix = 0;
+    }
+    if (pass == 7) idx_limit = ~prefix;
+  }
+  if (threadIdx.x == 0) sh.res[0] = 0;
+  __syncthreads();
+  for (uint32_t i = threadIdx.x; i < nt; i += MSEL_THREADS) {
+    const uint2 e = scratch[i];
+    if (e.x > kth_key || (e.x == kth_key && e.y <= idx_limit)) {
+      const uint32_t slot = atomicAdd(&sh.res[0], 1u);
+      if (slot < need) put(slot, e.x, e.y);
+    }
   }
   __syncthreads();
 }

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
 
   if (n >= SEG_PREFIX_MIN) {
     auto each_prefix = each_of(n / 8);
-    const uint32_t kp = block_select_kth<false>(each_prefix, (uint32_t)k, sh);  // k-th best key of the first eighth
+    const uint32_t kp = block_select_kth<false, false>(each_prefix, (uint32_t)k, sh);  // k-th best key of the first eighth
     const uint32_t bound = (kp == (uint32_t)k) ? sh.kth_key : 0u;               // fewer than k valid entries there: no bound
     __syncthreads();
     if (tid == 0) s_cnt = 0;
@@ -88,14 +88,14 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
           f(v.x, v.y);
         }
       };
-      const uint32_t kk = block_select_kth<true>(each_buf, (uint32_t)k, sh);
+      const uint32_t kk = block_select_kth<true, false>(each_buf, (uint32_t)k, sh);
       emit(each_buf, kk);
       return;
     }
     __syncthreads();
   }
 
-  const uint32_t kk = block_select_kth<true>(each, (uint32_t)k, sh);  // min(k, valid entries of the slice)
+  const uint32_t kk = block_select_kth<true, false>(each, (uint32_t)k, sh);  // min(k, valid entries of the slice)
   emit(each, kk);
 }
 

@@ -47,6 +47,76 @@ __device__ __forceinline__ void block_for_each(const T *p, int64_t n, F f) {
 //
 // One radix pass.  ON_IDX = false: digit of the key, among elements agreeing with sh.prefix above bit `hi`.
 // ON_IDX = true: digit of ~idx among the elements whose key equals sh.kth_key.
+// Two forms of the search for the digit that holds the wanted rank.  select_pass_narrow leaves it to the first
+// wavefront (the other fifteen wait at the barrier and cost nothing): right where the device is full of such
+// workgroups and instruction issue is what counts (level 1 of the final top-k at B = 1024).  select_pass gives every
+// thread two bins: a third of the latency, sixteen times the instructions: right where one workgroup per query is all
+// there is (thresholds, level 2 of the top-k).
+template <bool ON_IDX, class Each>
+__device__ void select_pass_narrow(Each each, int lo, int hi, SelectShared &sh) {
+  const int tid = threadIdx.x;
+  for (int i = tid; i < SELECT_BINS; i += SELECT_THREADS) sh.hist[i] = 0;
+  __syncthreads();
+  const uint32_t prefix = sh.prefix;
+  const uint32_t kth_key = sh.kth_key;
+  const int w = hi - lo + 1;
+  const uint32_t dmask = (1u << w) - 1u;
+  each([&](uint32_t key, uint32_t idx) {
+    uint32_t k = key;
+    bool valid = true;
+    if (ON_IDX) {
+      valid = key == kth_key;
+      k = ~idx;  // ascending index == descending ~index
+    }
+    const bool match = (hi >= 31) ? true : ((k >> (hi + 1)) == (prefix >> (hi + 1)));
+    if (valid && match) atomicAdd(&sh.hist[(k >> lo) & dmask], 1u);
+  });
+  __syncthreads();
+  // locate the digit that holds rank krem counting from the largest digit: the first wavefront alone, with lane scans
+  // (chunk t covers `per` consecutive digits from the top; then the lanes take one digit each of the chunk that holds it)
+  const int nb = 1 << w;
+  const int per = (nb + 63) / 64;  // digits per chunk (<= 32)
+  if (tid < 64) {
+    const uint32_t krem = sh.krem;
+    uint32_t s = 0;
+    const int top = nb - 1 - tid * per;
+    for (int j = 0; j < per; ++j) {
+      const int d = top - j;
+      if (d >= 0) s += sh.hist[d];
+    }
+    uint32_t incl = s;  // inclusive sum over chunks 0..tid
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t up = (uint32_t)__shfl_up((int)incl, o);
+      if (tid >= o) incl += up;
+    }
+    // first chunk whose inclusive sum reaches krem (the last chunk if none does: krem never exceeds the total)
+    const uint64_t reach = __ballot(incl >= krem);
+    const int c = reach ? __ffsll((unsigned long long)reach) - 1 : 63;
+    const uint32_t before = (uint32_t)__shfl((int)(incl - s), c);  // elements in the chunks above chunk c
+    // inside chunk c: lane j takes digit dtop - j
+    const int dtop = nb - 1 - c * per;
+    const int d_mine = dtop - tid;
+    const uint32_t h = (tid < per && d_mine >= 0) ? sh.hist[d_mine] : 0u;
+    uint32_t hin = h;
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+      const uint32_t up = (uint32_t)__shfl_up((int)hin, o);
+      if (tid >= o) hin += up;
+    }
+    const uint64_t hit = __ballot(tid < per && d_mine >= 0 && before + hin >= krem);
+    int j = hit ? __ffsll((unsigned long long)hit) - 1 : (dtop < per ? dtop : per - 1);  // fall back to the chunk's last digit
+    const uint32_t above = before + (uint32_t)__shfl((int)(hin - h), j);
+    if (tid == 0) {
+      const int d = dtop - j;
+      sh.krem = krem - above;  // rank inside digit d
+      sh.prefix = prefix | ((uint32_t)d << lo);
+      sh.ties = sh.hist[d];
+    }
+  }
+  __syncthreads();
+}
+
 // sh.hist must be all zero on entry and is all zero again on return.
 template <bool ON_IDX, class Each>
 __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
@@ -107,7 +177,7 @@ __device__ void select_pass(Each each, int lo, int hi, SelectShared &sh) {
 // idx <= idx_limit }, which has exactly the returned number of members; 0 is returned for an empty list or K = 0 and
 // nothing may then be accepted.
 // WITH_TIES = false skips the index stage (idx_limit = all ones): used when only the key value matters.
-template <bool WITH_TIES, class Each>
+template <bool WITH_TIES, bool WIDE = true, class Each>
 __device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   const int tid = threadIdx.x;
   // 1. size of the list and range of the keys: bits above the highest differing bit are common and need no pass
@@ -157,7 +227,8 @@ __device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
     while (hi >= 0) {
       int lo = hi - (SELECT_BITS - 1);
       if (lo < 0) lo = 0;
-      select_pass<false>(each, lo, hi, sh);
+      if constexpr (WIDE) select_pass<false>(each, lo, hi, sh);
+      else select_pass_narrow<false>(each, lo, hi, sh);
       hi = lo - 1;
     }
   }
@@ -174,7 +245,8 @@ __device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   for (int hi = 31; hi >= 0;) {
     int lo = hi - (SELECT_BITS - 1);
     if (lo < 0) lo = 0;
-    select_pass<true>(each, lo, hi, sh);
+    if constexpr (WIDE) select_pass<true>(each, lo, hi, sh);
+    else select_pass_narrow<true>(each, lo, hi, sh);
     hi = lo - 1;
   }
   if (tid == 0) sh.idx_limit = ~sh.prefix;

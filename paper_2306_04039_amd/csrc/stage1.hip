@@ -933,7 +933,7 @@ __device__ inline SurvCut surv_cut(uint2 stt, int Kp, const uint32_t *mhist, con
 // class at the cut, pads the row, writes cand_count, and sets up the exact redo when the lists cannot give the answer
 // (or more members are parked than the buffer holds).
 __device__ inline void surv_finish(const SurvCut &c, uint2 stt, int Kp, int b, const uint2 *tiebuf, uint2 *s_tie,
-                                   uint32_t *flags, uint32_t *gate, ExactState *state, uint32_t *ehist,
+                                   MselShared &sh, uint32_t *flags, uint32_t *gate, ExactState *state, uint32_t *ehist,
                                    int32_t *cand_idx, float *cand_score, int32_t *cand_count) {
   const int tid = threadIdx.x;
   const bool redo = c.kind == 2 || (c.kind == 1 && c.need != c.cbin && c.cbin > MSEL_TIE_CAP);
@@ -964,7 +964,7 @@ __device__ inline void surv_finish(const SurvCut &c, uint2 stt, int Kp, int b, c
     nout = (uint32_t)Kp;
     if (c.need != c.cbin) {  // only the `need` best of the cbin parked members of the class at the cut are taken
       const uint32_t base = (uint32_t)Kp - c.need;
-      msel_take_best(tiebuf + (size_t)b * MSEL_TIE_CAP, c.cbin, c.need, s_tie, [&](uint32_t rank, uint32_t key, uint32_t idx) {
+      msel_take_best(tiebuf + (size_t)b * MSEL_TIE_CAP, c.cbin, c.need, s_tie, sh, [&](uint32_t rank, uint32_t key, uint32_t idx) {
         oi[base + rank] = (int32_t)idx;
         if (os) os[base + rank] = key_to_f32(key);
       });
@@ -1057,7 +1057,7 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_surv_finish(const uint2 *sstat
   const int b = blockIdx.x;
   const uint2 stt = sstat[b];
   const SurvCut c = surv_cut(stt, Kp, mhist, win, B, b, sh);
-  surv_finish(c, stt, Kp, b, tiebuf, s_tie, flags, gate, state, ehist, cand_idx, cand_score, cand_count);
+  surv_finish(c, stt, Kp, b, tiebuf, s_tie, sh, flags, gate, state, ehist, cand_idx, cand_score, cand_count);
 }
 
 // ---- launch helpers ----------------------------------------------------------------------------------------------

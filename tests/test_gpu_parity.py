@@ -321,3 +321,41 @@ def test_hindexer_massive_ties_take_the_lowest_indices():
     assert np.all(cc == Kp)
     for b in range(B):
         assert sorted(ci[b].tolist()) == list(range(50)) + list(range(5000, 5150))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "int8"])
+def test_hindexer_cut_inside_a_long_run_of_equal_scores(dtype):
+    """300 distinct rows, each repeated 1000 times (interleaved): every query sees 300 score values with 1000 items each.
+    K' = 4500 puts the cut in the middle of the fifth value's run, so the slice of the key window at the cut holds 1000
+    parked entries of which the 500 lowest indices are taken (the selection in LDS of the finishing kernel, key digits
+    and index digits), without the exact redo: no survivor list overflows, the rows are interleaved."""
+    N, B, Kp, reps = 300_000, 6, 4500, 1000
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, n_clusters=16)
+    items, q, gw = make(wl)
+    proto = items["x1"][: N // reps].clone()
+    items["x1"][:] = proto.repeat(reps, 1)                      # item i is a copy of prototype i % 300
+    x1, q1 = items["x1"], q["q1"]
+    if dtype == "int8":
+        x1 = m().quantize_int8(x1, 127.0 / float(x1.float().abs().max()))
+        q1 = m().quantize_int8(q1, 127.0 / float(q1.float().abs().max()))
+    corpus = m().mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u)
+    ci, cs, cc = m().hindexer_topk(corpus, q1, Kp, seed=11)
+    torch.cuda.synchronize()
+    ci, cc = ci.cpu().numpy(), cc.cpu().numpy()
+    assert np.all(cc == Kp)
+    # scores of the prototypes in the arithmetic of the table (exact: fp64 of the stored values)
+    sp = orc.stage1_scores(bits(q1), bits(x1[: N // reps]))
+    checked = 0
+    for b in range(B):
+        order = np.argsort(-sp[b], kind="stable")
+        top = sp[b, order[:7]]
+        if np.min(top[:-1] - top[1:]) < (0.5 if dtype == "int8" else 1e-5):
+            continue                                            # two prototypes (nearly) tie for this query: not the case meant here
+        checked += 1
+        want = set()
+        for rank, pidx in enumerate(order[:5]):
+            members = np.arange(pidx, N, N // reps)            # ascending item indices of this prototype's copies
+            want.update(members[: reps if rank < 4 else Kp - 4 * reps].tolist())
+        assert set(ci[b].tolist()) == want, f"query {b}: the run at the cut must give its lowest indices"
+    assert checked >= B // 2
+    corpus.free()
