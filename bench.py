@@ -30,7 +30,7 @@ PAPER_CONTEXT = {"median_latency_ms_incl_batching_wait": 30.0, "hardware": "unna
 
 CSRC = os.path.join(ROOT, "paper_2306_04039_amd", "csrc")
 KERNEL_SOURCES = {  # the files a kernel is compiled from: their hash ties a profiler counter to the code that produced it
-    "k_stage1_scan": ("stage1.hip", "common.hpp", "msel.hpp"),
+    "k_stage1_scan": ("stage1.hip", "common.hpp", "msel.hpp", "select.hpp"),
     "k_mol_score": ("mol.hip", "common.hpp"),
 }
 

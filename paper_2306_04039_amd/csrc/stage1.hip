@@ -504,28 +504,55 @@ __global__ void k_gen_sample(int32_t *out, int64_t lambda, uint64_t seed, uint64
 
 // Per query: threshold = the rank-th largest sampled score (Algorithm 2, nthElement), by multi-workgroup radix
 // selection over the B x lambda score keys.  k_thr_hist is launched once per digit pass; k_thr_finish writes the
-// threshold and resets the flags and the redo gate.
+// threshold and resets the flags and the redo gate.  The same sweeps find the rank_u-th largest key (the top of the
+// query's key window) in a histogram set of its own: the first pass counts every key for both, the later ones count a
+// key for whichever of the two prefixes it matches.
 __global__ __launch_bounds__(MSEL_THREADS) void k_thr_hist(const uint32_t *skeys, int64_t stride, int64_t lambda,
-                                                           uint32_t rank, uint32_t *mhist, int B, int pass) {
+                                                           uint32_t rank, uint32_t rank_u, uint32_t *mhist,
+                                                           uint32_t *mhist_u, int B, int pass) {
   __shared__ MselShared sh;
+  __shared__ uint32_t hist_u[MSEL_BINS];
   const int b = blockIdx.y, blk = blockIdx.x, G = gridDim.x;
-  uint32_t prefix = 0;
-  if (pass > 0) prefix = msel_cut(mhist, B, b, rank, pass, sh).prefix;
+  uint32_t prefix = 0, prefix_u = 0;
+  if (pass > 0) {
+    prefix = msel_cut(mhist, B, b, rank, pass, sh).prefix;
+    if (rank_u) prefix_u = msel_cut(mhist_u, B, b, rank_u, pass, sh).prefix;
+  }
   const uint32_t *keys = skeys + (size_t)b * stride;  // rows are 16-byte aligned (stride is a multiple of 32 keys)
-  auto each = [&](auto f) {
-    const int64_t n4 = lambda >> 2;
-    msel_slice_for_each<4>(reinterpret_cast<const uint4 *>(keys), n4, blk, G, [&](int64_t, uint4 v, bool valid) {
-      if (valid) {
-        f(v.x, 0u);
-        f(v.y, 0u);
-        f(v.z, 0u);
-        f(v.w, 0u);
-      }
-    });
-    if (blk == 0)
-      for (int64_t i = 4 * n4 + threadIdx.x; i < lambda; i += MSEL_THREADS) f(keys[i], 0u);
+  const int nb = msel_bins(pass);
+  for (int i = threadIdx.x; i < nb; i += MSEL_THREADS) {
+    sh.hist[i] = 0;
+    hist_u[i] = 0;
+  }
+  __syncthreads();
+  const int lo = msel_lo(pass);
+  const int hi_shift = lo + (pass == 2 ? 10 : 11);
+  const uint32_t mask = (uint32_t)nb - 1u;
+  const bool both = rank_u != 0 && pass > 0;
+  auto count = [&](uint32_t key) {
+    const uint32_t d = (key >> lo) & mask;
+    if (pass == 0 || (key >> hi_shift) == (prefix >> hi_shift)) atomicAdd(&sh.hist[d], 1u);
+    if (both && (key >> hi_shift) == (prefix_u >> hi_shift)) atomicAdd(&hist_u[d], 1u);
   };
-  msel_hist_pass(each, pass, prefix, mhist + ((size_t)pass * B + b) * MSEL_BINS, sh);
+  const int64_t n4 = lambda >> 2;
+  msel_slice_for_each<4>(reinterpret_cast<const uint4 *>(keys), n4, blk, G, [&](int64_t, uint4 v, bool valid) {
+    if (valid) {
+      count(v.x);
+      count(v.y);
+      count(v.z);
+      count(v.w);
+    }
+  });
+  if (blk == 0)
+    for (int64_t i = 4 * n4 + threadIdx.x; i < lambda; i += MSEL_THREADS) count(keys[i]);
+  __syncthreads();
+  uint32_t *g = mhist + ((size_t)pass * B + b) * MSEL_BINS, *gu = mhist_u + ((size_t)pass * B + b) * MSEL_BINS;
+  for (int i = threadIdx.x; i < nb; i += MSEL_THREADS) {
+    const uint32_t v = sh.hist[i];
+    if (v) atomicAdd(&g[i], v);
+    const uint32_t vu = pass == 0 ? v : hist_u[i];
+    if (rank_u && vu) atomicAdd(&gu[i], vu);
+  }
 }
 
 // `passes` digit passes were made: 3 give the exact rank-th sampled key (Algorithm 2 as written); with 2 the threshold is
@@ -533,17 +560,19 @@ __global__ __launch_bounds__(MSEL_THREADS) void k_thr_hist(const uint32_t *skeys
 // at least K' items through (the exact top-K' of the survivors is taken afterwards) and one pass over the keys cheaper.
 // The upper end of the query's key window is the rank_u-th sampled key (its bucket's upper end), rank_u < rank chosen
 // by the host so that the K'-th best score of the corpus lies below it; rank_u = 0: no such rank exists in the sample.
-__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, int B, uint32_t rank, uint32_t rank_u,
-                                                             int passes, float *thr, uint2 *win, uint32_t *flags,
-                                                             uint32_t *gate) {
+__global__ __launch_bounds__(MSEL_THREADS) void k_thr_finish(const uint32_t *mhist, const uint32_t *mhist_u, int B,
+                                                             uint32_t rank, uint32_t rank_u, int passes, float *thr,
+                                                             uint2 *win, uint32_t *flags, uint32_t *gate) {
   __shared__ MselShared sh;
   const int b = blockIdx.x;
   const MselCut c = msel_cut(mhist, B, b, rank, passes, sh);
-  const MselCut cu = msel_cut(mhist, B, b, rank_u ? rank_u : 1u, passes, sh);
+  // without a rank for the window top: the largest sampled key, as far as the first pass (which counts every key)
+  // resolves it
+  const MselCut cu = rank_u ? msel_cut(mhist_u, B, b, rank_u, passes, sh) : msel_cut(mhist, B, b, 1u, 1, sh);
   if (threadIdx.x == 0) {
     const uint32_t t_key = c.K ? c.prefix : f32_to_key(-INFINITY);
-    uint32_t u_key = cu.K ? (cu.prefix | (passes < MSEL_PASSES ? 0x3ffu : 0u)) : 0xffffffffu;
-    if (rank_u == 0) u_key = window_top_from_max(t_key, u_key);
+    uint32_t u_key = 0xffffffffu;
+    if (cu.K) u_key = rank_u ? (cu.prefix | (passes < MSEL_PASSES ? 0x3ffu : 0u)) : window_top_from_max(t_key, cu.prefix | 0x1fffffu);
     thr[b] = key_to_f32(t_key);
     win[b] = make_uint2(t_key, u_key);
     flags[b] = 0;
@@ -1270,8 +1299,8 @@ mol_status_t hindexer_plan(const mol_corpus *c, int B, int Kp, int64_t lambda, i
   off = align_up(off + (size_t)B * 8, 256);
   p->off_surv = off;
   off = align_up(off + (size_t)B * p->L * p->cap * 8, 256);
-  p->off_mhist = off;  // two sets of radix-select histograms (sampled threshold, survivors), then counters
-  off = align_up(off + (size_t)2 * MSEL_PASSES * B * MSEL_BINS * 4, 256);
+  p->off_mhist = off;  // three sets of radix-select histograms (sampled threshold, survivors, window top), then counters
+  off = align_up(off + (size_t)3 * MSEL_PASSES * B * MSEL_BINS * 4, 256);
   p->off_mcnt = off;
   off = align_up(off + (size_t)B * MCNT_STRIDE * 4, 256);
   p->off_tie = off;
@@ -1301,6 +1330,7 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
 
   uint32_t *mhist = reinterpret_cast<uint32_t *>(ws + p.off_mhist);
   uint32_t *mhist2 = mhist + (size_t)MSEL_PASSES * B * MSEL_BINS;
+  uint32_t *mhist_u = mhist2 + (size_t)MSEL_PASSES * B * MSEL_BINS;
   uint32_t *mcnt = reinterpret_cast<uint32_t *>(ws + p.off_mcnt);
   uint2 *tiebuf = reinterpret_cast<uint2 *>(ws + p.off_tie);
   uint2 *win = reinterpret_cast<uint2 *>(ws + p.off_win);
@@ -1394,10 +1424,10 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
         const int passes = (mode & 0xff) == MOL_HINDEXER_EXACT ? MSEL_PASSES - 1 : MSEL_PASSES;
         for (int pass = 0; pass < passes; ++pass) {
           hipLaunchKernelGGL(k_thr_hist, dim3(G, B), dim3(MSEL_THREADS), 0, st, skeys, lam_pad, p.lambda, (uint32_t)p.rank,
-                             mhist, B, pass);
+                             (uint32_t)p.rank_u, mhist, mhist_u, B, pass);
           HIP_TRY(hipGetLastError());
         }
-        hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, B, (uint32_t)p.rank,
+        hipLaunchKernelGGL(k_thr_finish, dim3(B), dim3(MSEL_THREADS), 0, st, mhist, mhist_u, B, (uint32_t)p.rank,
                            (uint32_t)p.rank_u, passes, thr, win, flags, gate);
         HIP_TRY(hipGetLastError());
       }

@@ -61,9 +61,9 @@ def test_hindexer_exact_mode_matches_exact_topk(dtype, N, B, Kp):
         np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=S1_TOL)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_hindexer_paper_mode_matches_algorithm2(dtype):
-    N, B, Kp, lam = 60_000, 12, 600, 6000
+@pytest.mark.parametrize("dtype,N,B,Kp,lam", [("bf16", 60_000, 12, 600, 6000), ("f32", 60_000, 12, 600, 6000),
+                                               ("bf16", 400_000, 10, 3000, 40_000)])   # the last: digit passes over B x lambda keys
+def test_hindexer_paper_mode_matches_algorithm2(dtype, N, B, Kp, lam):
     wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype=dtype, n_clusters=64)
     items, q, gw = make(wl)
     corpus = pack(wl, items, gw)
