@@ -175,7 +175,8 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *                                     neighbouring rows) is redone on the device and gives the same set: the K' best
  *                                     that lie above t_b.
  *                 MOL_HINDEXER_EXACT  r = r_paper + ceil(5*sqrt(r_paper)) + 8 so that at least K' survive (the threshold is
- *                                     the rank-r sampled score resolved to its leading 22 key bits, rounded down), then the exact
+ *                                     the rank-r sampled score or a value just below it: only the result is defined in
+ *                                     this mode, and a lower threshold cannot change it), then the exact
  *                                     top-K' of the survivors; a query whose survivors number fewer than K' or overflow the
  *                                     workspace is redone on the device with an exact multi-pass radix threshold.  The
  *                                     result is the exact stage-1 top-K' under fp32 scores.  cand_count[b] = -1 (row
