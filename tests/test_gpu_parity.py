@@ -61,6 +61,42 @@ def test_hindexer_exact_mode_matches_exact_topk(dtype, N, B, Kp):
         np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=S1_TOL)
 
 
+@pytest.mark.parametrize("dtype,N,B,Kp,lam", [
+    ("bf16", 400_000, 40, 2000, 40_000),    # two query groups
+    ("f32", 300_000, 24, 1500, 36_000),     # fp32 table: the bracket kernel's 16-lanes-per-row form
+    ("int8", 400_000, 20, 2500, 50_000),    # int8 table: 4 lanes per row, integer scores (long runs of equal keys)
+    ("bf16", 350_000, 100, 1200, 34_000),   # four query groups: queries in LDS, 4-entry rings, short survivor lists
+])
+def test_hindexer_exact_mode_with_a_large_sample(dtype, N, B, Kp, lam):
+    """Samples too large for one workgroup's LDS take the bracket route in the exact-on-success mode: bracket from the
+    first 4096 sampled rows, the whole sample through the filtering scan, the threshold picked from what passed.  The
+    result must still be the exact top-K', with the library's own sample and with one handed in."""
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, stage1_dtype="f32" if dtype == "f32" else "bf16", n_clusters=64)
+    items, q, gw = make(wl)
+    x1, q1 = items["x1"], q["q1"]
+    if dtype == "int8":
+        x1 = m().quantize_int8(x1, 127.0 / float(x1.float().abs().max()))
+        q1 = m().quantize_int8(q1, 127.0 / float(q1.float().abs().max()))
+    corpus = m().mol_corpus_pack(x1, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, gw.b2, k_u=wl.k_u)
+    s = orc.stage1_scores(bits(q1), bits(x1))
+    S = orc.sample_indices(99, lam, N)
+    outs = [m().hindexer_topk(corpus, q1, Kp, lam=lam, seed=7),
+            m().hindexer_topk(corpus, q1, Kp, sample_idx=torch.from_numpy(S.astype(np.int32)).to(DEV))]
+    torch.cuda.synchronize()
+    tol = 0.0 if dtype == "int8" else S1_TOL
+    for ci, cs, cc in outs:
+        ci, cs, cc = ci.cpu().numpy(), cs.cpu().numpy(), cc.cpu().numpy()
+        assert np.all(cc == Kp)
+        for b in range(B):
+            if dtype == "int8":
+                ids, _ = orc.topk_desc(s[b], Kp)
+                assert np.array_equal(np.sort(ci[b]), np.sort(ids)), f"query {b}"
+            else:
+                assert_topk_set(ci[b], s[b], Kp, tol, f"query {b}")
+            np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=tol)
+    corpus.free()
+
+
 @pytest.mark.parametrize("dtype,N,B,Kp,lam", [("bf16", 60_000, 12, 600, 6000), ("f32", 60_000, 12, 600, 6000),
                                                ("bf16", 400_000, 10, 3000, 40_000)])   # the last: digit passes over B x lambda keys
 def test_hindexer_paper_mode_matches_algorithm2(dtype, N, B, Kp, lam):
