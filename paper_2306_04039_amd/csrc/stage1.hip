@@ -54,6 +54,18 @@ constexpr uint32_t scan_ring_entries(int nqg) { return nqg == 4 ? 4u : 16u; }
 // workgroup uses the same ones) and runs three wavefronts per SIMD: its 64 threshold compares per lane and tile are
 // dependent compare / branch pairs, and a third wavefront hides more of them than the registers were worth.
 constexpr bool scan_queries_in_lds(int epi, int nqg) { return epi == 0 /* EPI_FILTER */ && nqg == 4; }
+// The corpus scan with one query group (the 32-query batch of the 100M-item workload) reads the table with streaming
+// (non-temporal) loads, which only pay when every load instruction takes whole 128-byte lines: 7.1 instead of 6.3 TB/s
+// for a bare read of 12.8 GB, but 3.3 instead of 2.05 ms for the scan when each line is shared by four instructions, as
+// the operand layout (lane = row) has it.  So a wavefront loads a tile as it lies in memory (lane l: bytes 16 l .. 16 l + 15
+// of each KB) and turns it into the operand layout through LDS.
+#ifndef MOL_SCAN_STAGED
+#define MOL_SCAN_STAGED 1
+#endif
+constexpr bool scan_staged(int epi, int nqg, bool gather) {
+  return MOL_SCAN_STAGED && epi == 0 /* EPI_FILTER */ && nqg == 1 && !gather;
+}
+constexpr int scan_row_bytes(int dt) { return dt == MOL_F32 ? 256 : (dt == MOL_BF16 ? 128 : 64); }
 constexpr int scan_chunks(int dt) { return dt == MOL_F32 ? 8 : (dt == MOL_BF16 ? 4 : 2); }
 
 enum { EPI_FILTER = 0, EPI_KEYS = 1, EPI_HIST_KEY = 2, EPI_HIST_IDX = 3, EPI_FILTER_EXACT = 4 };
@@ -225,6 +237,10 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
   // to HBM cost a quarter of the scan's time: 4.6 M scattered partial-line writes at N = 1e8, K' = 1e5.)
   constexpr uint32_t RING = scan_ring_entries(NQG);
   constexpr bool QLDS = scan_queries_in_lds(EPI, NQG);
+  constexpr bool STAGED = scan_staged(EPI, NQG, GATHER);
+  constexpr int CPRW = ROWB / 16;      // 16-byte pieces per row
+  constexpr int RPI = 64 / CPRW;       // rows one load instruction of a wavefront covers when it reads memory as it lies
+  constexpr int STG_ROW = ROWB + 16;   // LDS row pitch of the staged tile (the padding keeps the transposed reads apart)
   if constexpr (REDO) {
     if (*a.gate == 0) return;
   }
@@ -236,6 +252,8 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
   uint4 q[QLDS ? 1 : NQG][QLDS ? 1 : NCH];
   // QLDS: [NQG][NCH][64 lanes] behind the survivor rings
   uint4 *q_lds = reinterpret_cast<uint4 *>(reinterpret_cast<char *>(lds_hist) + (size_t)4 * 64 * NQG * RING * 8);
+  // STAGED: one tile per wavefront, [32 rows][STG_ROW bytes], behind the rings
+  char *stg = reinterpret_cast<char *>(lds_hist) + (size_t)4 * 64 * NQG * RING * 8 + (size_t)(threadIdx.x >> 6) * 32 * STG_ROW;
   float thr[NQG];
   uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
   uint32_t cnt[NQG];
@@ -281,6 +299,15 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
   };
 
   auto load_tile = [&](uint4(&dst)[NCH], int64_t tile) {
+    if constexpr (STAGED) {
+#pragma unroll
+      for (int ci = 0; ci < NCH; ++ci) {
+        int64_t row = tile * 32 + ci * RPI + lane / CPRW;
+        if (row >= a.n_rows) row = a.n_rows - 1;
+        dst[ci] = ld16_stream(a.X + (size_t)row * ROWB + (lane % CPRW) * 16);
+      }
+      return;
+    }
     int64_t row = tile * 32 + r;
     if (row >= a.n_rows) row = a.n_rows - 1;
     if (GATHER) {
@@ -326,26 +353,46 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
           acc[g][j] = 0.f;
           iacc[g][j] = 0;
         }
+      uint4 op[STAGED ? NCH : 1];  // STAGED: the tile in operand layout (lane = row), read back from LDS
+      if constexpr (STAGED) {
+#pragma unroll
+        for (int ci = 0; ci < NCH; ++ci)
+          *reinterpret_cast<uint4 *>(stg + (ci * RPI + lane / CPRW) * STG_ROW + (lane % CPRW) * 16) = tb[ci];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int ci = 0; ci < NCH; ++ci) op[ci] = *reinterpret_cast<const uint4 *>(stg + r * STG_ROW + (2 * ci + h) * 16);
+        // the ring slot is free as soon as it is in LDS: the next tile's loads start before this tile's arithmetic
+        if (it + DEPTH < n_it) {
+          const int64_t tnext = tile_of(it + DEPTH);
+          if (tnext < ntiles) load_tile(tb, tnext);
+        }
+      }
+      auto rowop = [&](int ci) -> uint4 {
+        if constexpr (STAGED) return op[ci];
+        else return tb[ci];
+      };
 #pragma unroll
       for (int ci = 0; ci < NCH; ++ci) {
 #pragma unroll
         for (int g = 0; g < NQG; ++g) {
           if constexpr (DT == MOL_INT8) {
-            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(tb[ci]), as_i32x4(qop(g, ci)), iacc[g], 0, 0, 0);
+            iacc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_i32x4(rowop(ci)), as_i32x4(qop(g, ci)), iacc[g], 0, 0, 0);
           } else if constexpr (DT == MOL_F32) {
-            const float av[4] = {__uint_as_float(tb[ci].x), __uint_as_float(tb[ci].y), __uint_as_float(tb[ci].z),
-                                 __uint_as_float(tb[ci].w)};
+            const uint4 aa = rowop(ci);
+            const float av[4] = {__uint_as_float(aa.x), __uint_as_float(aa.y), __uint_as_float(aa.z), __uint_as_float(aa.w)};
             const uint4 qq = qop(g, ci);
             const float qv[4] = {__uint_as_float(qq.x), __uint_as_float(qq.y), __uint_as_float(qq.z), __uint_as_float(qq.w)};
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[e], qv[e], acc[g], 0, 0, 0);
           } else {
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(tb[ci]), as_bf16x8(qop(g, ci)), acc[g], 0,
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(rowop(ci)), as_bf16x8(qop(g, ci)), acc[g], 0,
                                                              0, 0);
           }
         }
       }
-      if (it + DEPTH < n_it) {
+      if (!STAGED && it + DEPTH < n_it) {
         const int64_t tnext = tile_of(it + DEPTH);
         if (tnext < ntiles) load_tile(tb, tnext);
       }
@@ -1107,7 +1154,9 @@ size_t scan_lds_bytes(int epi, int nqg, int dt) {
   if (epi == EPI_HIST_KEY || epi == EPI_HIST_IDX) return (size_t)32 * nqg * EXACT_BINS * 4;
   if (epi == EPI_FILTER)
     return (size_t)4 * 64 * nqg * scan_ring_entries(nqg) * 8 +
-           (scan_queries_in_lds(epi, nqg) ? (size_t)nqg * scan_chunks(dt) * 64 * 16 : 0);
+           (scan_queries_in_lds(epi, nqg) ? (size_t)nqg * scan_chunks(dt) * 64 * 16 : 0) +
+           // the staged tile of each wavefront (the gathering variant of the same shape does not use it)
+           (scan_staged(epi, nqg, false) ? (size_t)4 * 32 * (scan_row_bytes(dt) + 16) : 0);
   return 0;
 }
 
