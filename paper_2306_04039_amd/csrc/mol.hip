@@ -755,7 +755,7 @@ __global__ __launch_bounds__(256, (exh_min_waves<K_U, K_X, D_P, H>())) void k_mo
 }
 
 // U[b, h] = sum_j W1u[h, j] * gu[b, j]: the user part of gating layer 1, once per query (Section 3.2).
-// One thread per output, 8 bf16 of each operand per load when the rows allow it.
+// Eight lanes per output, 8 bf16 of each operand per load when the rows allow it; the partial sums meet in a fixed tree.
 // UP (optional): the same value as a half head and half remainder, head | remainder << 16, laid out [B][H/32][64] with
 // U[b, 32 mt + l] at [b][mt][l] and zeros at l >= 32 (exhaustive fast path).
 __device__ __forceinline__ uint32_t half_head_and_rest(float v) {
@@ -764,49 +764,54 @@ __device__ __forceinline__ uint32_t half_head_and_rest(float v) {
   return (uint32_t)__builtin_bit_cast(uint16_t, hd) | ((uint32_t)__builtin_bit_cast(uint16_t, rs) << 16);
 }
 
+#define USER_GATE_LPO 8  // lanes per output
 __global__ void k_user_gate(const uint16_t *w1u, const uint16_t *gu, float *U, uint32_t *UP, int B, int H, int d_gu,
                             bool f16) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= B * H) return;
+  constexpr int LPO = USER_GATE_LPO;
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  int i = t / LPO;
+  const int sub = t % LPO;
+  const bool live = i < B * H;
+  if (!live) i = B * H - 1;  // the lane still takes part in the exchange below
   const int b = i / H, hh = i % H;
-  const uint4 *wr = reinterpret_cast<const uint4 *>(w1u + (size_t)hh * d_gu);
-  const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)b * d_gu);
   float acc = 0.f;
   if (d_gu % 8 != 0) {  // rows are not 16-byte aligned: element by element
-    for (int j = 0; j < d_gu; ++j)
+    for (int j = sub; j < d_gu; j += LPO)
       acc = fmaf(dec16(w1u[(size_t)hh * d_gu + j], f16), dec16(gu[(size_t)b * d_gu + j], f16), acc);
+  } else {
+    // the LPO lanes of an output read consecutive 16-byte pieces of both rows (whole lines), four in flight per lane
+    const uint4 *wr = reinterpret_cast<const uint4 *>(w1u + (size_t)hh * d_gu);
+    const uint4 *gr = reinterpret_cast<const uint4 *>(gu + (size_t)b * d_gu);
+    constexpr int PF = 4;
+    const int np = d_gu / 8;
+    for (int j0 = sub; j0 < np; j0 += LPO * PF) {
+      uint4 wq[PF], gq[PF];
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int j = j0 + u * LPO < np ? j0 + u * LPO : j0;
+        wq[u] = wr[j];
+        gq[u] = gr[j];
+      }
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        if (j0 + u * LPO >= np) break;
+        const uint32_t wv[4] = {wq[u].x, wq[u].y, wq[u].z, wq[u].w}, gv[4] = {gq[u].x, gq[u].y, gq[u].z, gq[u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc = fmaf(dec16(wv[e] & 0xffffu, f16), dec16(gv[e] & 0xffffu, f16), acc);
+          acc = fmaf(dec16(wv[e] >> 16, f16), dec16(gv[e] >> 16, f16), acc);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < LPO; o <<= 1) acc += __shfl_xor(acc, o);
+  if (live && sub == 0) {
     U[i] = acc;
     if (UP) {
       UP[((size_t)b * (H / 32) + hh / 32) * 64 + (hh & 31)] = half_head_and_rest(acc);
       UP[((size_t)b * (H / 32) + hh / 32) * 64 + 32 + (hh & 31)] = 0u;
     }
-    return;
-  }
-  // eight 16-byte pieces of both rows in flight at a time (the sum itself stays in element order)
-  constexpr int PF = 8;
-  for (int j0 = 0; j0 < d_gu / 8; j0 += PF) {
-    uint4 wq[PF], gq[PF];
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      const int j = j0 + u < d_gu / 8 ? j0 + u : j0;
-      wq[u] = wr[j];
-      gq[u] = gr[j];
-    }
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      if (j0 + u >= d_gu / 8) break;
-      const uint32_t wv[4] = {wq[u].x, wq[u].y, wq[u].z, wq[u].w}, gv[4] = {gq[u].x, gq[u].y, gq[u].z, gq[u].w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc = fmaf(dec16(wv[e] & 0xffffu, f16), dec16(gv[e] & 0xffffu, f16), acc);
-        acc = fmaf(dec16(wv[e] >> 16, f16), dec16(gv[e] >> 16, f16), acc);
-      }
-    }
-  }
-  U[i] = acc;
-  if (UP) {
-    UP[((size_t)b * (H / 32) + hh / 32) * 64 + (hh & 31)] = half_head_and_rest(acc);
-    UP[((size_t)b * (H / 32) + hh / 32) * 64 + 32 + (hh & 31)] = 0u;
   }
 }
 
@@ -915,7 +920,7 @@ mol_status_t launch_user_gate(const mol_corpus *c, const void *user_gate, int B,
     HIP_TRY(hipGetLastError());
     return MOL_OK;
   }
-  hipLaunchKernelGGL(k_user_gate, dim3((n + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
+  hipLaunchKernelGGL(k_user_gate, dim3((n * USER_GATE_LPO + 255) / 256), dim3(256), 0, st, static_cast<const uint16_t *>(c->w1u),
                      static_cast<const uint16_t *>(user_gate), U, UP, B, c->H, c->d_gu, c->f16);
   HIP_TRY(hipGetLastError());
   return MOL_OK;
