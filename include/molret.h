@@ -54,6 +54,11 @@ enum { MOL_GATE_CONCAT = 0, MOL_GATE_DECOMPOSED = 1 }; /* gate_form */
 #define MOL_HINDEXER_PAPER 1 /* Algorithm 2 as written: rank K'*lambda/N, strict filter, at most K' kept */
 #define MOL_HINDEXER_FORCE_REDO 0x100 /* OR into mode: send every query through the exact radix redo (diagnostics, timing of an exact top-K');
                                          the result is that of the mode without the flag */
+#define MOL_HINDEXER_DEFER_REDO 0x200 /* OR into mode: do not redo on the device.  A query the sample misled (or whose lists
+                                         overflowed) comes back with cand_count[b] = -1 and an all -1 row, for the caller to
+                                         submit again without this flag; every other query is unaffected.  Saves the nine
+                                         launches of the redo, which return at once when no query needs them but still
+                                         cost 15-40 us per call: for callers that read cand_count back anyway */
 
 /*
  * Model description (host struct; read during mol_corpus_pack only).

@@ -11,6 +11,8 @@ import torch
 
 HINDEXER_EXACT = 0
 HINDEXER_PAPER = 1
+HINDEXER_FORCE_REDO = 0x100
+HINDEXER_DEFER_REDO = 0x200
 PACK_BORROW_STAGE1 = 1
 PACK_BORROW_EMBS = 2
 

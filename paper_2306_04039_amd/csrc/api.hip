@@ -163,13 +163,13 @@ extern "C" mol_status_t hindexer_topk(const mol_corpus_t *c, const void *q1, int
   if (c->d1 == 0 || !c->stage1) return mol_fail(MOL_EINVAL, "hindexer_topk: the corpus was packed without a stage-1 table");
   if (B < 1 || B > 1024) return mol_fail(MOL_EINVAL, "B=%d must be in [1, 1024]", B);
   if (Kp < 1 || Kp > c->N) return mol_fail(MOL_EINVAL, "Kp=%d must be in [1, N=%lld]", Kp, (long long)c->N);
-  if ((mode & ~MOL_HINDEXER_FORCE_REDO) != MOL_HINDEXER_EXACT && (mode & ~MOL_HINDEXER_FORCE_REDO) != MOL_HINDEXER_PAPER)
-    return mol_fail(MOL_EINVAL, "unknown mode %d", mode);
+  const int base_mode = mode & ~(MOL_HINDEXER_FORCE_REDO | MOL_HINDEXER_DEFER_REDO);
+  if (base_mode != MOL_HINDEXER_EXACT && base_mode != MOL_HINDEXER_PAPER) return mol_fail(MOL_EINVAL, "unknown mode %d", mode);
   if (sample_idx && lambda < 1) return mol_fail(MOL_EINVAL, "an explicit sample needs lambda >= 1");
   HindexerPlan p;
   mol_status_t rc = check_device(c);
   if (rc != MOL_OK) return rc;
-  rc = hindexer_plan(c, B, Kp, lambda, mode & ~MOL_HINDEXER_FORCE_REDO, &p);
+  rc = hindexer_plan(c, B, Kp, lambda, base_mode, &p);
   if (rc != MOL_OK) return rc;
   rc = check_ws(workspace, workspace_bytes, p.total);
   if (rc != MOL_OK) return rc;

@@ -1375,7 +1375,8 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   uint32_t *gate = reinterpret_cast<uint32_t *>(ws + p.off_state);
   ExactState *state = reinterpret_cast<ExactState *>(ws + p.off_state + 256);
   const bool force_redo = (mode & MOL_HINDEXER_FORCE_REDO) != 0;
-  mode &= ~MOL_HINDEXER_FORCE_REDO;
+  const bool defer_redo = (mode & MOL_HINDEXER_DEFER_REDO) != 0;
+  mode &= ~(MOL_HINDEXER_FORCE_REDO | MOL_HINDEXER_DEFER_REDO);
 
   uint32_t *mhist = reinterpret_cast<uint32_t *>(ws + p.off_mhist);
   uint32_t *mhist2 = mhist + (size_t)MSEL_PASSES * B * MSEL_BINS;
@@ -1522,6 +1523,8 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
     HIP_TRY(hipGetLastError());
   }
 
+  // the caller redoes flagged queries itself: k_surv_finish has left them with cand_count = -1 and an all -1 row
+  if (defer_redo) return MOL_OK;
   // exact redo of flagged queries: 8 histogram scans and the emitting scan; each returns at once when no query is
   // flagged (k_surv_finish has set up the per-query state; the last workgroup of every scan advances it)
   a.state = state;

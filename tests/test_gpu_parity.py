@@ -327,6 +327,39 @@ def test_hindexer_exact_redo_gives_the_exact_topk(dtype, N, B, Kp):
         np.testing.assert_allclose(cs[b], s[b, ci[b]], rtol=0, atol=S1_TOL)
 
 
+@pytest.mark.parametrize("mode_name", ["exact", "paper"])
+def test_hindexer_deferred_redo(mode_name):
+    """MOL_HINDEXER_DEFER_REDO: queries the lists resolve come back exactly as without the flag; queries that would be
+    redone come back with cand_count = -1 and an all -1 row, and submitting them again without the flag completes them."""
+    lib = m()
+    N, B, Kp = 60_000, 24, 512
+    wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, n_clusters=64)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    base = lib.HINDEXER_EXACT if mode_name == "exact" else lib.HINDEXER_PAPER
+    want = lib.hindexer_topk(corpus, q["q1"], Kp, mode=base, seed=5)
+    got = lib.hindexer_topk(corpus, q["q1"], Kp, mode=base | lib.HINDEXER_DEFER_REDO, seed=5)
+    torch.cuda.synchronize()
+    assert int(want[2].min()) >= 0 and torch.equal(want[2], got[2])
+    for b in range(B):  # the candidates are a set in no particular order: compare (index, score) pairs sorted by index
+        n = int(want[2][b])
+        ow, og = torch.argsort(want[0][b, :n]), torch.argsort(got[0][b, :n])
+        assert torch.equal(want[0][b, :n][ow], got[0][b, :n][og]) and torch.equal(want[1][b, :n][ow], got[1][b, :n][og])
+        assert torch.all(got[0][b, n:] == -1)
+    # every query flagged: nothing is redone, every row is handed back
+    ci, cs, cc = lib.hindexer_topk(corpus, q["q1"], Kp, mode=base | lib.HINDEXER_FORCE_REDO | lib.HINDEXER_DEFER_REDO, seed=5)
+    torch.cuda.synchronize()
+    assert torch.all(cc == -1) and torch.all(ci == -1) and torch.all(torch.isneginf(cs))
+    # ... and the same workspace-free call without the flag gives the forced redo's result: the exact top-K' in exact mode
+    ci2, cs2, cc2 = lib.hindexer_topk(corpus, q["q1"], Kp, mode=base | lib.HINDEXER_FORCE_REDO, seed=5)
+    torch.cuda.synchronize()
+    assert torch.equal(cc2, want[2])
+    for b in range(B):
+        n = int(cc2[b])
+        assert set(ci2[b, :n].tolist()) == set(want[0][b, :n].tolist())
+    corpus.free()
+
+
 def test_hindexer_massive_ties_take_the_lowest_indices():
     """Degenerate corpus: every item identical, so every score ties.  The sampled threshold keeps nothing (strict >),
     the redo finds the K'-th key and resolves the tie by index: items 0..K'-1.  With half the corpus replaced by a
