@@ -187,6 +187,9 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *                                     result is the exact stage-1 top-K' under fp32 scores.  cand_count[b] = -1 (row
  *                                     all -1) reports a query that could not be completed; it does not occur for
  *                                     finite scores.
+ *                 | MOL_HINDEXER_DEFER_REDO (either mode): the device redo is not run; a query that needs it is reported
+ *                                     with cand_count[b] = -1 and is to be submitted again without the flag.
+ *                 | MOL_HINDEXER_FORCE_REDO (either mode): every query takes the redo (same result; diagnostics).
  *   cand_idx    : out int32 [B, Kp]; a set, in no particular order; unused slots are -1.
  *   cand_score  : out f32 [B, Kp] stage-1 scores aligned with cand_idx (unused slots -inf), or NULL.
  *   cand_count  : out int32 [B] number of valid slots.
