@@ -255,6 +255,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
   // STAGED: one tile per wavefront, [32 rows][STG_ROW bytes], behind the rings
   char *stg = reinterpret_cast<char *>(lds_hist) + (size_t)4 * 64 * NQG * RING * 8 + (size_t)(threadIdx.x >> 6) * 32 * STG_ROW;
   float thr[NQG];
+  int32_t thr_i[NQG];  // DT = MOL_INT8, FILTER only
   uint32_t st_active[NQG], st_prefix[NQG], st_tkey[NQG], st_ilim[NQG];
   uint32_t cnt[NQG];
   uint2 *lst[NQG];
@@ -275,6 +276,12 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
     }
     thr[g] = (EPI == EPI_FILTER && b < a.B) ? a.thr[b] : INFINITY;
     if constexpr (EPI == EPI_FILTER_EXACT) thr[g] = (a.paper && b < a.B) ? a.thr[b] : -INFINITY;
+    // an int8 table: the filter compares the integer sums themselves (s > t  <=>  s > floor(t) for an integer s), which
+    // saves the 16 conversions per tile and query group of a scan that is bound by instruction issue, not by memory
+    if constexpr (DT == MOL_INT8 && EPI == EPI_FILTER) {
+      const float t = floorf(thr[g]);
+      thr_i[g] = t >= 2147483648.f ? 0x7fffffff : (t < -2147483648.f ? (int32_t)0x80000000 : (int32_t)t);
+    }
     st_active[g] = 0;
     cnt[g] = 0;
     lst[g] = nullptr;
@@ -397,7 +404,8 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
         if (tnext < ntiles) load_tile(tb, tnext);
       }
       mfma_settle();
-      if constexpr (DT == MOL_INT8) {
+      constexpr bool INT_FILTER = DT == MOL_INT8 && EPI == EPI_FILTER;
+      if constexpr (DT == MOL_INT8 && !INT_FILTER) {
 #pragma unroll
         for (int g = 0; g < NQG; ++g)
 #pragma unroll
@@ -413,22 +421,27 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
           // about 1.5 of the 1024 scores of a tile pass: one compare per accumulator, and the (rare) append is a
           // branch the wavefront skips when no lane takes it
           auto append = [&](int j) __attribute__((always_inline)) {
-            ring[g][cnt[g] & (RING - 1)] = make_uint2(f32_to_key(acc[g][j]), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
+            const float sc = INT_FILTER ? (float)iacc[g][j] : acc[g][j];  // |sum| < 2^24: exact
+            ring[g][cnt[g] & (RING - 1)] = make_uint2(f32_to_key(sc), (uint32_t)(row0 + 8 * (j >> 2) + (j & 3)));
             ++cnt[g];
             if ((cnt[g] & (RING - 1)) == 0) flush_ring(g, RING);
+          };
+          auto passes = [&](int gg, int j) -> bool {
+            if constexpr (INT_FILTER) return iacc[gg][j] > thr_i[gg];
+            else return acc[gg][j] > thr[gg];
           };
           if (tile != ntiles - 1) {
             // the wavefront-wide test first: when no lane passes (all but ~2 % of the compares) the cost is the compare
             // and one scalar branch on its mask, with no save / restore of the execution mask
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-              if (__builtin_amdgcn_ballot_w64(acc[g][j] > thr[g]) != 0) [[unlikely]] {
-                if (acc[g][j] > thr[g]) append(j);
+              if (__builtin_amdgcn_ballot_w64(passes(g, j)) != 0) [[unlikely]] {
+                if (passes(g, j)) append(j);
               }
           } else {
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-              if (acc[g][j] > thr[g] && row0 + 8 * (j >> 2) + (j & 3) < a.n_rows) append(j);  // the last tile can be partial
+              if (passes(g, j) && row0 + 8 * (j >> 2) + (j & 3) < a.n_rows) append(j);  // the last tile can be partial
           }
         } else if constexpr (EPI == EPI_FILTER_EXACT) {
           if (st_active[g] == 3u) {
