@@ -111,6 +111,7 @@ struct ScanArgs {
   int Kp;
   uint32_t *gate_rw;        // exact redo: the two gate words and, at [2], the workgroup ticket of the redo scans
   int stage;                // exact redo: step to run when a histogram scan has finished (1..8)
+  uint32_t idx_prefix;      // exact redo: digits of ~idx that are the same for every item (N <= 2^24: the top one is 0xff), not scanned for
   uint32_t *hist;           // exact redo: [B][EXACT_BINS] digit histogram
   const uint32_t *gate;     // exact redo: the kernel returns at once when *gate == 0
   int shift;                // exact redo: bit position of the digit
@@ -148,7 +149,7 @@ __device__ __forceinline__ uint32_t window_top_from_max(uint32_t t_key, uint32_t
 //   stage 5..8 : the same on ~idx among the ties; after the fourth the index limit is known.
 // The histogram row is read past the L1 cache (other workgroups added to it with device-scope atomics) and zeroed for
 // the next scan.
-__device__ inline void exact_step(int stage, ExactState *st, uint32_t *hb, uint32_t *gate, uint32_t *suf) {
+__device__ inline void exact_step(int stage, uint32_t idx_prefix, ExactState *st, uint32_t *hb, uint32_t *gate, uint32_t *suf) {
   const int t = threadIdx.x;
   __syncthreads();  // suf and *st may still be in use by the previous query's step
   const uint32_t want = stage <= 4 ? 1u : 2u;
@@ -179,7 +180,7 @@ __device__ inline void exact_step(int stage, ExactState *st, uint32_t *hb, uint3
         st->idx_limit = 0xffffffffu;
       } else {
         st->active = 2;
-        st->prefix = 0;
+        st->prefix = idx_prefix;
         st->krem = nk;
         gate[1] = 1;
       }
@@ -521,7 +522,7 @@ __global__ __launch_bounds__(256, scan_queries_in_lds(EPI, NQG) ? MOL_SCAN_WAVES
     if (last_workgroup(a.gate_rw + 2)) {
       uint32_t *suf = lds_hist;  // the LDS histogram is flushed: reuse its first EXACT_BINS words
       for (int b = a.qbase; b < a.B && b < a.qbase + 32 * NQG; ++b)
-        exact_step(a.stage, a.state + b, a.hist + (size_t)b * EXACT_BINS, a.gate_rw, suf);
+        exact_step(a.stage, a.idx_prefix, a.state + b, a.hist + (size_t)b * EXACT_BINS, a.gate_rw, suf);
     }
   }
   if constexpr (EPI == EPI_FILTER_EXACT) {
@@ -1548,7 +1549,11 @@ mol_status_t hindexer_run(const mol_corpus *c, const void *q1, int B, int Kp, co
   a.out_score = cand_score;
   a.out_count = cand_count;
   a.Kp = Kp;
+  // ~idx starts with the same 0xff digits for every item of a small corpus: those passes are not launched
+  const int idx_skip = c->N <= (1 << 8) ? 3 : (c->N <= (1 << 16) ? 2 : (c->N <= (1 << 24) ? 1 : 0));
+  a.idx_prefix = idx_skip ? 0xffffffffu << (32 - 8 * idx_skip) : 0u;
   for (int pass = 0; pass < 8; ++pass) {
+    if (pass >= 4 && pass < 4 + idx_skip) continue;
     a.shift = 24 - 8 * (pass & 3);
     a.gate = gate + (pass < 4 ? 0 : 1);
     a.stage = pass + 1;

@@ -360,11 +360,12 @@ def test_hindexer_deferred_redo(mode_name):
     corpus.free()
 
 
-def test_hindexer_massive_ties_take_the_lowest_indices():
+@pytest.mark.parametrize("N", [6000, 70_000])  # two and one leading digits of the index are the same for every item
+def test_hindexer_massive_ties_take_the_lowest_indices(N):
     """Degenerate corpus: every item identical, so every score ties.  The sampled threshold keeps nothing (strict >),
     the redo finds the K'-th key and resolves the tie by index: items 0..K'-1.  With half the corpus replaced by a
     better item, the better half comes first and the rest is filled by index."""
-    N, B, Kp = 6000, 3, 200
+    B, Kp = 3, 200
     wl = synth.CONFIGS["C2"].replace(N=N, B=B, Kp=Kp, n_clusters=4)
     items, q, gw = make(wl)
     items["x1"][:] = items["x1"][0]
