@@ -106,6 +106,33 @@ def test_final_selection_levels_with_ties_and_padding(Kp, k):
     corpus.free()
 
 
+@pytest.mark.parametrize("Kp", [20_000, 60_000])
+def test_final_selection_of_a_row_sorted_by_score(Kp):
+    """Candidate rows in ascending and in descending score order.  The bound taken from the head of an ascending row (or
+    slice) lets everything through, so the collecting pass overflows its buffer and the multi-pass selection takes over;
+    the head of a descending row gives the final bound at once.  Both must return the exact top-k."""
+    k = 100
+    wl = synth.CONFIGS["C2"].replace(N=80_000, B=2, n_clusters=8)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(Kp)
+    pick = torch.randperm(wl.N, generator=g)[:Kp].to(torch.int32)
+    cand = torch.stack([pick, pick]).to(DEV)
+    scores = m().mol_score(corpus, q["F"], q["gu"], cand)
+    order = torch.argsort(scores, dim=1)                       # ascending
+    cand = torch.gather(cand, 1, order.to(torch.int64))
+    cand[1] = torch.flip(cand[1], dims=[0])                    # row 1 descending
+    cand = cand.contiguous()
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], cand, k)
+    scores = m().mol_score(corpus, q["F"], q["gu"], cand).cpu().numpy()
+    idx, sc, ids = idx.cpu().numpy(), sc.cpu().numpy(), cand.cpu().numpy()
+    for b in range(2):
+        want = np.lexsort((ids[b], -scores[b].astype(np.float64)))[:k]
+        assert idx[b].tolist() == ids[b][want].tolist(), f"row {b}"
+        assert np.array_equal(sc[b], scores[b][want])
+    corpus.free()
+
+
 @pytest.mark.parametrize("shape", [dict(k_u=16, k_x=1, d_p=32, H=32, d_gu=32, d_gx=32), dict(k_u=8, k_x=8, d_p=64, H=128, d_gu=128, d_gx=128)])
 def test_gather_items_is_a_bit_exact_row_copy(shape):
     """Index select (Section 4.1.3): rows of 64 B and of 1 KB, with padding and repeated ids."""
