@@ -104,6 +104,36 @@ def test_exhaustive_scores_and_topk_beyond_one_query_chunk(shape, gate, B, every
     corpus.free()
 
 
+@pytest.mark.parametrize("shift", [300.0, -300.0, 0.0])
+def test_exhaustive_softmax_with_gate_logits_outside_the_exponent_range(shift):
+    """Gate logits near +-300: without the maximum subtracted their exponentials would leave the fp32 range (inf, or all
+    zero).  With shift 0 the biases are spread over +-120 instead: the largest exponential is finite, the others
+    underflow against it.  The scores must still be the oracle's."""
+    N, B = 5_003, 40
+    wl = synth.CONFIGS["C5"].replace(N=N, B=B, k=10, n_clusters=16, bias_scale=0.1, **SHAPES["C2"])
+    cen = synth.make_centres(wl, DEV)
+    items = synth.make_items(wl, cen)
+    q = synth.make_queries(wl, cen)
+    gw = synth.make_gate_weights(wl, DEV)
+    b2 = gw.b2.clone()
+    if shift:
+        b2 += shift
+    else:
+        b2 += torch.linspace(-120.0, 120.0, b2.numel(), device=b2.device)
+    corpus = m().mol_corpus_pack(None, items["G"], items["gx"], gw.W1, gw.b1, gw.W2, b2, k_u=wl.k_u,
+                                 logit_scale=wl.logit_scale, act=wl.act)
+    model = orc.MolModel(bits(items["G"]), bits(items["gx"]), bits(gw.W1), bits(gw.b1), bits(gw.W2), bits(b2),
+                         wl.logit_scale, wl.act)
+    got = m().mol_score(corpus, q["F"], q["gu"], None).cpu().numpy()
+    assert np.all(np.isfinite(got))
+    Fb, gub = bits(q["F"]), bits(q["gu"])
+    ids = np.arange(N)
+    for b in (0, 7, B - 1):
+        ref = orc.mol_scores_for(model, orc.as_f64(Fb[b]), orc.as_f64(gub[b]), ids)
+        assert_scores_close(got[b], ref, wl.logit_scale, f"shift {shift} query {b}")
+    corpus.free()
+
+
 @pytest.mark.parametrize("N,B,k", [(40_961, 5, 100), (70_000, 260, 10), (300_000, 3, 1024)])
 def test_exhaustive_topk_two_level_selection_over_implicit_indices(N, B, k):
     """Rows of >= 16384 x 2 entries take the two-level selection; without a candidate list the item index is the
