@@ -172,7 +172,8 @@ int64_t hindexer_default_lambda(const mol_corpus_t *corpus, int Kp);
  *   q1          : [B, d1] of the corpus' stage1_dtype.   1 <= B <= 1024, 1 <= Kp <= N.
  *   sample_idx  : int32 [lambda] explicit sample (each in [0, N)), or NULL: the library then draws
  *                 idx_i = floor(N * hi32(SplitMix64_i(seed)) / 2^32), i = 1..lambda (stream state seed + i*0x9E3779B97F4A7C15).
- *   lambda      : sample size (a count); <= 0 = hindexer_default_lambda().  Ignored when 4*Kp >= N (no sampling: every
+ *   lambda      : sample size (a count); <= 0 = hindexer_default_lambda(); values above N are taken as N (of an
+ *                 explicit sample the first N entries are used).  Ignored when 4*Kp >= N (no sampling: every
  *                 item passes and the exact top-K' is taken).
  *   mode        : MOL_HINDEXER_PAPER  r = max(1, floor(Kp*lambda/N)); more than K' survivors are cut to the K' best,
  *                                     fewer are returned as they are (cand_count[b] < Kp).  A query whose survivors
