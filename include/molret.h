@@ -228,7 +228,8 @@ mol_status_t mol_gather_items(const mol_corpus_t *corpus, const int32_t *cand_id
  *   cand_count: int32 [B] or NULL.  When given (hindexer_topk's output of that name), only the first cand_count[b] slots
  *               of row b are read -- the rest of the row is neither scored nor gathered, whatever it holds; a negative
  *               count reads as 0.  NULL = all Kp slots (negative entries are still padding).  Needs cand_idx.
- *   out_idx   : out int32 [B, k] item indices, best first (score desc, index asc); -1 where fewer than k exist.
+ *   out_idx   : out int32 [B, k] item indices, best first (score desc, index asc); -1 where fewer than k exist.  An
+ *               item that a row names more than once is a candidate as often as it is named (and can be returned so).
  *   out_score : out f32 [B, k] their MoL scores (-inf padding).
  */
 mol_status_t mol_topk(const mol_corpus_t *corpus, const void *user_embs, const void *user_gate, int B,

@@ -50,15 +50,22 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_seg_topk(const float *scores
     if (tid == 0) sh.out_count = 0;
     __syncthreads();
     if (kk > 0) {
-      from([&](uint32_t key, uint32_t idx) {
-        if (select_accept(key, idx, sh)) {
-          const uint32_t slot = atomicAdd(&sh.out_count, 1u);
-          if (slot < kk) {
-            os[slot] = key_to_f32(key);
-            oi[slot] = (int32_t)idx;
-          }
+      auto put = [&](uint32_t key, uint32_t idx) {
+        const uint32_t slot = atomicAdd(&sh.out_count, 1u);
+        if (slot < kk) {
+          os[slot] = key_to_f32(key);
+          oi[slot] = (int32_t)idx;
         }
+      };
+      from([&](uint32_t key, uint32_t idx) {
+        if (select_before_kth(key, idx, sh)) put(key, idx);
       });
+      if (sh.idx_limit != 0xffffffffu) {  // copies of the K-th element itself fill what is left
+        __syncthreads();
+        from([&](uint32_t key, uint32_t idx) {
+          if (select_equals_kth(key, idx, sh)) put(key, idx);
+        });
+      }
     }
     for (uint32_t i = kk + tid; i < (uint32_t)k; i += SELECT_THREADS) {
       os[i] = -INFINITY;
@@ -133,15 +140,22 @@ __global__ __launch_bounds__(SELECT_THREADS) void k_final_topk(const float *scor
   // the accepted entries of `from` (kk of them) go to the sort buffer
   auto take = [&](auto from, uint32_t kk) {
     if (kk > 0) {
-      from([&](uint32_t key, uint32_t idx) {
-        if (select_accept(key, idx, sh)) {
-          uint32_t slot = atomicAdd(&sh.out_count, 1u);
-          if (slot < TOPK_MAX) {
-            skey[slot] = key;
-            sidx[slot] = idx;
-          }
+      auto put = [&](uint32_t key, uint32_t idx) {
+        uint32_t slot = atomicAdd(&sh.out_count, 1u);
+        if (slot < kk) {
+          skey[slot] = key;
+          sidx[slot] = idx;
         }
+      };
+      from([&](uint32_t key, uint32_t idx) {
+        if (select_before_kth(key, idx, sh)) put(key, idx);
       });
+      if (sh.idx_limit != 0xffffffffu) {  // copies of the K-th element itself fill what is left
+        __syncthreads();
+        from([&](uint32_t key, uint32_t idx) {
+          if (select_equals_kth(key, idx, sh)) put(key, idx);
+        });
+      }
     }
   };
   uint32_t kk = 0;

@@ -254,6 +254,13 @@ __device__ uint32_t block_select_kth(Each each, uint32_t K, SelectShared &sh) {
   return K;
 }
 
-__device__ __forceinline__ bool select_accept(uint32_t key, uint32_t idx, const SelectShared &sh) {
-  return key > sh.kth_key || (key == sh.kth_key && idx <= sh.idx_limit);
+// What block_select_kth accepts, in two classes: entries that come before the K-th element in the total order, and
+// entries equal to it in key and index.  A list may name an item more than once (a caller's candidate row), and then
+// more entries may equal the K-th than there is room for: whoever collects the K results takes the first class whole
+// (fewer than K entries when the second is not empty) and fills up from the second.
+__device__ __forceinline__ bool select_before_kth(uint32_t key, uint32_t idx, const SelectShared &sh) {
+  return key > sh.kth_key || (key == sh.kth_key && idx < sh.idx_limit);
+}
+__device__ __forceinline__ bool select_equals_kth(uint32_t key, uint32_t idx, const SelectShared &sh) {
+  return key == sh.kth_key && idx == sh.idx_limit;
 }

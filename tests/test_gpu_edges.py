@@ -106,6 +106,31 @@ def test_final_selection_levels_with_ties_and_padding(Kp, k):
     corpus.free()
 
 
+@pytest.mark.parametrize("Kp,k", [(20_000, 64), (20_000, 100), (30_000, 394), (60_000, 64), (3000, 1024)])
+def test_final_selection_with_items_listed_more_than_once(Kp, k):
+    """Candidate rows drawn with replacement from a small corpus: most items appear several times, so copies of the k-th
+    element itself compete for the last places (in a slice of the two-level form, and in the final selection).  Every
+    entry that comes before the k-th must be returned, and copies of the k-th fill the rest: the result is the first k
+    of the row's entries sorted by (score descending, index ascending), copies included."""
+    wl = synth.CONFIGS["C2"].replace(N=4000, B=5, n_clusters=8)
+    items, q, gw = make(wl)
+    corpus = pack(wl, items, gw)
+    g = torch.Generator().manual_seed(Kp + k)
+    cand = torch.randint(0, wl.N, (wl.B, Kp), generator=g, dtype=torch.int32)
+    cand[1, torch.rand(Kp, generator=g) < 0.5] = -1
+    cand = cand.to(DEV)
+    idx, sc = m().mol_topk(corpus, q["F"], q["gu"], cand, k)
+    scores = m().mol_score(corpus, q["F"], q["gu"], cand).cpu().numpy()
+    idx, sc, ids = idx.cpu().numpy(), sc.cpu().numpy(), cand.cpu().numpy()
+    for b in range(wl.B):
+        valid = ids[b] >= 0
+        ids_v, s_v = ids[b][valid], scores[b][valid]
+        want = np.lexsort((ids_v, -s_v.astype(np.float64)))[:k]
+        assert idx[b].tolist() == ids_v[want].tolist(), f"row {b}"
+        assert np.array_equal(sc[b], s_v[want])
+    corpus.free()
+
+
 @pytest.mark.parametrize("Kp", [20_000, 60_000])
 def test_final_selection_of_a_row_sorted_by_score(Kp):
     """Candidate rows in ascending and in descending score order.  The bound taken from the head of an ascending row (or
